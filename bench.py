@@ -1,0 +1,205 @@
+#!/usr/bin/env python3
+"""Benchmark of the FFT convolution hot path on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of synthetic input
+already resident in HBM: the three forward transforms (x, w, dL/dy), the three
+per-bin contractions and the three inverse transforms + crops, i.e. fprop, bprop
+and accGrad of one layer with every spectrum computed once and reused.
+
+Prints ONE JSON line on stdout.  `value` is direct-equivalent GFLOP/s of the
+step: 3 * 2*S*f*f'*(n-k+1)^2*k^2 divided by the step time (the direct method's
+operation count of the paper's Sec. 2.2 table, times two for multiply+add).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(layer, x, w, g, budget_s=18.0):
+    """Time the fp64 direct-sum oracle on a bounded sample of the same layer."""
+    from oracle import direct
+    from paper_1312_5851_amd import workloads as wl
+    S, f, fo, n, k = layer.S, layer.f, layer.fo, layer.n, layer.k
+    totals = (S * fo, S * f, fo * f)
+    # probe with a few units to size the sample to the budget (a third of it per pass)
+    counts = []
+    t_meas = []
+    fns = (lambda u: direct.fprop(x, w, u), lambda u: direct.bprop(g, w, n, u), lambda u: direct.accgrad(g, x, k, u))
+    xs = [a.astype(np.float64) for a in (x, w, g)]
+    x, w, g = xs
+    for p, (fn, total) in enumerate(zip(fns, totals)):
+        probe = wl.sample_units(total, min(total, 16), layer.seed + 70 + p)
+        t0 = time.perf_counter(); fn(probe); dt = max(time.perf_counter() - t0, 1e-4)
+        cnt = int(max(16, min(total, (budget_s / 3.0) / (dt / len(probe)))))
+        u = wl.sample_units(total, cnt, layer.seed + 80 + p)
+        t0 = time.perf_counter(); fn(u); dt = time.perf_counter() - t0
+        counts.append(len(u)); t_meas.append(dt)
+    # every unit of a pass costs the same, so full-pass time = sample time * total / count
+    full_s = sum(t * tot / c for t, tot, c in zip(t_meas, totals, counts))
+    return {
+        "value": 3 * layer.direct_flops / full_s / 1e9,
+        "unit": "GFLOP/s (direct-equivalent)",
+        "cores": direct.num_threads(),
+        "kind": "oracle",
+        "sample": (f"fp64 direct loops on {counts[0]}/{totals[0]} fprop maps, {counts[1]}/{totals[1]} bprop maps, "
+                   f"{counts[2]}/{totals[2]} accGrad kernels of the same layer ({sum(t_meas):.1f} s), "
+                   f"extrapolated per pass by units total / units run"),
+        "extrapolated_step_s": full_s,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="mid", help="layer name from paper_1312_5851_amd.workloads")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-stage-events", action="store_true", help="do not bracket kernels with HIP events")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (every box has one); --gpus must be 1")
+
+    import torch
+    from paper_1312_5851_amd import fftconv as fc
+    from paper_1312_5851_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    layer = wl.by_name(args.workload)
+    x, w, g = wl.make_inputs(layer)
+    xd, wd, gd = (torch.from_numpy(a).cuda() for a in (x, w, g))
+    plan = fc.Plan(layer.S, layer.f, layer.fo, layer.n, layer.k)
+    plan.alloc_workspace()
+    y = torch.empty(layer.shapes()[2], dtype=torch.float32, device="cuda")
+    dx = torch.empty_like(xd)
+    dw = torch.empty_like(wd)
+
+    def step():
+        plan.invalidate()
+        plan.fprop(xd, wd, y)
+        plan.bprop(gd, wd, dx)
+        plan.accgrad(gd, xd, dw)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    plan.profile_enable(not args.no_stage_events)
+    plan.profile_read()
+    stage_ms = {name: [0.0, 0] for name in fc.STAGE_NAMES}
+
+    def drain():
+        for name, (ms, cnt) in plan.profile_read().items():
+            stage_ms[name][0] += ms
+            stage_ms[name][1] += cnt
+
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step()
+        if (i + 1) % 200 == 0:   # the event pool holds 4096 launches
+            drain()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    drain()
+    plan.profile_enable(False)
+    ms_per_step = elapsed * 1e3 / args.steps
+
+    stages = {name: (ms / cnt if cnt else None) for name, (ms, cnt) in stage_ms.items()}
+
+    # per-pass times, warm (operand spectra cached) and cold (pass includes its forward transforms)
+    def time_pass(fn, slots, iters=20):
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        out = []
+        for cold in (False, True):
+            ts = []
+            for _ in range(iters + 3):
+                if cold:
+                    plan.invalidate(slots)
+                ev0.record(); fn(); ev1.record(); ev1.synchronize()
+                ts.append(ev0.elapsed_time(ev1))
+            out.append(float(np.median(ts[3:])))
+        return {"warm_ms": out[0], "cold_ms": out[1]}
+
+    plan.fprop(xd, wd, y); plan.bprop(gd, wd, dx); plan.accgrad(gd, xd, dw)
+    passes = {
+        "fprop": time_pass(lambda: plan.fprop(xd, wd, y), fc.SPEC_X | fc.SPEC_W),
+        "bprop": time_pass(lambda: plan.bprop(gd, wd, dx), fc.SPEC_G | fc.SPEC_W),
+        "accgrad": time_pass(lambda: plan.accgrad(gd, xd, dw), fc.SPEC_G | fc.SPEC_X),
+    }
+    for v in passes.values():
+        v["warm_direct_equiv_gflops"] = layer.direct_flops / (v["warm_ms"] * 1e-3) / 1e9
+        v["cold_direct_equiv_gflops"] = layer.direct_flops / (v["cold_ms"] * 1e-3) / 1e9
+
+    # roofline of the dominant kernel: the per-bin contraction (three launches per step)
+    gemm_names = ("cgemm_fprop", "cgemm_bprop", "cgemm_accgrad")
+    roofline = None
+    if all(stages[n] for n in gemm_names):
+        gemm_ms = float(np.mean([stages[n] for n in gemm_names]))
+        achieved = plan.contraction_flops / (gemm_ms * 1e-3) / 1e12
+        traffic = None
+        tpath = os.path.join(ROOT, "profiles", f"traffic_{layer.name}.json")
+        if os.path.exists(tpath):
+            traffic = json.load(open(tpath)).get("cgemm_hbm_bytes_per_launch")
+        roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                    "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": traffic,
+                    "kernel": "bin_cgemm_kernel (mean of the fprop/bprop/accGrad launches)",
+                    "avg_launch_ms": gemm_ms, "flops_per_launch": plan.contraction_flops}
+    # HBM-side view of the transform stages: algorithmic bytes = unpadded real map + stored half spectrum
+    B = plan.num_bins
+    ext = {"fft_x": (layer.n, layer.S * layer.f), "fft_w": (layer.k, layer.fo * layer.f),
+           "fft_g": (layer.no, layer.S * layer.fo), "ifft_y": (layer.no, layer.S * layer.fo),
+           "ifft_dx": (layer.n, layer.S * layer.f), "ifft_dw": (layer.k, layer.fo * layer.f)}
+    stage_report = {}
+    for name, ms in stages.items():
+        if ms is None:
+            continue
+        rec = {"avg_ms": ms}
+        if name in ext:
+            e, M = ext[name]
+            nbytes = M * (4 * e * e + 8 * B)
+            rec["algorithmic_bytes"] = nbytes
+            rec["GBps"] = nbytes / (ms * 1e-3) / 1e9
+            rec["frac_hbm_peak"] = rec["GBps"] / PEAK_HBM_GBS
+        else:
+            rec["TFLOPs"] = plan.contraction_flops / (ms * 1e-3) / 1e12
+            rec["frac_mfma_peak"] = rec["TFLOPs"] / PEAK_FP32_MFMA_TFLOPS
+        stage_report[name] = rec
+
+    out = {
+        "metric": "direct-equiv GFLOP/s + ms per fprop/bprop/accGrad, fp32, 1 MI355X",
+        "value": 3 * layer.direct_flops / (ms_per_step * 1e-3) / 1e9,
+        "unit": "GFLOP/s (direct-equivalent, fprop+bprop+accGrad step)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{layer.name}: S={layer.S} f={layer.f} f'={layer.fo} n={layer.n} k={layer.k} "
+                               f"(N={plan.fft_size}, {B} bins); step = FFT(x,w,dL/dy) + 3 contractions + 3 inverse+crop",
+                   "seed": layer.seed},
+        "passes": passes,
+        "stages": stage_report,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        log("timing the CPU oracle on a bounded sample ...")
+        out["cpu_baseline"] = cpu_baseline(layer, x, w, g)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,158 @@
+/*
+ * fftconv -- the three passes of one convolutional layer computed through FFTs
+ * on one MI355X (gfx950), after "Fast Training of Convolutional Networks through
+ * FFTs" (Mathieu, Henaff, LeCun; arXiv 1312.5851).
+ *
+ * Notation (paper Sec. 2.1): S minibatch size, f input maps, fo (= f') output
+ * maps, n x n inputs, k x k kernels, no = n - k + 1 (valid output, stride 1).
+ * "*" is read as the cross-correlation of neural-network layers.
+ *
+ * Every pass follows Sec. 2.2: each 2-D map is Fourier-transformed once (zero
+ * padded to N x N, N = n rounded up to a power of two, Sec. 4), the products are
+ * accumulated per frequency bin over the summed index, and the result is
+ * inverse-transformed and cropped.  The spectra of x, w and dL/dy are kept in a
+ * caller-owned workspace and reused by later passes (the "keep the Fourier
+ * representations in memory" option of Sec. 2.3) until the caller invalidates
+ * them.
+ *
+ * ALL DATA POINTERS ARE DEVICE POINTERS (fp32, contiguous, row-major):
+ *   x [S][f ][n ][n ]     w [fo][f][k][k]
+ *   y [S][fo][no][no]     g = dL/dy like y,  dx like x,  dw like w
+ * The library allocates no device memory and keeps no device pointer beyond a
+ * call, except that the cache-valid bits are tied to the workspace address last
+ * used (a different address invalidates every slot).  `stream` is a hipStream_t
+ * passed as void* (NULL = the default stream).  Calls only enqueue kernels; they
+ * never synchronise with the host.  Return values report argument and launch
+ * errors; on an argument error nothing is launched.
+ *
+ * A plan is not thread-safe; use one plan per host thread / stream.
+ */
+#ifndef FFTCONV_H
+#define FFTCONV_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct fftconv_plan_s *fftconv_plan_t;
+
+typedef struct {
+    int S, f, fo, n, k;
+    unsigned flags; /* must be 0 */
+} fftconv_desc;
+
+enum {
+    FFTCONV_OK = 0,
+    FFTCONV_EINVAL = 1,       /* null pointer, non-positive size, k > n, bad slot/pass */
+    FFTCONV_EUNSUPPORTED = 2, /* n > 64 (no compiled transform size) or flags != 0 */
+    FFTCONV_EWORKSPACE = 3,   /* workspace pointer null or not 256-byte aligned */
+    FFTCONV_ELAUNCH = 4,      /* the HIP runtime refused a launch or an event call */
+    FFTCONV_ENOTREADY = 5     /* a stage-level call needs a spectrum that is not cached */
+};
+
+/* Spectral cache slots (bit flags) and the scratch slot holding a pass's result spectrum. */
+enum { FFTCONV_SPEC_X = 1, FFTCONV_SPEC_W = 2, FFTCONV_SPEC_G = 4, FFTCONV_SPEC_OUT = 8 };
+
+/* Passes: Eq. (1), (2), (3) of Sec. 2.1. */
+enum { FFTCONV_FPROP = 0, FFTCONV_BPROP = 1, FFTCONV_ACCGRAD = 2 };
+
+/* Stages timed by the optional profiler, in hot-path order. */
+enum {
+    FFTCONV_STAGE_FFT_X = 0, FFTCONV_STAGE_FFT_W = 1, FFTCONV_STAGE_FFT_G = 2,
+    FFTCONV_STAGE_CGEMM_FPROP = 3, FFTCONV_STAGE_CGEMM_BPROP = 4, FFTCONV_STAGE_CGEMM_ACCGRAD = 5,
+    FFTCONV_STAGE_IFFT_Y = 6, FFTCONV_STAGE_IFFT_DX = 7, FFTCONV_STAGE_IFFT_DW = 8,
+    FFTCONV_NUM_STAGES = 9
+};
+
+/* ---- plan (host only) -------------------------------------------------- */
+
+/* Validates the layer and fixes N, the bin count and the workspace layout.
+ * Errors: EINVAL for null arguments, sizes < 1 or k > n; EUNSUPPORTED for n > 64
+ * or non-zero flags.  *out is written only on success. */
+int fftconv_plan(fftconv_plan_t *out, const fftconv_desc *d);
+int fftconv_plan_destroy(fftconv_plan_t p);
+
+/* Transform size N (power of two, >= n) and number of stored bins B = (N/2+1)*N:
+ * the half spectrum a real map determines (Sec. 2.3), kept as N/2+1 full rows. */
+int fftconv_fft_size(fftconv_plan_t p);
+int fftconv_num_bins(fftconv_plan_t p);
+
+/* Bytes of device workspace the passes need: the x, w and g spectra (8*B bytes
+ * per map for S*f + fo*f + S*fo maps, the count of Sec. 2.3) plus one result
+ * spectrum of 8*B*max(S*fo, S*f, fo*f) bytes; each slot 256-byte aligned. */
+size_t fftconv_workspace_bytes(fftconv_plan_t p);
+
+/* Layout of one slot inside the workspace: byte offset and number of maps M.
+ * A slot holds spec[b][m] as interleaved (re, im) floats, b = ky*N + kx with
+ * ky in [0, N/2], kx in [0, N); m is the map index in the tensor's own order
+ * (s*f+i for x, j*f+i for w, s*fo+j for g).  FFTCONV_SPEC_OUT holds the spectrum
+ * of the last pass's result, laid out like that result.  Returns (size_t)-1 /
+ * -1 for a bad slot. */
+size_t fftconv_slot_offset(fftconv_plan_t p, int slot);
+long   fftconv_slot_maps(fftconv_plan_t p, int slot);
+
+/* The caller changed the contents of x / w / g: drop their cached spectra
+ * (bitwise OR of FFTCONV_SPEC_X/W/G).  This is the only way the library learns
+ * that a tensor changed. */
+int fftconv_invalidate(fftconv_plan_t p, unsigned slots);
+unsigned fftconv_valid_slots(fftconv_plan_t p);
+
+/* ---- the three passes (Sec. 2.1, computed as in Sec. 2.2) --------------- */
+
+/* Eq. (1): y[s,j] = sum_i x[s,i] * w[j,i].  Transforms x and/or w only if their
+ * slot is invalid, contracts per bin over i, inverse-transforms and stores the
+ * no x no window.  y is overwritten. */
+int fftconv_fprop(fftconv_plan_t p, const float *x, const float *w, float *y, void *ws, void *stream);
+
+/* Eq. (2), summed over j: dx[s,i] = sum_j g[s,j] * w[j,i]^T (adjoint of fprop in x).
+ * Uses the g and w slots; stores the full n x n window.  dx is overwritten. */
+int fftconv_bprop(fftconv_plan_t p, const float *g, const float *w, float *dx, void *ws, void *stream);
+
+/* Eq. (3), summed over the minibatch: dw[j,i] = sum_s g[s,j] * x[s,i] (adjoint of
+ * fprop in w).  Uses the g and x slots; stores the k x k window.  accumulate = 0
+ * overwrites dw, accumulate = 1 adds the gradient to it. */
+int fftconv_accgrad(fftconv_plan_t p, const float *g, const float *x, float *dw, void *ws, void *stream,
+                    int accumulate);
+
+/* ---- single stages (same kernels; for stage tests and per-stage timing) - */
+
+/* Forward transform of one tensor into its slot (slot = FFTCONV_SPEC_X, _W or _G),
+ * unconditionally; marks the slot valid. */
+int fftconv_forward_transform(fftconv_plan_t p, int slot, const float *src, void *ws, void *stream);
+
+/* Per-bin contraction of a pass on cached spectra into the OUT slot.
+ * ENOTREADY if an operand slot is not valid for this workspace. */
+int fftconv_contract(fftconv_plan_t p, int pass, void *ws, void *stream);
+
+/* Inverse transform + crop of the OUT slot into the pass's result tensor. */
+int fftconv_inverse_transform(fftconv_plan_t p, int pass, float *dst, void *ws, void *stream, int accumulate);
+
+/* ---- stage timing ------------------------------------------------------- */
+
+/* When enabled, every kernel launch is bracketed by HIP events on the launch
+ * stream (up to 4096 launches between reads).  fftconv_profile_read waits for
+ * the recorded events, adds each stage's elapsed milliseconds and launch count
+ * into the caller's arrays of FFTCONV_NUM_STAGES entries (host memory), and
+ * clears the record. */
+int fftconv_profile_enable(fftconv_plan_t p, int enable);
+int fftconv_profile_read(fftconv_plan_t p, double *ms_sum, long *launches);
+
+/* ---- helpers ------------------------------------------------------------ */
+
+const char *fftconv_strerror(int status);
+
+/* The paper's closed form for frequency-domain memory, Sec. 2.3:
+ * 4 n (n+1) (S f + S fo + f fo) bytes (it counts n(n+1)/2 complex numbers per
+ * map; the workspace query above counts the (N/2+1)*N actually stored). */
+size_t fftconv_paper_ram_bytes(int S, int n, int f, int fo);
+
+/* Real floating-point operations the contraction of one pass issues:
+ * 8 * S * f * fo * B (four real multiply-adds per complex product per bin). */
+double fftconv_contraction_flops(fftconv_plan_t p);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FFTCONV_H */

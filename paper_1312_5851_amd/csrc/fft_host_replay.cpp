@@ -1,0 +1,66 @@
+// Host replay of the FFT kernels' two phases (no GPU, no HIP): every block and
+// every lane is run in a loop, phase by phase, on an ordinary array standing in
+// for LDS.  Used only by CPU tests to check the kernels' index arithmetic and
+// the transform conventions against a naive DFT; it is not part of the product
+// path and is not linked into the GPU library.
+#include <cstring>
+#include <vector>
+
+#include "fft_dispatch.hpp"
+
+using namespace fftconv;
+
+template <class G>
+static void replay_forward(const FwdArgs &a)
+{
+    std::vector<cf> lds(G::LDS_ELEMS);
+    const int blocks = (a.M + G::T - 1) / G::T;
+    for (int blk = 0; blk < blocks; ++blk) {
+        // poison: a phase-x read of something phase-y did not write shows up as NaN
+        std::memset(lds.data(), 0xFF, sizeof(cf) * lds.size());
+        for (int tid = 0; tid < G::THREADS; ++tid) fwd_phase_y<G>(tid, blk, a, lds.data());
+        for (int tid = 0; tid < G::THREADS; ++tid) fwd_phase_x<G>(tid, blk, a, lds.data());
+    }
+}
+
+template <class G>
+static void replay_inverse(const InvArgs &a)
+{
+    std::vector<cf> lds(G::LDS_ELEMS);
+    const int blocks = (a.M + G::T - 1) / G::T;
+    for (int blk = 0; blk < blocks; ++blk) {
+        std::memset(lds.data(), 0xFF, sizeof(cf) * lds.size());
+        for (int tid = 0; tid < G::THREADS; ++tid) inv_phase_x<G>(tid, blk, a, lds.data());
+        for (int tid = 0; tid < G::THREADS; ++tid) inv_phase_y<G>(tid, blk, a, lds.data());
+    }
+}
+
+extern "C" {
+
+int replay_fft_size(int n) { return fft_size_for(n); }
+int replay_extent_class(int N, int ext) { return extent_class(N, ext); }
+
+// src: [M][ext][ext] floats; spec: [B][M] complex (2 floats each), B = (N/2+1)*N.
+int replay_fft2d_r2c(int N, const float *src, float *spec, int M, int ext)
+{
+    FwdArgs a{src, reinterpret_cast<cf *>(spec), M, ext};
+    const int T = maps_per_block(N), NX = extent_class(N, ext);
+#define X(n_, t_, nx_) \
+    if (N == n_ && T == t_ && NX == nx_) { replay_forward<TileGeom<n_, t_, nx_>>(a); return 0; }
+    FFTCONV_FOR_EACH_GEOM(X)
+#undef X
+    return 1;
+}
+
+int replay_ifft2d_c2r_crop(int N, const float *spec, float *dst, int M, int crop, int accumulate)
+{
+    InvArgs a{reinterpret_cast<const cf *>(spec), dst, M, crop, accumulate, 1.0f / (float)(N * N)};
+    const int T = maps_per_block(N), NX = extent_class(N, crop);
+#define X(n_, t_, nx_) \
+    if (N == n_ && T == t_ && NX == nx_) { replay_inverse<TileGeom<n_, t_, nx_>>(a); return 0; }
+    FFTCONV_FOR_EACH_GEOM(X)
+#undef X
+    return 1;
+}
+
+}  // extern "C"

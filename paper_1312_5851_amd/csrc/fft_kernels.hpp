@@ -1,0 +1,237 @@
+// Batched 2-D real-to-complex FFT of zero-padded maps, and the complex-to-real
+// inverse fused with cropping (paper Sec. 2.2: transform every map once, crop
+// the circular result; Sec. 2.3: a 2-D FFT is two sets of 1-D FFTs).
+//
+// Spectrum layout ("bin-major"): spec[b * M + m] is bin b of map m, complex
+// interleaved, with b = ky * N + kx, ky in [0, N/2], kx in [0, N): the half of
+// the N x N spectrum that a real map determines (Sec. 2.3, symmetry of FFTs of
+// real inputs), kept as N/2+1 full rows.  For a fixed bin the M maps are
+// contiguous, which makes every bin a dense row-major matrix for the
+// per-frequency contraction.
+//
+// One workgroup transforms T consecutive maps so that each bin is written (or
+// read) as one contiguous run of T complex numbers.  The work is two phases
+// separated by a workgroup barrier:
+//
+//   forward  A: lane <-> (map pair, column x).  Two real maps are packed as
+//               one complex column (re = map a, im = map b), transformed along
+//               y in registers, and split back into the two half spectra.
+//            B: lane <-> (row ky, map).  Complex transform along x in
+//               registers, then the bin-major store with lanes along maps.
+//               The purely real rows ky = 0 and ky = N/2 of a map are packed
+//               into one complex row ("row 0") and split after the transform.
+//   inverse  runs the same two phases backwards and stores only the cropped
+//            window, scaled by 1/N^2.
+//
+// Between the phases the data sits in LDS as lds[r][x][m] (m fastest) with
+// strides padded so that both phases touch distinct banks.
+//
+// Each phase is a plain function of (thread id, block id): the device kernels
+// call them around __syncthreads(), and a host build replays them in loops to
+// check the index arithmetic without a GPU.
+#pragma once
+#include "fft_core.hpp"
+
+namespace fftconv {
+
+struct FwdArgs {
+    const float *src;   // [M][ext][ext] real maps
+    cf *spec;           // [B][M] bin-major spectrum
+    int M;              // number of maps
+    int ext;            // spatial extent of a map (n, k or n'); everything beyond is zero padding
+};
+
+struct InvArgs {
+    const cf *spec;     // [B][M]
+    float *dst;         // [M][crop][crop]
+    int M;
+    int crop;           // stored window [0,crop)^2
+    int accumulate;     // 0: dst = result, 1: dst += result
+    float scale;        // 1 / N^2
+};
+
+template <int N_, int T_, int NX_>
+struct TileGeom {
+    static constexpr int N = N_;     // transform size
+    static constexpr int T = T_;     // maps per workgroup (even)
+    static constexpr int NX = NX_;   // columns that can be non-zero (forward) / are needed (inverse)
+    static constexpr int ROWS = N / 2;                 // packed row 0 + rows 1..N/2-1
+    static constexpr int THREADS = T * ROWS;           // one lane per (row, map) in the x-phase
+    static constexpr int SX = T + 1;                   // complex elements between consecutive x
+    static constexpr int SR_BASE = NX * SX;
+    // row stride: congruent to T modulo 32 complex (= 64 dwords) so that the row groups
+    // sharing a half-wave in the x-phase start T complex apart in bank space
+    static constexpr int SR = SR_BASE + ((((T - SR_BASE) % 32) + 32) % 32);
+    static constexpr int LDS_ELEMS = ROWS * SR;
+    static constexpr int LDS_BYTES = LDS_ELEMS * 8;
+    static constexpr int YITEMS = (T / 2) * NX;        // work items of the y-phase
+    static_assert(T % 2 == 0, "maps are processed in pairs");
+    static_assert(NX <= N, "extent class cannot exceed the transform size");
+};
+
+// ------------------------------------------------------------------ forward
+
+template <class G>
+FC_HD void fwd_phase_y(int tid, int blk, const FwdArgs &a, cf *lds)
+{
+    constexpr int N = G::N, NX = G::NX;
+    const int m0 = blk * G::T;
+    for (int item = tid; item < G::YITEMS; item += G::THREADS) {
+        const int p = item / NX, x = item % NX;
+        const int ma = m0 + 2 * p, mb = ma + 1;
+        const bool va = (ma < a.M) && (x < a.ext), vb = (mb < a.M) && (x < a.ext);
+        const float *pa = a.src + ((size_t)ma * a.ext) * a.ext + x;
+        const float *pb = a.src + ((size_t)mb * a.ext) * a.ext + x;
+        cf z[N];
+        static_for<0, NX>([&](auto yi) {
+            constexpr int y = decltype(yi)::value;
+            const float fa = (va && y < a.ext) ? pa[y * a.ext] : 0.0f;
+            const float fb = (vb && y < a.ext) ? pb[y * a.ext] : 0.0f;
+            z[y] = mk(fa, fb);
+        });
+        fft_dif<N, false, ~low_mask(NX)>(z);
+        cf *base = lds + x * G::SX + 2 * p;
+        {   // packed row 0: (ky = 0, ky = N/2), both real for a real map
+            const cf z0 = z[brev<N>(0)], zh = z[brev<N>(N / 2)];
+            base[0] = mk(z0.x, zh.x);
+            base[1] = mk(z0.y, zh.y);
+        }
+        static_for<1, N / 2>([&](auto ri) {
+            constexpr int r = decltype(ri)::value;
+            const cf zk = z[brev<N>(r)], zn = z[brev<N>(N - r)];
+            // A = (Z[k] + conj Z[N-k]) / 2,  B = (Z[k] - conj Z[N-k]) / (2i)
+            base[r * G::SR + 0] = mk(0.5f * (zk.x + zn.x), 0.5f * (zk.y - zn.y));
+            base[r * G::SR + 1] = mk(0.5f * (zk.y + zn.y), 0.5f * (zn.x - zk.x));
+        });
+    }
+}
+
+template <class G>
+FC_HD void fwd_phase_x(int tid, int blk, const FwdArgs &a, const cf *lds)
+{
+    constexpr int N = G::N, NX = G::NX;
+    const int r = tid / G::T, m = tid % G::T;
+    const int mg = blk * G::T + m;
+    cf v[N];
+    const cf *base = lds + r * G::SR + m;
+    static_for<0, NX>([&](auto xi) {
+        constexpr int x = decltype(xi)::value;
+        v[x] = base[x * G::SX];
+    });
+    fft_dif<N, false, ~low_mask(NX)>(v);
+    if (mg >= a.M) return;
+    cf *out = a.spec + mg;
+    const size_t M = (size_t)a.M;
+    if (r != 0) {
+        static_for<0, N>([&](auto ki) {
+            constexpr int kx = decltype(ki)::value;
+            out[((size_t)r * N + kx) * M] = v[brev<N>(kx)];
+        });
+    } else {
+        // C = FFT(row0 + i rowH)  ->  row0[k] = (C[k] + conj C[-k]) / 2,  rowH[k] = (C[k] - conj C[-k]) / (2i)
+        static_for<0, N>([&](auto ki) {
+            constexpr int kx = decltype(ki)::value;
+            const cf c = v[brev<N>(kx)], d = v[brev<N>((N - kx) % N)];
+            out[(size_t)kx * M] = mk(0.5f * (c.x + d.x), 0.5f * (c.y - d.y));
+            out[((size_t)(N / 2) * N + kx) * M] = mk(0.5f * (c.y + d.y), 0.5f * (d.x - c.x));
+        });
+    }
+}
+
+// ------------------------------------------------------------------ inverse
+
+template <class G>
+FC_HD void inv_phase_x(int tid, int blk, const InvArgs &a, cf *lds)
+{
+    constexpr int N = G::N, NX = G::NX;
+    const int r = tid / G::T, m = tid % G::T;
+    const int mg = blk * G::T + m;
+    const bool valid = mg < a.M;
+    const cf *in = a.spec + (valid ? mg : 0);
+    const size_t M = (size_t)a.M;
+    cf v[N];
+    if (r != 0) {
+        static_for<0, N>([&](auto ki) {
+            constexpr int kx = decltype(ki)::value;
+            v[kx] = valid ? in[((size_t)r * N + kx) * M] : mk(0.0f, 0.0f);
+        });
+    } else {
+        // rows ky = 0 and ky = N/2 are Hermitian in kx, so their inverse transforms are
+        // real: send both through one complex transform as row0 + i rowH
+        static_for<0, N>([&](auto ki) {
+            constexpr int kx = decltype(ki)::value;
+            const cf y0 = valid ? in[(size_t)kx * M] : mk(0.0f, 0.0f);
+            const cf yh = valid ? in[((size_t)(N / 2) * N + kx) * M] : mk(0.0f, 0.0f);
+            v[kx] = mk(y0.x - yh.y, y0.y + yh.x);
+        });
+    }
+    fft_dif<N, true, 0, first_outputs_mask<N>(NX)>(v);
+    cf *base = lds + r * G::SR + m;
+    static_for<0, NX>([&](auto xi) {
+        constexpr int x = decltype(xi)::value;
+        base[x * G::SX] = v[brev<N>(x)];
+    });
+}
+
+template <class G>
+FC_HD void inv_phase_y(int tid, int blk, const InvArgs &a, const cf *lds)
+{
+    constexpr int N = G::N, NX = G::NX;
+    const int m0 = blk * G::T;
+    for (int item = tid; item < G::YITEMS; item += G::THREADS) {
+        const int p = item / NX, x = item % NX;
+        const int ma = m0 + 2 * p, mb = ma + 1;
+        const cf *base = lds + x * G::SX + 2 * p;
+        cf z[N];
+        {
+            const cf ra = base[0], rb = base[1];    // (row 0, row N/2) of map a / map b, all real
+            z[0] = mk(ra.x, rb.x);
+            z[N / 2] = mk(ra.y, rb.y);
+        }
+        static_for<1, N / 2>([&](auto ri) {
+            constexpr int r = decltype(ri)::value;
+            const cf A = base[r * G::SR + 0], B = base[r * G::SR + 1];
+            z[r] = mk(A.x - B.y, A.y + B.x);        // A + i B
+            z[N - r] = mk(A.x + B.y, B.x - A.y);    // conj A + i conj B
+        });
+        fft_dif<N, true, 0, first_outputs_mask<N>(NX)>(z);
+        if (x >= a.crop) continue;
+        const bool va = ma < a.M, vb = mb < a.M;
+        float *pa = a.dst + ((size_t)ma * a.crop) * a.crop + x;
+        float *pb = a.dst + ((size_t)mb * a.crop) * a.crop + x;
+        static_for<0, NX>([&](auto yi) {
+            constexpr int y = decltype(yi)::value;
+            if (y < a.crop) {
+                const cf o = z[brev<N>(y)];
+                if (va) pa[y * a.crop] = (a.accumulate ? pa[y * a.crop] : 0.0f) + o.x * a.scale;
+                if (vb) pb[y * a.crop] = (a.accumulate ? pb[y * a.crop] : 0.0f) + o.y * a.scale;
+            }
+        });
+    }
+}
+
+#if defined(__HIPCC__)
+// Device kernels: the two phases around one workgroup barrier.  Launch with
+// G::THREADS threads, ceil(M / G::T) blocks and G::LDS_BYTES of dynamic LDS.
+template <class G>
+__global__ __launch_bounds__(G::THREADS) void fft2d_r2c_kernel(FwdArgs a)
+{
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    cf *lds = reinterpret_cast<cf *>(lds_raw);
+    fwd_phase_y<G>((int)threadIdx.x, (int)blockIdx.x, a, lds);
+    __syncthreads();
+    fwd_phase_x<G>((int)threadIdx.x, (int)blockIdx.x, a, lds);
+}
+
+template <class G>
+__global__ __launch_bounds__(G::THREADS) void ifft2d_c2r_crop_kernel(InvArgs a)
+{
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    cf *lds = reinterpret_cast<cf *>(lds_raw);
+    inv_phase_x<G>((int)threadIdx.x, (int)blockIdx.x, a, lds);
+    __syncthreads();
+    inv_phase_y<G>((int)threadIdx.x, (int)blockIdx.x, a, lds);
+}
+#endif
+
+}  // namespace fftconv

@@ -1,0 +1,451 @@
+// C-ABI entry points of the fftconv library (declared in include/fftconv.h):
+// plan bookkeeping, the spectral cache, kernel selection and launches.
+// Host code only enqueues work on the caller's stream; all arithmetic of the
+// path runs in the kernels of fft_kernels.hpp and contract_kernels.hpp.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/fftconv.h"
+#include "contract_kernels.hpp"
+#include "fft_dispatch.hpp"
+
+using namespace fftconv;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+constexpr int kMaxProfileRecords = 4096;
+constexpr int kNumCUs = 256;
+
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct ProfileRecord {
+    int stage;
+    hipEvent_t start, stop;
+};
+
+// ------------------------------------------------------------------ kernel tables
+
+typedef void (*FwdKernel)(FwdArgs);
+typedef void (*InvKernel)(InvArgs);
+typedef void (*GemmKernel)(GemmArgs);
+
+struct FftEntry {
+    int N, T, NX, threads, lds_bytes;
+    FwdKernel fwd;
+    InvKernel inv;
+};
+
+#define X(n_, t_, nx_)                                                                          \
+    {n_, t_, nx_, TileGeom<n_, t_, nx_>::THREADS, TileGeom<n_, t_, nx_>::LDS_BYTES,              \
+     fft2d_r2c_kernel<TileGeom<n_, t_, nx_>>, ifft2d_c2r_crop_kernel<TileGeom<n_, t_, nx_>>},
+const FftEntry kFftTable[] = {FFTCONV_FOR_EACH_GEOM(X)};
+#undef X
+
+const FftEntry *find_fft(int N, int ext)
+{
+    const int T = maps_per_block(N), NX = extent_class(N, ext);
+    for (const FftEntry &e : kFftTable)
+        if (e.N == N && e.T == T && e.NX == NX) return &e;
+    return nullptr;
+}
+
+struct GemmEntry {
+    int MT, NT, threads, lds_bytes;
+    GemmKernel pass[3];   // indexed by FFTCONV_FPROP / BPROP / ACCGRAD
+};
+
+// Layout / conjugation per pass (see contract_kernels.hpp):
+//   fprop   A = Xh [S][f]  K contiguous,  B = Wh [fo][f] K contiguous, conj B
+//   bprop   A = Gh [S][fo] K contiguous,  B = Wh [fo][f] K outer
+//   accGrad A = Gh [S][fo] K outer, conj A,  B = Xh [S][f] K outer
+#define GEMM_ENTRY(mt, nt, wm, wn)                                                         \
+    {mt, nt, GemmTile<mt, nt, wm, wn>::THREADS, GemmTile<mt, nt, wm, wn>::LDS_BYTES,         \
+     {bin_cgemm_kernel<GemmTile<mt, nt, wm, wn>, true, true, false, true>,                   \
+      bin_cgemm_kernel<GemmTile<mt, nt, wm, wn>, true, false, false, false>,                 \
+      bin_cgemm_kernel<GemmTile<mt, nt, wm, wn>, false, false, true, false>}}
+const GemmEntry kGemmTable[] = {
+    GEMM_ENTRY(128, 128, 2, 2), GEMM_ENTRY(64, 128, 2, 2), GEMM_ENTRY(128, 64, 2, 2),
+    GEMM_ENTRY(64, 64, 2, 2),   GEMM_ENTRY(128, 96, 4, 1), GEMM_ENTRY(64, 96, 2, 1),
+    GEMM_ENTRY(32, 32, 1, 1),
+};
+#undef GEMM_ENTRY
+constexpr int kNumGemm = sizeof(kGemmTable) / sizeof(kGemmTable[0]);
+
+// Estimated relative time of a tile shape: the busiest CU's share of the padded
+// MFMA work, with a mild penalty for small tiles (more operand traffic per flop).
+int choose_gemm_tile(int Md, int Nd, int bins)
+{
+    if (const char *env = std::getenv("FFTCONV_GEMM_TILE")) {
+        const int v = std::atoi(env);
+        if (v >= 0 && v < kNumGemm) return v;
+    }
+    int best = 0;
+    double best_cost = 1e300;
+    for (int i = 0; i < kNumGemm; ++i) {
+        const GemmEntry &e = kGemmTable[i];
+        const long tiles = (long)((Md + e.MT - 1) / e.MT) * ((Nd + e.NT - 1) / e.NT) * bins;
+        const long per_cu = (tiles + kNumCUs - 1) / kNumCUs;
+        const double traffic_penalty = 1.0 + 8.0 * (1.0 / e.MT + 1.0 / e.NT);
+        const double cost = (double)per_cu * e.MT * e.NT * traffic_penalty;
+        if (cost < best_cost) { best_cost = cost; best = i; }
+    }
+    return best;
+}
+
+}  // namespace
+
+struct fftconv_plan_s {
+    fftconv_desc d;
+    int no, N, B;
+    long maps_x, maps_w, maps_g, maps_out;
+    size_t off_x, off_w, off_g, off_out, ws_bytes;
+    unsigned valid;
+    void *last_ws;
+    int gemm_tile[3];
+    bool profiling;
+    std::vector<ProfileRecord> records;
+    std::vector<hipEvent_t> free_events;
+};
+
+namespace {
+
+struct StageTimer {
+    fftconv_plan_t p;
+    hipStream_t stream;
+    hipEvent_t stop;
+    bool active;
+    int status;
+    StageTimer(fftconv_plan_t p_, int stage, hipStream_t s) : p(p_), stream(s), stop(nullptr), active(false), status(FFTCONV_OK)
+    {
+        if (!p->profiling || (int)p->records.size() >= kMaxProfileRecords) return;
+        hipEvent_t ev[2];
+        for (int i = 0; i < 2; ++i) {
+            if (!p->free_events.empty()) {
+                ev[i] = p->free_events.back();
+                p->free_events.pop_back();
+            } else if (hipEventCreate(&ev[i]) != hipSuccess) {
+                status = FFTCONV_ELAUNCH;
+                return;
+            }
+        }
+        if (hipEventRecord(ev[0], stream) != hipSuccess) { status = FFTCONV_ELAUNCH; return; }
+        p->records.push_back({stage, ev[0], ev[1]});
+        stop = ev[1];
+        active = true;
+    }
+    int finish()
+    {
+        if (active && hipEventRecord(stop, stream) != hipSuccess) return FFTCONV_ELAUNCH;
+        return status;
+    }
+};
+
+int check_launch() { return hipGetLastError() == hipSuccess ? FFTCONV_OK : FFTCONV_ELAUNCH; }
+
+template <class K>
+int allow_lds(K kernel, int bytes)
+{
+    if (bytes <= 64 * 1024) return FFTCONV_OK;
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               bytes) == hipSuccess
+               ? FFTCONV_OK
+               : FFTCONV_ELAUNCH;
+}
+
+int bind_workspace(fftconv_plan_t p, void *ws)
+{
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0) return FFTCONV_EWORKSPACE;
+    if (ws != p->last_ws) {
+        p->valid = 0;
+        p->last_ws = ws;
+    }
+    return FFTCONV_OK;
+}
+
+cf *slot_ptr(fftconv_plan_t p, void *ws, int slot)
+{
+    size_t off = 0;
+    switch (slot) {
+        case FFTCONV_SPEC_X: off = p->off_x; break;
+        case FFTCONV_SPEC_W: off = p->off_w; break;
+        case FFTCONV_SPEC_G: off = p->off_g; break;
+        default: off = p->off_out; break;
+    }
+    return reinterpret_cast<cf *>(static_cast<unsigned char *>(ws) + off);
+}
+
+int launch_forward(fftconv_plan_t p, int slot, const float *src, void *ws, hipStream_t stream)
+{
+    long M;
+    int ext, stage;
+    switch (slot) {
+        case FFTCONV_SPEC_X: M = p->maps_x; ext = p->d.n; stage = FFTCONV_STAGE_FFT_X; break;
+        case FFTCONV_SPEC_W: M = p->maps_w; ext = p->d.k; stage = FFTCONV_STAGE_FFT_W; break;
+        case FFTCONV_SPEC_G: M = p->maps_g; ext = p->no; stage = FFTCONV_STAGE_FFT_G; break;
+        default: return FFTCONV_EINVAL;
+    }
+    const FftEntry *e = find_fft(p->N, ext);
+    if (!e) return FFTCONV_EUNSUPPORTED;
+    if (int rc = allow_lds(e->fwd, e->lds_bytes)) return rc;
+    FwdArgs a{src, slot_ptr(p, ws, slot), (int)M, ext};
+    const unsigned blocks = (unsigned)((M + e->T - 1) / e->T);
+    StageTimer timer(p, stage, stream);
+    hipLaunchKernelGGL(e->fwd, dim3(blocks), dim3(e->threads), e->lds_bytes, stream, a);
+    if (int rc = check_launch()) return rc;
+    if (int rc = timer.finish()) return rc;
+    p->valid |= (unsigned)slot;
+    return FFTCONV_OK;
+}
+
+void pass_dims(fftconv_plan_t p, int pass, int &Md, int &Nd, int &Kd, int &slot_a, int &slot_b)
+{
+    switch (pass) {
+        case FFTCONV_FPROP: Md = p->d.S; Nd = p->d.fo; Kd = p->d.f; slot_a = FFTCONV_SPEC_X; slot_b = FFTCONV_SPEC_W; break;
+        case FFTCONV_BPROP: Md = p->d.S; Nd = p->d.f; Kd = p->d.fo; slot_a = FFTCONV_SPEC_G; slot_b = FFTCONV_SPEC_W; break;
+        default:            Md = p->d.fo; Nd = p->d.f; Kd = p->d.S; slot_a = FFTCONV_SPEC_G; slot_b = FFTCONV_SPEC_X; break;
+    }
+}
+
+int launch_contract(fftconv_plan_t p, int pass, void *ws, hipStream_t stream)
+{
+    int Md, Nd, Kd, sa, sb;
+    pass_dims(p, pass, Md, Nd, Kd, sa, sb);
+    if ((p->valid & (unsigned)sa) == 0 || (p->valid & (unsigned)sb) == 0) return FFTCONV_ENOTREADY;
+    const GemmEntry &e = kGemmTable[p->gemm_tile[pass]];
+    GemmArgs g;
+    g.A = slot_ptr(p, ws, sa);
+    g.B = slot_ptr(p, ws, sb);
+    g.C = slot_ptr(p, ws, FFTCONV_SPEC_OUT);
+    g.Md = Md; g.Nd = Nd; g.Kd = Kd;
+    g.bins = p->B;
+    g.tiles_m = (Md + e.MT - 1) / e.MT;
+    g.tiles_n = (Nd + e.NT - 1) / e.NT;
+    const long blocks = (long)g.bins * g.tiles_m * g.tiles_n;
+    if (blocks <= 0 || blocks > 0x7fffffffL) return FFTCONV_EUNSUPPORTED;
+    if (int rc = allow_lds(e.pass[pass], e.lds_bytes)) return rc;
+    StageTimer timer(p, FFTCONV_STAGE_CGEMM_FPROP + pass, stream);
+    hipLaunchKernelGGL(e.pass[pass], dim3((unsigned)blocks), dim3(e.threads), e.lds_bytes, stream, g);
+    if (int rc = check_launch()) return rc;
+    return timer.finish();
+}
+
+int launch_inverse(fftconv_plan_t p, int pass, float *dst, void *ws, hipStream_t stream, int accumulate)
+{
+    long M;
+    int crop;
+    switch (pass) {
+        case FFTCONV_FPROP: M = p->maps_g; crop = p->no; break;
+        case FFTCONV_BPROP: M = p->maps_x; crop = p->d.n; break;
+        default:            M = p->maps_w; crop = p->d.k; break;
+    }
+    const FftEntry *e = find_fft(p->N, crop);
+    if (!e) return FFTCONV_EUNSUPPORTED;
+    if (int rc = allow_lds(e->inv, e->lds_bytes)) return rc;
+    InvArgs a{slot_ptr(p, ws, FFTCONV_SPEC_OUT), dst, (int)M, crop, accumulate ? 1 : 0,
+              1.0f / ((float)p->N * (float)p->N)};
+    const unsigned blocks = (unsigned)((M + e->T - 1) / e->T);
+    StageTimer timer(p, FFTCONV_STAGE_IFFT_Y + pass, stream);
+    hipLaunchKernelGGL(e->inv, dim3(blocks), dim3(e->threads), e->lds_bytes, stream, a);
+    if (int rc = check_launch()) return rc;
+    return timer.finish();
+}
+
+int run_pass(fftconv_plan_t p, int pass, const float *src_a, const float *src_b, float *dst, void *ws, void *stream,
+             int accumulate)
+{
+    if (!p || !src_a || !src_b || !dst) return FFTCONV_EINVAL;
+    if (int rc = bind_workspace(p, ws)) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int Md, Nd, Kd, sa, sb;
+    pass_dims(p, pass, Md, Nd, Kd, sa, sb);
+    if ((p->valid & (unsigned)sa) == 0)
+        if (int rc = launch_forward(p, sa, src_a, ws, s)) return rc;
+    if ((p->valid & (unsigned)sb) == 0)
+        if (int rc = launch_forward(p, sb, src_b, ws, s)) return rc;
+    if (int rc = launch_contract(p, pass, ws, s)) return rc;
+    return launch_inverse(p, pass, dst, ws, s, accumulate);
+}
+
+}  // namespace
+
+extern "C" {
+
+int fftconv_plan(fftconv_plan_t *out, const fftconv_desc *d)
+{
+    if (!out || !d) return FFTCONV_EINVAL;
+    if (d->S < 1 || d->f < 1 || d->fo < 1 || d->n < 1 || d->k < 1 || d->k > d->n) return FFTCONV_EINVAL;
+    if (d->flags != 0 || d->n > 64) return FFTCONV_EUNSUPPORTED;
+    const long maps_x = (long)d->S * d->f, maps_w = (long)d->fo * d->f, maps_g = (long)d->S * d->fo;
+    if (maps_x > 0x7fffffffL || maps_w > 0x7fffffffL || maps_g > 0x7fffffffL) return FFTCONV_EUNSUPPORTED;
+    fftconv_plan_s *p = new (std::nothrow) fftconv_plan_s();
+    if (!p) return FFTCONV_EINVAL;
+    p->d = *d;
+    p->no = d->n - d->k + 1;
+    p->N = fft_size_for(d->n);
+    p->B = (p->N / 2 + 1) * p->N;
+    p->maps_x = maps_x;
+    p->maps_w = maps_w;
+    p->maps_g = maps_g;
+    p->maps_out = maps_x > maps_w ? (maps_x > maps_g ? maps_x : maps_g) : (maps_w > maps_g ? maps_w : maps_g);
+    const size_t per_map = (size_t)8 * p->B;
+    p->off_x = 0;
+    p->off_w = p->off_x + align_up(per_map * maps_x);
+    p->off_g = p->off_w + align_up(per_map * maps_w);
+    p->off_out = p->off_g + align_up(per_map * maps_g);
+    p->ws_bytes = p->off_out + align_up(per_map * p->maps_out);
+    p->valid = 0;
+    p->last_ws = nullptr;
+    p->profiling = false;
+    for (int pass = 0; pass < 3; ++pass) {
+        int Md, Nd, Kd, sa, sb;
+        pass_dims(p, pass, Md, Nd, Kd, sa, sb);
+        p->gemm_tile[pass] = choose_gemm_tile(Md, Nd, p->B);
+    }
+    *out = p;
+    return FFTCONV_OK;
+}
+
+int fftconv_plan_destroy(fftconv_plan_t p)
+{
+    if (!p) return FFTCONV_EINVAL;
+    for (ProfileRecord &r : p->records) {
+        hipEventDestroy(r.start);
+        hipEventDestroy(r.stop);
+    }
+    for (hipEvent_t e : p->free_events) hipEventDestroy(e);
+    delete p;
+    return FFTCONV_OK;
+}
+
+int fftconv_fft_size(fftconv_plan_t p) { return p ? p->N : -1; }
+int fftconv_num_bins(fftconv_plan_t p) { return p ? p->B : -1; }
+size_t fftconv_workspace_bytes(fftconv_plan_t p) { return p ? p->ws_bytes : 0; }
+
+size_t fftconv_slot_offset(fftconv_plan_t p, int slot)
+{
+    if (!p) return (size_t)-1;
+    switch (slot) {
+        case FFTCONV_SPEC_X: return p->off_x;
+        case FFTCONV_SPEC_W: return p->off_w;
+        case FFTCONV_SPEC_G: return p->off_g;
+        case FFTCONV_SPEC_OUT: return p->off_out;
+        default: return (size_t)-1;
+    }
+}
+
+long fftconv_slot_maps(fftconv_plan_t p, int slot)
+{
+    if (!p) return -1;
+    switch (slot) {
+        case FFTCONV_SPEC_X: return p->maps_x;
+        case FFTCONV_SPEC_W: return p->maps_w;
+        case FFTCONV_SPEC_G: return p->maps_g;
+        case FFTCONV_SPEC_OUT: return p->maps_out;
+        default: return -1;
+    }
+}
+
+int fftconv_invalidate(fftconv_plan_t p, unsigned slots)
+{
+    if (!p || (slots & ~(unsigned)(FFTCONV_SPEC_X | FFTCONV_SPEC_W | FFTCONV_SPEC_G)) != 0) return FFTCONV_EINVAL;
+    p->valid &= ~slots;
+    return FFTCONV_OK;
+}
+
+unsigned fftconv_valid_slots(fftconv_plan_t p) { return p ? p->valid : 0; }
+
+int fftconv_fprop(fftconv_plan_t p, const float *x, const float *w, float *y, void *ws, void *stream)
+{
+    return run_pass(p, FFTCONV_FPROP, x, w, y, ws, stream, 0);
+}
+
+int fftconv_bprop(fftconv_plan_t p, const float *g, const float *w, float *dx, void *ws, void *stream)
+{
+    return run_pass(p, FFTCONV_BPROP, g, w, dx, ws, stream, 0);
+}
+
+int fftconv_accgrad(fftconv_plan_t p, const float *g, const float *x, float *dw, void *ws, void *stream, int accumulate)
+{
+    return run_pass(p, FFTCONV_ACCGRAD, g, x, dw, ws, stream, accumulate);
+}
+
+int fftconv_forward_transform(fftconv_plan_t p, int slot, const float *src, void *ws, void *stream)
+{
+    if (!p || !src) return FFTCONV_EINVAL;
+    if (slot != FFTCONV_SPEC_X && slot != FFTCONV_SPEC_W && slot != FFTCONV_SPEC_G) return FFTCONV_EINVAL;
+    if (int rc = bind_workspace(p, ws)) return rc;
+    return launch_forward(p, slot, src, ws, static_cast<hipStream_t>(stream));
+}
+
+int fftconv_contract(fftconv_plan_t p, int pass, void *ws, void *stream)
+{
+    if (!p || pass < 0 || pass > 2) return FFTCONV_EINVAL;
+    if (int rc = bind_workspace(p, ws)) return rc;
+    return launch_contract(p, pass, ws, static_cast<hipStream_t>(stream));
+}
+
+int fftconv_inverse_transform(fftconv_plan_t p, int pass, float *dst, void *ws, void *stream, int accumulate)
+{
+    if (!p || !dst || pass < 0 || pass > 2) return FFTCONV_EINVAL;
+    if (int rc = bind_workspace(p, ws)) return rc;
+    return launch_inverse(p, pass, dst, ws, static_cast<hipStream_t>(stream), accumulate);
+}
+
+int fftconv_profile_enable(fftconv_plan_t p, int enable)
+{
+    if (!p) return FFTCONV_EINVAL;
+    p->profiling = enable != 0;
+    return FFTCONV_OK;
+}
+
+int fftconv_profile_read(fftconv_plan_t p, double *ms_sum, long *launches)
+{
+    if (!p || !ms_sum || !launches) return FFTCONV_EINVAL;
+    int status = FFTCONV_OK;
+    for (ProfileRecord &r : p->records) {
+        float ms = 0.0f;
+        if (hipEventSynchronize(r.stop) != hipSuccess || hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess) {
+            status = FFTCONV_ELAUNCH;
+        } else if (r.stage >= 0 && r.stage < FFTCONV_NUM_STAGES) {
+            ms_sum[r.stage] += (double)ms;
+            launches[r.stage] += 1;
+        }
+        p->free_events.push_back(r.start);
+        p->free_events.push_back(r.stop);
+    }
+    p->records.clear();
+    return status;
+}
+
+const char *fftconv_strerror(int status)
+{
+    switch (status) {
+        case FFTCONV_OK: return "ok";
+        case FFTCONV_EINVAL: return "invalid argument";
+        case FFTCONV_EUNSUPPORTED: return "unsupported layer (n > 64 or non-zero flags)";
+        case FFTCONV_EWORKSPACE: return "workspace pointer null or not 256-byte aligned";
+        case FFTCONV_ELAUNCH: return "HIP launch or event call failed";
+        case FFTCONV_ENOTREADY: return "operand spectrum not cached for this workspace";
+        default: return "unknown status";
+    }
+}
+
+size_t fftconv_paper_ram_bytes(int S, int n, int f, int fo)
+{
+    if (S < 1 || n < 1 || f < 1 || fo < 1) return 0;
+    return (size_t)4 * n * (n + 1) * ((size_t)S * f + (size_t)S * fo + (size_t)f * fo);
+}
+
+double fftconv_contraction_flops(fftconv_plan_t p)
+{
+    if (!p) return 0.0;
+    return 8.0 * p->d.S * p->d.f * p->d.fo * p->B;
+}
+
+}  // extern "C"

@@ -1,0 +1,199 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 direct-sum oracle.
+
+Tolerance (per output tensor, fp32 arithmetic on the GPU, fp64 oracle):
+    max |gpu - oracle| <= 1e-4 * max |oracle|   and   ||gpu - oracle||_2 <= 1e-5 * ||oracle||_2
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import direct
+from paper_1312_5851_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS_REL = 1e-4
+REL_L2 = 1e-5
+
+
+@pytest.fixture(scope="module")
+def fc(fftconv_lib_path):
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU")
+    from paper_1312_5851_amd import fftconv
+    return fftconv
+
+
+def check(gpu, ref, what):
+    gpu = np.asarray(gpu, dtype=np.float64)
+    assert gpu.shape == ref.shape, what
+    assert np.all(np.isfinite(gpu)), f"{what}: non-finite values"
+    diff = gpu - ref
+    scale = np.abs(ref).max()
+    l2 = np.linalg.norm(ref.ravel())
+    max_abs = np.abs(diff).max()
+    rel_l2 = np.linalg.norm(diff.ravel()) / l2 if l2 > 0 else np.linalg.norm(diff.ravel())
+    print(f"{what}: max_abs/scale={max_abs / max(scale, 1e-300):.3e} rel_l2={rel_l2:.3e}", flush=True)
+    assert max_abs <= MAX_ABS_REL * scale + 1e-30, f"{what}: max-abs {max_abs:.3e} vs scale {scale:.3e}"
+    assert rel_l2 <= REL_L2, f"{what}: rel L2 {rel_l2:.3e}"
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def run_three(fc, layer, x, w, g):
+    plan = fc.Plan(layer.S, layer.f, layer.fo, layer.n, layer.k)
+    xd, wd, gd = dev(x), dev(w), dev(g)
+    y = plan.fprop(xd, wd)
+    dx = plan.bprop(gd, wd)
+    dw = plan.accgrad(gd, xd)
+    torch.cuda.synchronize()
+    assert plan.valid_slots() == fc.SPEC_X | fc.SPEC_W | fc.SPEC_G
+    return plan, y.cpu().numpy(), dx.cpu().numpy(), dw.cpu().numpy()
+
+
+SMALL_LAYERS = [
+    wl.TINY,
+    wl.Layer("ragged16", 3, 5, 7, 13, 4, 0.1, 11),      # N=16, odd map counts, ragged tiles
+    wl.Layer("k1", 2, 3, 4, 16, 1, 0.1, 12),            # k = 1
+    wl.Layer("k_eq_n", 2, 3, 2, 8, 8, 0.1, 13),         # k = n, single output pixel, N=8
+    wl.Layer("n9", 2, 2, 3, 9, 3, 0.1, 14),             # n just above a power of two -> N=16
+    wl.Layer("ragged32", 5, 7, 9, 29, 6, 0.05, 15),     # N=32, nothing a multiple of anything
+    wl.Layer("n32k13", 4, 6, 5, 32, 13, 0.05, 16),
+    wl.Layer("ragged64", 3, 3, 5, 50, 11, 0.05, 17),    # N=64
+    wl.Layer("n64full", 2, 2, 2, 64, 3, 0.05, 18),
+    wl.Layer("single", 1, 1, 1, 16, 3, 0.1, 19),
+    wl.Layer("wide", 9, 40, 70, 16, 3, 0.05, 20),       # several GEMM tiles with tails
+    wl.Layer("tall", 150, 33, 17, 12, 5, 0.05, 21),     # M tail beyond one 128 tile
+]
+
+
+@pytest.mark.parametrize("layer", SMALL_LAYERS, ids=lambda l: l.name)
+def test_full_parity_small(fc, layer):
+    print(f"\ncase {layer}", flush=True)
+    x, w, g = wl.make_inputs(layer)
+    plan, y, dx, dw = run_three(fc, layer, x, w, g)
+    check(y, direct.fprop(x, w), f"{layer.name} fprop")
+    check(dx, direct.bprop(g, w, layer.n), f"{layer.name} bprop")
+    check(dw, direct.accgrad(g, x, layer.k), f"{layer.name} accgrad")
+
+
+@pytest.mark.parametrize("name", ["mid", "first", "deep"])
+def test_sampled_parity_full_size(fc, name):
+    """BASELINE layer shapes at full size in the launch configuration bench.py times;
+    the oracle evaluates a seeded sample of whole output maps / kernels."""
+    layer = wl.CONFIGS[name]
+    print(f"\ncase {layer}", flush=True)
+    x, w, g = wl.make_inputs(layer)
+    plan, y, dx, dw = run_three(fc, layer, x, w, g)
+    S, f, fo, n, k, no = layer.S, layer.f, layer.fo, layer.n, layer.k, layer.no
+    per = {"mid": (384, 192, 256), "first": (192, 128, 288), "deep": (512, 256, 512)}[name]
+    u = wl.sample_units(S * fo, per[0], layer.seed)
+    check(y.reshape(S * fo, no, no)[u], direct.fprop(x, w, u), f"{name} fprop sample")
+    u = wl.sample_units(S * f, per[1], layer.seed + 1)
+    check(dx.reshape(S * f, n, n)[u], direct.bprop(g, w, n, u), f"{name} bprop sample")
+    u = wl.sample_units(fo * f, per[2], layer.seed + 2)
+    check(dw.reshape(fo * f, k, k)[u], direct.accgrad(g, x, k, u), f"{name} accgrad sample")
+    # properties that hold at any size: adjoint identity on the full tensors (fp64 dot products)
+    a = np.vdot(y.astype(np.float64), g.astype(np.float64))
+    b = np.vdot(x.astype(np.float64), dx.astype(np.float64))
+    c = np.vdot(w.astype(np.float64), dw.astype(np.float64))
+    print(f"adjoint: {a:.9e} {b:.9e} {c:.9e}", flush=True)
+    scale = np.linalg.norm(y.astype(np.float64)) * np.linalg.norm(g.astype(np.float64))
+    assert abs(a - b) <= 1e-5 * scale and abs(a - c) <= 1e-5 * scale
+
+
+def test_spectrum_stage_against_fft2(fc):
+    """Forward stage alone: slot contents equal the half spectrum of the zero-padded maps."""
+    layer = wl.Layer("stage", 3, 5, 4, 20, 6, 0.1, 31)
+    x, w, g = wl.make_inputs(layer)
+    plan = fc.Plan(layer.S, layer.f, layer.fo, layer.n, layer.k)
+    N = plan.fft_size
+    assert N == 32 and plan.num_bins == (N // 2 + 1) * N
+    for slot, arr in ((fc.SPEC_X, x), (fc.SPEC_W, w), (fc.SPEC_G, g)):
+        plan.forward_transform(slot, dev(arr))
+        torch.cuda.synchronize()
+        spec = plan.slot_view(slot).cpu().numpy().astype(np.float64)
+        spec = spec[..., 0] + 1j * spec[..., 1]
+        maps = arr.reshape(-1, arr.shape[-2], arr.shape[-1]).astype(np.float64)
+        pad = np.zeros((maps.shape[0], N, N))
+        pad[:, :maps.shape[1], :maps.shape[2]] = maps
+        ref = np.fft.fft2(pad)[:, :N // 2 + 1, :].reshape(maps.shape[0], -1).T
+        err = np.abs(spec - ref).max() / np.abs(ref).max()
+        print(f"slot {slot}: rel max err {err:.3e}", flush=True)
+        assert err < 2e-6
+    # impulse -> flat spectrum; constant -> only the DC bin
+    imp = np.zeros_like(x); imp[:, :, 0, 0] = 1.0
+    plan.forward_transform(fc.SPEC_X, dev(imp)); torch.cuda.synchronize()
+    s = plan.slot_view(fc.SPEC_X).cpu().numpy()
+    assert np.array_equal(s[..., 0], np.ones_like(s[..., 0])) and np.all(s[..., 1] == 0)
+    # constant map filling the whole transform -> only the DC bin (needs n == N)
+    plan16 = fc.Plan(2, 3, 2, 16, 3)
+    plan16.forward_transform(fc.SPEC_X, torch.ones((2, 3, 16, 16), device="cuda")); torch.cuda.synchronize()
+    s = plan16.slot_view(fc.SPEC_X).cpu().numpy()
+    assert np.array_equal(s[0, :, 0], np.full(6, 256.0, np.float32)) and np.abs(s[1:]).max() < 1e-4
+    # Hermitian symmetry inside the stored rows ky = 0 and ky = N/2, and Parseval on one map
+    plan.forward_transform(fc.SPEC_X, dev(x)); torch.cuda.synchronize()
+    s = plan.slot_view(fc.SPEC_X).cpu().numpy().astype(np.float64)
+    z = (s[..., 0] + 1j * s[..., 1]).reshape(N // 2 + 1, N, -1)
+    for ky in (0, N // 2):
+        assert np.array_equal(z[ky, 1:], np.conj(z[ky, :0:-1]))
+    full = np.abs(z[1:N // 2]) ** 2
+    energy = (np.abs(z[0]) ** 2).sum(0) + (np.abs(z[N // 2]) ** 2).sum(0) + 2 * full.sum((0, 1))
+    np.testing.assert_allclose(energy / (N * N), (x.astype(np.float64) ** 2).reshape(-1, layer.n ** 2).sum(1), rtol=1e-5)
+
+
+def test_cache_bits_invalidate_and_accumulate(fc):
+    layer = wl.Layer("cache", 4, 6, 5, 16, 3, 0.1, 41)
+    x, w, g = wl.make_inputs(layer)
+    plan = fc.Plan(layer.S, layer.f, layer.fo, layer.n, layer.k)
+    xd, wd, gd = dev(x), dev(w), dev(g)
+    assert plan.valid_slots() == 0
+    y1 = plan.fprop(xd, wd)
+    assert plan.valid_slots() == fc.SPEC_X | fc.SPEC_W
+    # a changed tensor is ignored until invalidated: the cache is explicit
+    x2 = (x * 2).astype(np.float32)
+    y_stale = plan.fprop(dev(x2), wd)
+    assert torch.equal(y_stale, y1)
+    plan.invalidate(fc.SPEC_X)
+    assert plan.valid_slots() == fc.SPEC_W
+    y2 = plan.fprop(dev(x2), wd)
+    check(y2.cpu().numpy(), direct.fprop(x2, w), "after invalidate")
+    # stage-level contract refuses a missing operand
+    plan.invalidate(fc.SPEC_X | fc.SPEC_W | fc.SPEC_G)
+    with pytest.raises(fc.FftconvError) as ei:
+        plan.contract(fc.FPROP)
+    assert ei.value.status == 5
+    # accumulate adds the gradient to dw
+    dw = plan.accgrad(gd, xd)
+    ref = direct.accgrad(g, x, layer.k)
+    check(dw.cpu().numpy(), ref, "accgrad overwrite")
+    dw2 = plan.accgrad(gd, xd, dw=dw.clone(), accumulate=True)
+    check(dw2.cpu().numpy(), 2 * ref, "accgrad accumulate")
+    # a different workspace address drops every slot
+    plan.alloc_workspace()
+    plan.fprop(xd, wd)
+    assert plan.valid_slots() == fc.SPEC_X | fc.SPEC_W
+
+
+def test_bitwise_reproducible(fc):
+    layer = wl.Layer("repro", 8, 24, 40, 16, 5, 0.05, 51)
+    x, w, g = wl.make_inputs(layer)
+    a = run_three(fc, layer, x, w, g)[1:]
+    b = run_three(fc, layer, x, w, g)[1:]
+    for u, v in zip(a, b):
+        assert np.array_equal(u, v)
+
+
+def test_argument_errors_launch_nothing(fc):
+    plan = fc.Plan(2, 2, 2, 16, 3)
+    t = torch.zeros(4, device="cuda")
+    with pytest.raises(ValueError):
+        plan.fprop(t.double(), t, t)
+    import ctypes
+    rc = fc._lib.fftconv_fprop(plan._h, None, None, None, None, None)
+    assert rc == 1
+    rc = fc._lib.fftconv_fprop(plan._h, ctypes.c_void_p(t.data_ptr()), ctypes.c_void_p(t.data_ptr()),
+                               ctypes.c_void_p(t.data_ptr()), ctypes.c_void_p(t.data_ptr() + 4), None)
+    assert rc == 3
