@@ -69,8 +69,10 @@ struct TileLoader {
             coords(tid, p, r, kk);
             const int gr = r0 + r, gk = k0 + kk;
             const bool ok = (p * THREADS + tid < ELEMS) && gr < rmax && gk < kmax;
-            cf v = mk(0.0f, 0.0f);
-            if (ok) v = KIN ? base[(size_t)gr * ld + gk] : base[(size_t)gk * ld + gr];
+            // unconditional load from a clamped (valid) address, masked afterwards: no branch per load
+            const int grc = gr < rmax ? gr : rmax - 1, gkc = gk < kmax ? gk : kmax - 1;
+            cf v = KIN ? base[(size_t)grc * ld + gkc] : base[(size_t)gkc * ld + grc];
+            if (!ok) v = mk(0.0f, 0.0f);
             if (CONJ) v.y = -v.y;
             regs[p] = v;
         }

@@ -24,14 +24,17 @@ static void replay_forward(const FwdArgs &a)
 }
 
 template <class G>
-static void replay_inverse(const InvArgs &a)
+static void replay_inverse(const InvArgs &a, bool acc)
 {
     std::vector<cf> lds(G::LDS_ELEMS);
     const int blocks = (a.M + G::T - 1) / G::T;
     for (int blk = 0; blk < blocks; ++blk) {
         std::memset(lds.data(), 0xFF, sizeof(cf) * lds.size());
         for (int tid = 0; tid < G::THREADS; ++tid) inv_phase_x<G>(tid, blk, a, lds.data());
-        for (int tid = 0; tid < G::THREADS; ++tid) inv_phase_y<G>(tid, blk, a, lds.data());
+        for (int tid = 0; tid < G::THREADS; ++tid) {
+            if (acc) inv_phase_y<G, true>(tid, blk, a, lds.data());
+            else inv_phase_y<G, false>(tid, blk, a, lds.data());
+        }
     }
 }
 
@@ -54,10 +57,10 @@ int replay_fft2d_r2c(int N, const float *src, float *spec, int M, int ext)
 
 int replay_ifft2d_c2r_crop(int N, const float *spec, float *dst, int M, int crop, int accumulate)
 {
-    InvArgs a{reinterpret_cast<const cf *>(spec), dst, M, crop, accumulate, 1.0f / (float)(N * N)};
+    InvArgs a{reinterpret_cast<const cf *>(spec), dst, M, crop, 1.0f / (float)(N * N)};
     const int T = maps_per_block(N), NX = extent_class(N, crop);
 #define X(n_, t_, nx_) \
-    if (N == n_ && T == t_ && NX == nx_) { replay_inverse<TileGeom<n_, t_, nx_>>(a); return 0; }
+    if (N == n_ && T == t_ && NX == nx_) { replay_inverse<TileGeom<n_, t_, nx_>>(a, accumulate != 0); return 0; }
     FFTCONV_FOR_EACH_GEOM(X)
 #undef X
     return 1;

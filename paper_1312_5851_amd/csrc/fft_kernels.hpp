@@ -46,7 +46,6 @@ struct InvArgs {
     float *dst;         // [M][crop][crop]
     int M;
     int crop;           // stored window [0,crop)^2
-    int accumulate;     // 0: dst = result, 1: dst += result
     float scale;        // 1 / N^2
 };
 
@@ -79,15 +78,29 @@ FC_HD void fwd_phase_y(int tid, int blk, const FwdArgs &a, cf *lds)
     for (int item = tid; item < G::YITEMS; item += G::THREADS) {
         const int p = item / NX, x = item % NX;
         const int ma = m0 + 2 * p, mb = ma + 1;
+        // Loads are unconditional from clamped (always valid) addresses and masked
+        // afterwards, so that they issue back to back; rows beyond the extent are
+        // skipped by a wave-uniform branch.
         const bool va = (ma < a.M) && (x < a.ext), vb = (mb < a.M) && (x < a.ext);
-        const float *pa = a.src + ((size_t)ma * a.ext) * a.ext + x;
-        const float *pb = a.src + ((size_t)mb * a.ext) * a.ext + x;
+        const int xc = x < a.ext ? x : a.ext - 1;
+        const int mac = ma < a.M ? ma : a.M - 1, mbc = mb < a.M ? mb : a.M - 1;
+        const float *pa = a.src + ((size_t)mac * a.ext) * a.ext + xc;
+        const float *pb = a.src + ((size_t)mbc * a.ext) * a.ext + xc;
+        float fa[NX], fb[NX];
+        static_for<0, NX>([&](auto yi) {
+            constexpr int y = decltype(yi)::value;
+            if (y < a.ext) {
+                fa[y] = pa[y * a.ext];
+                fb[y] = pb[y * a.ext];
+            } else {
+                fa[y] = 0.0f;
+                fb[y] = 0.0f;
+            }
+        });
         cf z[N];
         static_for<0, NX>([&](auto yi) {
             constexpr int y = decltype(yi)::value;
-            const float fa = (va && y < a.ext) ? pa[y * a.ext] : 0.0f;
-            const float fb = (vb && y < a.ext) ? pb[y * a.ext] : 0.0f;
-            z[y] = mk(fa, fb);
+            z[y] = mk(va ? fa[y] : 0.0f, vb ? fb[y] : 0.0f);
         });
         fft_dif<N, false, ~low_mask(NX)>(z);
         cf *base = lds + x * G::SX + 2 * p;
@@ -146,23 +159,28 @@ FC_HD void inv_phase_x(int tid, int blk, const InvArgs &a, cf *lds)
     constexpr int N = G::N, NX = G::NX;
     const int r = tid / G::T, m = tid % G::T;
     const int mg = blk * G::T + m;
-    const bool valid = mg < a.M;
-    const cf *in = a.spec + (valid ? mg : 0);
+    // Lanes beyond the last map read the last map's bins (valid memory) instead of
+    // branching around each load; what they compute is never stored.
+    const cf *in = a.spec + (mg < a.M ? mg : a.M - 1);
     const size_t M = (size_t)a.M;
     cf v[N];
     if (r != 0) {
         static_for<0, N>([&](auto ki) {
             constexpr int kx = decltype(ki)::value;
-            v[kx] = valid ? in[((size_t)r * N + kx) * M] : mk(0.0f, 0.0f);
+            v[kx] = in[((size_t)r * N + kx) * M];
         });
     } else {
         // rows ky = 0 and ky = N/2 are Hermitian in kx, so their inverse transforms are
         // real: send both through one complex transform as row0 + i rowH
+        cf y0[N], yh[N];
         static_for<0, N>([&](auto ki) {
             constexpr int kx = decltype(ki)::value;
-            const cf y0 = valid ? in[(size_t)kx * M] : mk(0.0f, 0.0f);
-            const cf yh = valid ? in[((size_t)(N / 2) * N + kx) * M] : mk(0.0f, 0.0f);
-            v[kx] = mk(y0.x - yh.y, y0.y + yh.x);
+            y0[kx] = in[(size_t)kx * M];
+            yh[kx] = in[((size_t)(N / 2) * N + kx) * M];
+        });
+        static_for<0, N>([&](auto ki) {
+            constexpr int kx = decltype(ki)::value;
+            v[kx] = mk(y0[kx].x - yh[kx].y, y0[kx].y + yh[kx].x);
         });
     }
     fft_dif<N, true, 0, first_outputs_mask<N>(NX)>(v);
@@ -173,7 +191,29 @@ FC_HD void inv_phase_x(int tid, int blk, const InvArgs &a, cf *lds)
     });
 }
 
-template <class G>
+// Stores one cropped output column (rows y < crop of one map at one x), scaled;
+// with ACC the old values are all loaded first, then added, then stored.
+template <class G, bool ACC, class Get>
+FC_HD void store_column(float *col, bool valid, const InvArgs &a, Get &&get)
+{
+    if (!valid) return;
+    float old[G::NX];
+    if constexpr (ACC) {
+        static_for<0, G::NX>([&](auto yi) {
+            constexpr int y = decltype(yi)::value;
+            old[y] = (y < a.crop) ? col[y * a.crop] : 0.0f;
+        });
+    }
+    static_for<0, G::NX>([&](auto yi) {
+        constexpr int y = decltype(yi)::value;
+        if (y < a.crop) {
+            if constexpr (ACC) col[y * a.crop] = old[y] + get(yi) * a.scale;
+            else col[y * a.crop] = get(yi) * a.scale;
+        }
+    });
+}
+
+template <class G, bool ACC>
 FC_HD void inv_phase_y(int tid, int blk, const InvArgs &a, const cf *lds)
 {
     constexpr int N = G::N, NX = G::NX;
@@ -196,16 +236,11 @@ FC_HD void inv_phase_y(int tid, int blk, const InvArgs &a, const cf *lds)
         });
         fft_dif<N, true, 0, first_outputs_mask<N>(NX)>(z);
         if (x >= a.crop) continue;
-        const bool va = ma < a.M, vb = mb < a.M;
-        float *pa = a.dst + ((size_t)ma * a.crop) * a.crop + x;
-        float *pb = a.dst + ((size_t)mb * a.crop) * a.crop + x;
-        static_for<0, NX>([&](auto yi) {
-            constexpr int y = decltype(yi)::value;
-            if (y < a.crop) {
-                const cf o = z[brev<N>(y)];
-                if (va) pa[y * a.crop] = (a.accumulate ? pa[y * a.crop] : 0.0f) + o.x * a.scale;
-                if (vb) pb[y * a.crop] = (a.accumulate ? pb[y * a.crop] : 0.0f) + o.y * a.scale;
-            }
+        store_column<G, ACC>(a.dst + ((size_t)ma * a.crop) * a.crop + x, ma < a.M, a, [&](auto yi) {
+            return z[brev<N>(decltype(yi)::value)].x;
+        });
+        store_column<G, ACC>(a.dst + ((size_t)mb * a.crop) * a.crop + x, mb < a.M, a, [&](auto yi) {
+            return z[brev<N>(decltype(yi)::value)].y;
         });
     }
 }
@@ -223,14 +258,14 @@ __global__ __launch_bounds__(G::THREADS) void fft2d_r2c_kernel(FwdArgs a)
     fwd_phase_x<G>((int)threadIdx.x, (int)blockIdx.x, a, lds);
 }
 
-template <class G>
+template <class G, bool ACC>   // ACC: dst += result instead of dst = result
 __global__ __launch_bounds__(G::THREADS) void ifft2d_c2r_crop_kernel(InvArgs a)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     cf *lds = reinterpret_cast<cf *>(lds_raw);
     inv_phase_x<G>((int)threadIdx.x, (int)blockIdx.x, a, lds);
     __syncthreads();
-    inv_phase_y<G>((int)threadIdx.x, (int)blockIdx.x, a, lds);
+    inv_phase_y<G, ACC>((int)threadIdx.x, (int)blockIdx.x, a, lds);
 }
 #endif
 

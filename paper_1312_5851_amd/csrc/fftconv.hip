@@ -38,12 +38,13 @@ typedef void (*GemmKernel)(GemmArgs);
 struct FftEntry {
     int N, T, NX, threads, lds_bytes;
     FwdKernel fwd;
-    InvKernel inv;
+    InvKernel inv, inv_acc;
 };
 
 #define X(n_, t_, nx_)                                                                          \
     {n_, t_, nx_, TileGeom<n_, t_, nx_>::THREADS, TileGeom<n_, t_, nx_>::LDS_BYTES,              \
-     fft2d_r2c_kernel<TileGeom<n_, t_, nx_>>, ifft2d_c2r_crop_kernel<TileGeom<n_, t_, nx_>>},
+     fft2d_r2c_kernel<TileGeom<n_, t_, nx_>>, ifft2d_c2r_crop_kernel<TileGeom<n_, t_, nx_>, false>,   \
+     ifft2d_c2r_crop_kernel<TileGeom<n_, t_, nx_>, true>},
 const FftEntry kFftTable[] = {FFTCONV_FOR_EACH_GEOM(X)};
 #undef X
 
@@ -246,12 +247,12 @@ int launch_inverse(fftconv_plan_t p, int pass, float *dst, void *ws, hipStream_t
     }
     const FftEntry *e = find_fft(p->N, crop);
     if (!e) return FFTCONV_EUNSUPPORTED;
-    if (int rc = allow_lds(e->inv, e->lds_bytes)) return rc;
-    InvArgs a{slot_ptr(p, ws, FFTCONV_SPEC_OUT), dst, (int)M, crop, accumulate ? 1 : 0,
-              1.0f / ((float)p->N * (float)p->N)};
+    InvKernel kernel = accumulate ? e->inv_acc : e->inv;
+    if (int rc = allow_lds(kernel, e->lds_bytes)) return rc;
+    InvArgs a{slot_ptr(p, ws, FFTCONV_SPEC_OUT), dst, (int)M, crop, 1.0f / ((float)p->N * (float)p->N)};
     const unsigned blocks = (unsigned)((M + e->T - 1) / e->T);
     StageTimer timer(p, FFTCONV_STAGE_IFFT_Y + pass, stream);
-    hipLaunchKernelGGL(e->inv, dim3(blocks), dim3(e->threads), e->lds_bytes, stream, a);
+    hipLaunchKernelGGL(kernel, dim3(blocks), dim3(e->threads), e->lds_bytes, stream, a);
     if (int rc = check_launch()) return rc;
     return timer.finish();
 }

@@ -1,0 +1,136 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what include/fftconv.h declares,
+and its host logic (validation, workspace layout, closed forms) is right.  No kernel runs here."""
+import ctypes
+import json
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+@pytest.fixture(scope="module")
+def fc(fftconv_lib_path):
+    from paper_1312_5851_amd import fftconv
+    return fftconv
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "fftconv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fftconv_[a-z_]+)\s*\(", text)))
+
+
+def test_header_and_binding_agree_and_every_symbol_is_exported(fc, fftconv_lib_path):
+    names = declared_functions()
+    assert len(names) >= 18
+    assert sorted(fc.EXPORTS) == names
+    lib = ctypes.CDLL(fftconv_lib_path)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_signatures_carry_no_torch_types():
+    text = open(os.path.join(ROOT, "include", "fftconv.h")).read()
+    assert "torch" not in text.lower() and "at::" not in text and "hipStream_t stream" not in text
+
+
+@pytest.mark.parametrize("n,N", [(1, 8), (8, 8), (9, 16), (16, 16), (17, 32), (32, 32), (33, 64), (34, 64), (64, 64)])
+def test_fft_size_is_next_power_of_two(fc, n, N):
+    # Sec. 4: sizes that are not a power of two are padded to the next one (34 -> 64)
+    p = fc.Plan(2, 3, 4, n, 1)
+    assert p.fft_size == N and p.num_bins == (N // 2 + 1) * N
+
+
+def test_workspace_layout(fc):
+    p = fc.Plan(128, 96, 256, 32, 5)
+    B = p.num_bins
+    maps = {fc.SPEC_X: 128 * 96, fc.SPEC_W: 256 * 96, fc.SPEC_G: 128 * 256, fc.SPEC_OUT: 128 * 256}
+    off = 0
+    for slot in (fc.SPEC_X, fc.SPEC_W, fc.SPEC_G, fc.SPEC_OUT):
+        assert p.slot_maps(slot) == maps[slot]
+        assert p.slot_offset(slot) == off and off % 256 == 0
+        off += (8 * B * maps[slot] + 255) // 256 * 256
+    assert p.workspace_bytes == off
+    # the three cached spectra are the S f + S f' + f f' frequency representations of Sec. 2.3
+    assert p.slot_offset(fc.SPEC_OUT) == 8 * B * (128 * 96 + 128 * 256 + 96 * 256)
+    assert p.slot_maps(3) == -1
+    assert p.contraction_flops == 8.0 * 128 * 96 * 256 * B
+
+
+@pytest.mark.parametrize("args,status", [
+    ((0, 1, 1, 8, 3), 1), ((1, 0, 1, 8, 3), 1), ((1, 1, 0, 8, 3), 1), ((1, 1, 1, 0, 1), 1),
+    ((1, 1, 1, 8, 0), 1), ((1, 1, 1, 8, 9), 1), ((1, 1, 1, 65, 3), 2), ((1, 1, 1, 128, 3), 2),
+])
+def test_plan_rejects_bad_layers(fc, args, status):
+    with pytest.raises(fc.FftconvError) as ei:
+        fc.Plan(*args)
+    assert ei.value.status == status
+
+
+def test_plan_rejects_flags_and_nulls(fc):
+    with pytest.raises(fc.FftconvError) as ei:
+        fc.Plan(1, 1, 1, 8, 3, flags=1)
+    assert ei.value.status == 2
+    assert fc._lib.fftconv_plan(None, None) == 1
+    assert fc._lib.fftconv_plan_destroy(None) == 1
+    assert fc._lib.fftconv_fft_size(None) == -1
+
+
+def test_invalidate_bookkeeping_and_null_pointer_errors(fc):
+    p = fc.Plan(2, 2, 2, 16, 3)
+    assert p.valid_slots() == 0
+    p.invalidate(fc.SPEC_X | fc.SPEC_G)
+    with pytest.raises(fc.FftconvError):
+        p.invalidate(fc.SPEC_OUT)
+    lib = fc._lib
+    one = ctypes.c_void_p(256)
+    assert lib.fftconv_fprop(p._h, None, one, one, one, None) == 1
+    assert lib.fftconv_bprop(p._h, one, one, None, one, None) == 1
+    assert lib.fftconv_accgrad(p._h, one, one, one, None, None, 0) == 3       # null workspace
+    assert lib.fftconv_accgrad(p._h, one, one, one, ctypes.c_void_p(260), None, 0) == 3  # misaligned
+    assert lib.fftconv_forward_transform(p._h, 3, one, one, None) == 1
+    assert lib.fftconv_contract(p._h, 7, one, None) == 1
+    assert lib.fftconv_contract(p._h, 0, one, None) == 5                      # nothing cached: launches nothing
+    assert lib.fftconv_inverse_transform(p._h, 0, None, one, None, 0) == 1
+    for s in range(6):
+        assert fc.strerror(s) and fc.strerror(s) != "unknown status"
+    assert fc.strerror(99) == "unknown status"
+
+
+def test_paper_ram_closed_form_and_table(fc):
+    gold = json.load(open(os.path.join(GOLD, "paper_ram_table.json")))
+    for row in gold["rows"]:
+        b = fc.paper_ram_bytes(row["S_formula"], row["n"], row["f"], row["fo"])
+        assert b == 4 * row["n"] * (row["n"] + 1) * (row["S_formula"] * row["f"] + row["S_formula"] * row["fo"] + row["f"] * row["fo"])
+        assert abs(b / 1e6 - row["MB"]) < 1.0, row
+    # rows printed with S=128 that only match at S=64 do NOT match at the printed value
+    for row in gold["rows"]:
+        if row["S_printed"] != row["S_formula"]:
+            b = fc.paper_ram_bytes(row["S_printed"], row["n"], row["f"], row["fo"])
+            assert abs(b / 1e6 - row["MB"]) > 10
+    assert fc.paper_ram_bytes(0, 1, 1, 1) == 0
+
+
+def test_stored_bins_exceed_paper_count_only_by_the_extra_half_rows(fc):
+    # paper counts n(n+1)/2 complex per map; N/2+1 full rows store N(N/2+1): N/2 more
+    for n in (16, 32, 64):
+        p = fc.Plan(1, 1, 1, n, 3)
+        assert p.num_bins - n * (n + 1) // 2 == n // 2
+
+
+def test_workloads_are_seeded_and_shaped():
+    from paper_1312_5851_amd import workloads as wl
+    x, w, g = wl.make_inputs(wl.TINY)
+    x2, w2, g2 = wl.make_inputs(wl.TINY)
+    assert np.array_equal(x, x2) and np.array_equal(w, w2) and np.array_equal(g, g2)
+    assert x.dtype == np.float32 and x.shape == (4, 8, 16, 16) and w.shape == (8, 8, 5, 5) and g.shape == (4, 8, 12, 12)
+    assert np.abs(x).max() <= 1 and abs(w.std() - 0.05) < 0.01 and abs(g.std() - 1) < 0.1
+    assert wl.MID.direct_flops == 2 * 128 * 96 * 256 * 28 * 28 * 25
+    assert len(wl.sweep_layers()) == 18 and len(wl.paper_table_layers()) == 5
+    assert wl.by_name("sweep_n32_k7").k == 7
+    u = wl.sample_units(100, 10, 3)
+    assert len(set(u.tolist())) == 10 and np.array_equal(u, wl.sample_units(100, 10, 3))

@@ -1,0 +1,93 @@
+"""CPU replay of the FFT kernels' two phases (same source as the device kernels, run
+lane by lane on the host) against a naive O(N^4) fp64 DFT and numpy's fft2.
+
+This checks the transform conventions, the pair packing, the row-0 packing, the LDS
+indexing and the zero-padding / cropping pruning of every compiled tile geometry
+without a GPU.  It is a test of the HIP path's index arithmetic, not the oracle."""
+import ctypes
+
+import numpy as np
+import pytest
+
+
+@pytest.fixture(scope="module")
+def replay():
+    from paper_1312_5851_amd import build
+    lib = ctypes.CDLL(build.build_host_replay())
+    return lib
+
+
+FP = ctypes.POINTER(ctypes.c_float)
+
+
+def forward(lib, src, N):
+    M, ext, _ = src.shape
+    B = (N // 2 + 1) * N
+    spec = np.full((B, M, 2), np.nan, np.float32)
+    assert lib.replay_fft2d_r2c(N, src.ctypes.data_as(FP), spec.ctypes.data_as(FP), M, ext) == 0
+    return spec[..., 0].astype(np.float64) + 1j * spec[..., 1]
+
+
+def inverse(lib, spec, N, crop, into=None):
+    s = np.ascontiguousarray(np.stack([spec.real, spec.imag], -1).astype(np.float32))
+    M = spec.shape[1]
+    dst = np.full((M, crop, crop), np.nan, np.float32) if into is None else into.copy()
+    assert lib.replay_ifft2d_c2r_crop(N, s.ctypes.data_as(FP), dst.ctypes.data_as(FP), M, crop, 0 if into is None else 1) == 0
+    return dst
+
+
+def naive_dft2(pad):
+    """X[ky,kx] = sum_{y,x} pad[y,x] exp(-2 pi i (ky y + kx x)/N), written out as sums."""
+    N = pad.shape[-1]
+    idx = np.arange(N)
+    W = np.exp(-2j * np.pi * np.outer(idx, idx) / N)
+    return np.einsum("ky,myx,lx->mkl", W, pad, W)
+
+
+def test_size_rules(replay):
+    assert [replay.replay_fft_size(n) for n in (1, 8, 9, 16, 17, 34, 64)] == [8, 8, 16, 16, 32, 64, 64]
+    assert replay.replay_extent_class(32, 5) == 8 and replay.replay_extent_class(32, 9) == 16
+    assert replay.replay_extent_class(32, 28) == 32 and replay.replay_extent_class(8, 2) == 4
+
+
+@pytest.mark.parametrize("N", [8, 16, 32, 64])
+def test_forward_matches_naive_dft_and_fft2(replay, N):
+    rng = np.random.default_rng(N)
+    T = 512 // N
+    for ext in sorted({1, 3, N // 4, N // 4 + 1, N // 2, N // 2 + 1, N - 3, N}):
+        for M in (1, T - 1, T + 3):
+            src = rng.uniform(-1, 1, (M, ext, ext)).astype(np.float32)
+            pad = np.zeros((M, N, N)); pad[:, :ext, :ext] = src
+            got = forward(replay, src, N)
+            ref = np.fft.fft2(pad)[:, :N // 2 + 1, :].reshape(M, -1).T
+            assert np.abs(got - ref).max() <= 3e-6 * max(np.abs(ref).max(), 1), (N, ext, M)
+            if N <= 16 and M == 1:
+                nv = naive_dft2(pad)[:, :N // 2 + 1, :].reshape(M, -1).T
+                assert np.abs(got - nv).max() <= 3e-6 * max(np.abs(nv).max(), 1)
+
+
+@pytest.mark.parametrize("N", [8, 16, 32, 64])
+def test_inverse_crops_scales_and_accumulates(replay, N):
+    rng = np.random.default_rng(100 + N)
+    T = 512 // N
+    for crop in sorted({1, 3, N // 4, N // 4 + 1, N // 2 + 1, N - 2, N}):
+        for M in (2, T + 1):
+            full = rng.uniform(-1, 1, (M, N, N))
+            spec = np.fft.fft2(full)[:, :N // 2 + 1, :].reshape(M, -1).T
+            got = inverse(replay, spec, N, crop)
+            assert np.abs(got - full[:, :crop, :crop]).max() < 3e-6, (N, crop, M)
+            base = rng.uniform(-1, 1, (M, crop, crop)).astype(np.float32)
+            acc = inverse(replay, spec, N, crop, into=base)
+            assert np.abs(acc - (base + full[:, :crop, :crop])).max() < 3e-6
+
+
+def test_impulse_constant_and_round_trip(replay):
+    N = 16
+    imp = np.zeros((3, N, N), np.float32); imp[:, 0, 0] = 1
+    s = forward(replay, imp, N)
+    assert np.array_equal(s, np.ones_like(s))
+    s = forward(replay, np.ones((2, N, N), np.float32), N)
+    assert np.array_equal(s[0], [N * N, N * N]) and np.abs(s[1:]).max() < 1e-4
+    x = np.random.default_rng(5).uniform(-1, 1, (5, 11, 11)).astype(np.float32)
+    back = inverse(replay, forward(replay, x, N), N, 11)
+    assert np.abs(back - x).max() < 1e-6
