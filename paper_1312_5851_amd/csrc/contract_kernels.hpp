@@ -37,8 +37,10 @@ struct GemmArgs {
     int Md, Nd, Kd;  // per-bin product sizes: C (Md x Nd) = op(A) (Md x Kd) * op(B) (Kd x Nd)
     int bins;
     int tiles_m, tiles_n;
+    int xcd_remap;   // 1: renumber workgroups so that each XCD gets contiguous work
 };
 
+constexpr int kXcds = 8;   // accelerator complex dies on MI355X, workgroups are dealt to them round-robin
 constexpr int kKT = 16;   // complex K elements per chunk (one 128-byte line of a K-contiguous row)
 
 // Loads one operand tile chunk (ROWS non-K indices x KT K indices) from global memory
@@ -112,9 +114,17 @@ __global__ __launch_bounds__(G::THREADS) void bin_cgemm_kernel(GemmArgs g)
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave % G::WM, wn = wave / G::WM;
 
+    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Renumber
+    // them so that every XCD walks a contiguous range of (bin, tile) work: all tiles of
+    // a bin then share one L2 and each operand panel is fetched from HBM once.
+    const int total = (int)gridDim.x;
+    const int xcd = (int)blockIdx.x % kXcds, slot = (int)blockIdx.x / kXcds;
+    const int per = total / kXcds, rem = total % kXcds;
+    const int work = g.xcd_remap ? xcd * per + (xcd < rem ? xcd : rem) + slot : (int)blockIdx.x;
+
     const int tiles = g.tiles_m * g.tiles_n;
-    const int bin = (int)blockIdx.x / tiles;
-    const int t = (int)blockIdx.x % tiles;
+    const int bin = work / tiles;
+    const int t = work % tiles;
     const int i0 = (t % g.tiles_m) * G::MT, j0 = (t / g.tiles_m) * G::NT;
 
     // leading dimensions follow from the layouts: K-contiguous operands are [rows][Kd],

@@ -227,6 +227,7 @@ int launch_contract(fftconv_plan_t p, int pass, void *ws, hipStream_t stream)
     g.bins = p->B;
     g.tiles_m = (Md + e.MT - 1) / e.MT;
     g.tiles_n = (Nd + e.NT - 1) / e.NT;
+    g.xcd_remap = std::getenv("FFTCONV_NO_XCD_REMAP") ? 0 : 1;
     const long blocks = (long)g.bins * g.tiles_m * g.tiles_n;
     if (blocks <= 0 || blocks > 0x7fffffffL) return FFTCONV_EUNSUPPORTED;
     if (int rc = allow_lds(e.pass[pass], e.lds_bytes)) return rc;
