@@ -74,8 +74,9 @@ enum {
 int fftconv_plan(fftconv_plan_t *out, const fftconv_desc *d);
 int fftconv_plan_destroy(fftconv_plan_t p);
 
-/* Transform size N (power of two, >= n) and number of stored bins B = (N/2+1)*N:
- * the half spectrum a real map determines (Sec. 2.3), kept as N/2+1 full rows. */
+/* Transform size N (power of two, >= n) and number of stored bins B = N*N/2 + 2:
+ * the part of the spectrum a real map determines (Sec. 2.3), i.e. every bin that
+ * is not the complex conjugate of another stored bin. */
 int fftconv_fft_size(fftconv_plan_t p);
 int fftconv_num_bins(fftconv_plan_t p);
 
@@ -85,9 +86,12 @@ int fftconv_num_bins(fftconv_plan_t p);
 size_t fftconv_workspace_bytes(fftconv_plan_t p);
 
 /* Layout of one slot inside the workspace: byte offset and number of maps M.
- * A slot holds spec[b][m] as interleaved (re, im) floats, b = ky*N + kx with
- * ky in [0, N/2], kx in [0, N); m is the map index in the tensor's own order
- * (s*f+i for x, j*f+i for w, s*fo+j for g).  FFTCONV_SPEC_OUT holds the spectrum
+ * A slot holds spec[c][m] as interleaved (re, im) floats; stored bin c is
+ *   (ky = 0, kx = c)                 for c in [0, N/2],
+ *   (ky = N/2, kx = c - (N/2+1))     for c in [N/2+1, N+1],
+ *   (ky, kx), c = N+2 + (ky-1)*N+kx  for ky in [1, N/2-1], kx in [0, N);
+ * m is the map index in the tensor's own order (s*f+i for x, j*f+i for w,
+ * s*fo+j for g).  FFTCONV_SPEC_OUT holds the spectrum
  * of the last pass's result, laid out like that result.  Returns (size_t)-1 /
  * -1 for a bad slot. */
 size_t fftconv_slot_offset(fftconv_plan_t p, int slot);
@@ -148,8 +152,9 @@ const char *fftconv_strerror(int status);
  * map; the workspace query above counts the (N/2+1)*N actually stored). */
 size_t fftconv_paper_ram_bytes(int S, int n, int f, int fo);
 
-/* Real floating-point operations the contraction of one pass issues:
- * 8 * S * f * fo * B (four real multiply-adds per complex product per bin). */
+/* Matrix-core floating-point operations the contraction of one pass issues:
+ * 6 * S * f * fo * B (three real multiply-adds per complex product, Gauss's
+ * form, over the B stored bins), tile padding not counted. */
 double fftconv_contraction_flops(fftconv_plan_t p);
 
 #ifdef __cplusplus

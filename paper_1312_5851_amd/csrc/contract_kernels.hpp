@@ -11,16 +11,23 @@
 // (cross-correlation <-> conjugate of the kernel-side spectrum).  All spectra are
 // bin-major, complex interleaved, row-major inside a bin.
 //
-// A complex product is four real ones, issued as v_mfma_f32_32x32x2_f32:
-//   Cre += Are*Bre;  Cre += (-Aim)*Bim;  Cim += Are*Bim;  Cim += Aim*Bre
-// i.e. 8*M*N*K real flops per bin.  Conjugation is applied once, while an operand
-// tile is written to LDS.
+// Arithmetic.  A complex product needs three real products when sums of the
+// operands are formed first (Gauss):
+//     k1 = (ar + ai) * br,   k2 = ar * (bi - br),   k3 = ai * (br + bi)
+//     re = k1 - k3,          im = k1 + k2
+// Each is accumulated over K by v_mfma_f32_32x32x2_f32 in its own fp32 tile, so a
+// bin costs 6*M*N*K matrix-core flops instead of the 8*M*N*K of the four-product
+// form; the operand sums are three VALU adds per fragment, and re/im are formed
+// once in the epilogue.  Conjugation is applied while a tile is written to LDS.
 //
-// A workgroup of WM x WN waves owns an MT x NT tile of one bin's product and walks
-// K in chunks of KT.  Operand tiles are staged through LDS as Ps[k][r] (non-K index
-// fastest, complex interleaved), so a 32x2 MFMA fragment is one ds_read_b64 per
-// lane: lane l reads Ps[k0 + l/32][r0 + l%32].  The next chunk's global loads are
-// issued before the current chunk's MFMAs and land in registers meanwhile.
+// Data flow.  A workgroup of WM x WN waves owns an MT x NT tile of one bin and
+// walks K in chunks of kKT.  Operand chunks go global -> registers -> LDS, laid
+// out Ps[k][r] (non-K index fastest), so the 32x2 operand fragment of an MFMA is
+// one ds_read_b64 per lane: lane l reads Ps[k0 + l/32][r0 + l%32].  LDS holds two
+// chunks: while chunk c is multiplied, chunk c+1 is written to the other half
+// (its global loads were issued one chunk earlier) and chunk c+2's loads are
+// issued; one barrier per chunk.  Fragments are double-buffered in registers so
+// the LDS latency of step ks+1 hides behind the MFMAs of step ks.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -40,22 +47,23 @@ struct GemmArgs {
     int xcd_remap;   // 1: renumber workgroups so that each XCD gets contiguous work
 };
 
-constexpr int kXcds = 8;   // accelerator complex dies on MI355X, workgroups are dealt to them round-robin
-constexpr int kKT = 16;   // complex K elements per chunk (one 128-byte line of a K-contiguous row)
+constexpr int kXcds = 8;   // accelerator complex dies on MI355X; workgroups are dealt to them round-robin
+constexpr int kKT = 16;    // complex K elements per chunk (one 128-byte line of a K-contiguous row)
 
-// Loads one operand tile chunk (ROWS non-K indices x KT K indices) from global memory
-// into registers and later writes it to LDS as Ps[kk * SP + r].
+// Moves one operand chunk (ROWS non-K indices x kKT K indices) global -> registers -> LDS.
 //   KIN = true : global element (r, k) at base[r * ld + k]   (K contiguous)
 //   KIN = false: global element (r, k) at base[k * ld + r]   (non-K index contiguous)
+// LDS layout Ps[kk * SP + r].  SP is odd: the 16 lanes that an LDS store of 8-byte
+// elements serves together then hit 16 different bank pairs whether they run along r
+// (stride 1) or along kk (stride SP).
 template <int ROWS, int THREADS, bool KIN, bool CONJ>
 struct TileLoader {
     static constexpr int ELEMS = ROWS * kKT;
     static constexpr int PER_THREAD = (ELEMS + THREADS - 1) / THREADS;
-    static constexpr int SP = ROWS + 2;   // LDS row stride (complex); ROWS % 32 == 0 so SP % 32 == 2
+    static constexpr int SP = ROWS + 1;
 
     cf regs[PER_THREAD];
 
-    // element e of the tile handled by this thread in pass p
     __device__ __forceinline__ static void coords(int tid, int p, int &r, int &kk)
     {
         const int e = p * THREADS + tid;
@@ -70,7 +78,7 @@ struct TileLoader {
             int r, kk;
             coords(tid, p, r, kk);
             const int gr = r0 + r, gk = k0 + kk;
-            const bool ok = (p * THREADS + tid < ELEMS) && gr < rmax && gk < kmax;
+            const bool ok = (ELEMS % THREADS == 0 || p * THREADS + tid < ELEMS) && gr < rmax && gk < kmax;
             // unconditional load from a clamped (valid) address, masked afterwards: no branch per load
             const int grc = gr < rmax ? gr : rmax - 1, gkc = gk < kmax ? gk : kmax - 1;
             cf v = KIN ? base[(size_t)grc * ld + gkc] : base[(size_t)gkc * ld + grc];
@@ -86,37 +94,38 @@ struct TileLoader {
         for (int p = 0; p < PER_THREAD; ++p) {
             int r, kk;
             coords(tid, p, r, kk);
-            if (p * THREADS + tid < ELEMS) Ps[kk * SP + r] = regs[p];
+            if (ELEMS % THREADS == 0 || p * THREADS + tid < ELEMS) Ps[kk * SP + r] = regs[p];
         }
     }
 };
 
-template <int MT_, int NT_, int WM_, int WN_>
+// IT x JT 32x32 MFMA tiles per wave, WM x WN waves per workgroup.
+template <int IT_, int JT_, int WM_, int WN_>
 struct GemmTile {
-    static constexpr int MT = MT_, NT = NT_, WM = WM_, WN = WN_;
+    static constexpr int IT = IT_, JT = JT_, WM = WM_, WN = WN_;
+    static constexpr int MT = 32 * IT * WM, NT = 32 * JT * WN;
     static constexpr int THREADS = 64 * WM * WN;
-    static constexpr int IT = MT / WM / 32;   // 32x32 MFMA tiles per wave along M
-    static constexpr int JT = NT / WN / 32;   // ... along N
-    static constexpr int SA = MT + 2, SB = NT + 2;
-    static constexpr int LDS_BYTES = kKT * (SA + SB) * 8;
-    static_assert(MT % (32 * WM) == 0 && NT % (32 * WN) == 0, "wave tiles are multiples of 32x32");
+    static constexpr int SA = MT + 1, SB = NT + 1;
+    static constexpr int STAGE = kKT * (SA + SB);       // complex elements of one chunk (A then B)
+    static constexpr int LDS_BYTES = 2 * STAGE * 8;     // two chunks
+    static constexpr int ACC_REGS = 3 * IT * JT * 16;
 };
 
 // Launch: grid = bins * tiles_m * tiles_n blocks of G::THREADS threads, G::LDS_BYTES dynamic LDS.
 template <class G, bool A_KIN, bool B_KIN, bool CONJ_A, bool CONJ_B>
 __global__ __launch_bounds__(G::THREADS) void bin_cgemm_kernel(GemmArgs g)
 {
+    constexpr int IT = G::IT, JT = G::JT, KS = kKT / 2;
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    cf *As = reinterpret_cast<cf *>(lds_raw);
-    cf *Bs = As + kKT * G::SA;
+    cf *lds = reinterpret_cast<cf *>(lds_raw);
 
     const int tid = (int)threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave % G::WM, wn = wave / G::WM;
 
-    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Renumber
+    // Workgroups are dealt round-robin to the XCDs (each with its own L2).  Renumber
     // them so that every XCD walks a contiguous range of (bin, tile) work: all tiles of
-    // a bin then share one L2 and each operand panel is fetched from HBM once.
+    // a bin then share one L2.
     const int total = (int)gridDim.x;
     const int xcd = (int)blockIdx.x % kXcds, slot = (int)blockIdx.x / kXcds;
     const int per = total / kXcds, rem = total % kXcds;
@@ -138,53 +147,72 @@ __global__ __launch_bounds__(G::THREADS) void bin_cgemm_kernel(GemmArgs g)
     TileLoader<G::MT, G::THREADS, A_KIN, CONJ_A> la;
     TileLoader<G::NT, G::THREADS, B_KIN, CONJ_B> lb;
 
-    floatx16 cre[G::IT][G::JT], cim[G::IT][G::JT];
+    floatx16 k1[IT][JT], k2[IT][JT], k3[IT][JT];
 #pragma unroll
-    for (int a = 0; a < G::IT; ++a)
+    for (int a = 0; a < IT; ++a)
 #pragma unroll
-        for (int b = 0; b < G::JT; ++b)
+        for (int b = 0; b < JT; ++b)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) { cre[a][b][v] = 0.0f; cim[a][b][v] = 0.0f; }
+            for (int v = 0; v < 16; ++v) { k1[a][b][v] = 0.0f; k2[a][b][v] = 0.0f; k3[a][b][v] = 0.0f; }
 
+    const int nchunks = (g.Kd + kKT - 1) / kKT;
     la.load(Ab, lda, i0, g.Md, 0, g.Kd, tid);
     lb.load(Bb, ldb, j0, g.Nd, 0, g.Kd, tid);
+    la.store(lds, tid);
+    lb.store(lds + kKT * G::SA, tid);
+    if (nchunks > 1) {
+        la.load(Ab, lda, i0, g.Md, kKT, g.Kd, tid);
+        lb.load(Bb, ldb, j0, g.Nd, kKT, g.Kd, tid);
+    }
+    __syncthreads();
 
     const int lrow = lane & 31, lk = lane >> 5;
-    const cf *Afrag = As + lk * G::SA + wm * (G::IT * 32) + lrow;
-    const cf *Bfrag = Bs + lk * G::SB + wn * (G::JT * 32) + lrow;
+    const int a_off = lk * G::SA + wm * (IT * 32) + lrow;
+    const int b_off = kKT * G::SA + lk * G::SB + wn * (JT * 32) + lrow;
 
-    for (int k0 = 0; k0 < g.Kd; k0 += kKT) {
-        la.store(As, tid);
-        lb.store(Bs, tid);
-        __syncthreads();
-        if (k0 + kKT < g.Kd) {   // next chunk's loads fly during this chunk's MFMAs
-            la.load(Ab, lda, i0, g.Md, k0 + kKT, g.Kd, tid);
-            lb.load(Bb, ldb, j0, g.Nd, k0 + kKT, g.Kd, tid);
-        }
+    for (int c = 0; c < nchunks; ++c) {
+        const cf *Af = lds + (c & 1) * G::STAGE + a_off;
+        const cf *Bf = lds + (c & 1) * G::STAGE + b_off;
+        cf af[2][IT], bf[2][JT];
 #pragma unroll
-        for (int ks = 0; ks < kKT / 2; ++ks) {
-            cf af[G::IT], bf[G::JT];
-            float nai[G::IT];
+        for (int a = 0; a < IT; ++a) af[0][a] = Af[a * 32];
 #pragma unroll
-            for (int a = 0; a < G::IT; ++a) {
-                af[a] = Afrag[(2 * ks) * G::SA + a * 32];
-                nai[a] = -af[a].y;
+        for (int b = 0; b < JT; ++b) bf[0][b] = Bf[b * 32];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int cur = ks & 1, nxt = cur ^ 1;
+            if (ks + 1 < KS) {   // fragments of the next step: their LDS latency hides behind this step's MFMAs
+#pragma unroll
+                for (int a = 0; a < IT; ++a) af[nxt][a] = Af[(2 * (ks + 1)) * G::SA + a * 32];
+#pragma unroll
+                for (int b = 0; b < JT; ++b) bf[nxt][b] = Bf[(2 * (ks + 1)) * G::SB + b * 32];
+            }
+            if (ks == KS / 2) {   // mid-chunk: hand the next chunk to LDS, start fetching the one after
+                cf *stage = lds + ((c + 1) & 1) * G::STAGE;
+                if (c + 1 < nchunks) {
+                    la.store(stage, tid);
+                    lb.store(stage + kKT * G::SA, tid);
+                }
+                if (c + 2 < nchunks) {
+                    la.load(Ab, lda, i0, g.Md, (c + 2) * kKT, g.Kd, tid);
+                    lb.load(Bb, ldb, j0, g.Nd, (c + 2) * kKT, g.Kd, tid);
+                }
+            }
+            float as[IT], bd[JT], bs[JT];
+#pragma unroll
+            for (int a = 0; a < IT; ++a) as[a] = af[cur][a].x + af[cur][a].y;
+#pragma unroll
+            for (int b = 0; b < JT; ++b) {
+                bd[b] = bf[cur][b].y - bf[cur][b].x;
+                bs[b] = bf[cur][b].x + bf[cur][b].y;
             }
 #pragma unroll
-            for (int b = 0; b < G::JT; ++b) bf[b] = Bfrag[(2 * ks) * G::SB + b * 32];
+            for (int a = 0; a < IT; ++a)
 #pragma unroll
-            for (int a = 0; a < G::IT; ++a)
-#pragma unroll
-                for (int b = 0; b < G::JT; ++b) {
-                    cre[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[a].x, bf[b].x, cre[a][b], 0, 0, 0);
-                    cim[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[a].x, bf[b].y, cim[a][b], 0, 0, 0);
-                }
-#pragma unroll
-            for (int a = 0; a < G::IT; ++a)
-#pragma unroll
-                for (int b = 0; b < G::JT; ++b) {
-                    cre[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(nai[a], bf[b].y, cre[a][b], 0, 0, 0);
-                    cim[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[a].y, bf[b].x, cim[a][b], 0, 0, 0);
+                for (int b = 0; b < JT; ++b) {
+                    k1[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(as[a], bf[cur][b].x, k1[a][b], 0, 0, 0);
+                    k2[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cur][a].x, bd[b], k2[a][b], 0, 0, 0);
+                    k3[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cur][a].y, bs[b], k3[a][b], 0, 0, 0);
                 }
         }
         __syncthreads();
@@ -192,15 +220,15 @@ __global__ __launch_bounds__(G::THREADS) void bin_cgemm_kernel(GemmArgs g)
 
     // 32x32 accumulator layout: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32
 #pragma unroll
-    for (int a = 0; a < G::IT; ++a)
+    for (int a = 0; a < IT; ++a)
 #pragma unroll
-        for (int b = 0; b < G::JT; ++b) {
-            const int col = j0 + wn * (G::JT * 32) + b * 32 + lrow;
+        for (int b = 0; b < JT; ++b) {
+            const int col = j0 + wn * (JT * 32) + b * 32 + lrow;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int row = i0 + wm * (G::IT * 32) + a * 32 + 8 * (v / 4) + 4 * lk + (v % 4);
+                const int row = i0 + wm * (IT * 32) + a * 32 + 8 * (v / 4) + 4 * lk + (v % 4);
                 if (row < g.Md && col < g.Nd)
-                    Cb[(size_t)row * g.Nd + col] = mk(cre[a][b][v], cim[a][b][v]);
+                    Cb[(size_t)row * g.Nd + col] = mk(k1[a][b][v] - k3[a][b][v], k1[a][b][v] + k2[a][b][v]);
             }
         }
 }

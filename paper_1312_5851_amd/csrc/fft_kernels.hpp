@@ -2,12 +2,16 @@
 // inverse fused with cropping (paper Sec. 2.2: transform every map once, crop
 // the circular result; Sec. 2.3: a 2-D FFT is two sets of 1-D FFTs).
 //
-// Spectrum layout ("bin-major"): spec[b * M + m] is bin b of map m, complex
-// interleaved, with b = ky * N + kx, ky in [0, N/2], kx in [0, N): the half of
-// the N x N spectrum that a real map determines (Sec. 2.3, symmetry of FFTs of
-// real inputs), kept as N/2+1 full rows.  For a fixed bin the M maps are
-// contiguous, which makes every bin a dense row-major matrix for the
-// per-frequency contraction.
+// Spectrum layout ("bin-major"): spec[c * M + m] is stored bin c of map m, complex
+// interleaved.  A real map determines only half of its N x N spectrum (Sec. 2.3,
+// symmetry of FFTs of real inputs).  Stored are exactly the bins that are not the
+// conjugate of another stored bin, B = N*N/2 + 2 of them, in this order:
+//     c in [0, N/2]            (ky = 0,   kx = c)
+//     c in [N/2+1, N+1]        (ky = N/2, kx = c - (N/2+1))
+//     c = N+2 + (ky-1)*N + kx  (ky in [1, N/2-1], kx in [0, N))
+// (rows ky = 0 and ky = N/2 are Hermitian in kx, so only kx <= N/2 is kept).
+// For a fixed bin the M maps are contiguous, which makes every bin a dense
+// row-major matrix for the per-frequency contraction.
 //
 // One workgroup transforms T consecutive maps so that each bin is written (or
 // read) as one contiguous run of T complex numbers.  The work is two phases
@@ -36,7 +40,7 @@ namespace fftconv {
 
 struct FwdArgs {
     const float *src;   // [M][ext][ext] real maps
-    cf *spec;           // [B][M] bin-major spectrum
+    cf *spec;           // [B][M] bin-major spectrum, B = N*N/2 + 2 stored bins
     int M;              // number of maps
     int ext;            // spatial extent of a map (n, k or n'); everything beyond is zero padding
 };
@@ -138,15 +142,16 @@ FC_HD void fwd_phase_x(int tid, int blk, const FwdArgs &a, const cf *lds)
     if (r != 0) {
         static_for<0, N>([&](auto ki) {
             constexpr int kx = decltype(ki)::value;
-            out[((size_t)r * N + kx) * M] = v[brev<N>(kx)];
+            out[((size_t)(N + 2) + (size_t)(r - 1) * N + kx) * M] = v[brev<N>(kx)];
         });
     } else {
-        // C = FFT(row0 + i rowH)  ->  row0[k] = (C[k] + conj C[-k]) / 2,  rowH[k] = (C[k] - conj C[-k]) / (2i)
-        static_for<0, N>([&](auto ki) {
+        // C = FFT(row0 + i rowH)  ->  row0[k] = (C[k] + conj C[-k]) / 2,  rowH[k] = (C[k] - conj C[-k]) / (2i);
+        // both rows are Hermitian in k, only k <= N/2 is stored
+        static_for<0, N / 2 + 1>([&](auto ki) {
             constexpr int kx = decltype(ki)::value;
             const cf c = v[brev<N>(kx)], d = v[brev<N>((N - kx) % N)];
             out[(size_t)kx * M] = mk(0.5f * (c.x + d.x), 0.5f * (c.y - d.y));
-            out[((size_t)(N / 2) * N + kx) * M] = mk(0.5f * (c.y + d.y), 0.5f * (d.x - c.x));
+            out[(size_t)(N / 2 + 1 + kx) * M] = mk(0.5f * (c.y + d.y), 0.5f * (d.x - c.x));
         });
     }
 }
@@ -167,20 +172,23 @@ FC_HD void inv_phase_x(int tid, int blk, const InvArgs &a, cf *lds)
     if (r != 0) {
         static_for<0, N>([&](auto ki) {
             constexpr int kx = decltype(ki)::value;
-            v[kx] = in[((size_t)r * N + kx) * M];
+            v[kx] = in[((size_t)(N + 2) + (size_t)(r - 1) * N + kx) * M];
         });
     } else {
         // rows ky = 0 and ky = N/2 are Hermitian in kx, so their inverse transforms are
-        // real: send both through one complex transform as row0 + i rowH
-        cf y0[N], yh[N];
-        static_for<0, N>([&](auto ki) {
+        // real: send both through one complex transform as row0 + i rowH, rebuilding the
+        // bins kx > N/2 that are not stored from their conjugates
+        cf y0[N / 2 + 1], yh[N / 2 + 1];
+        static_for<0, N / 2 + 1>([&](auto ki) {
             constexpr int kx = decltype(ki)::value;
             y0[kx] = in[(size_t)kx * M];
-            yh[kx] = in[((size_t)(N / 2) * N + kx) * M];
+            yh[kx] = in[(size_t)(N / 2 + 1 + kx) * M];
         });
-        static_for<0, N>([&](auto ki) {
+        static_for<0, N / 2 + 1>([&](auto ki) {
             constexpr int kx = decltype(ki)::value;
-            v[kx] = mk(y0[kx].x - yh[kx].y, y0[kx].y + yh[kx].x);
+            v[kx] = mk(y0[kx].x - yh[kx].y, y0[kx].y + yh[kx].x);                 // y0 + i yh
+            if constexpr (kx > 0 && kx < N / 2)
+                v[N - kx] = mk(y0[kx].x + yh[kx].y, yh[kx].x - y0[kx].y);        // conj y0 + i conj yh
         });
     }
     fft_dif<N, true, 0, first_outputs_mask<N>(NX)>(v);

@@ -57,7 +57,7 @@ const FftEntry *find_fft(int N, int ext)
 }
 
 struct GemmEntry {
-    int MT, NT, threads, lds_bytes;
+    int MT, NT, wave_tiles, waves, occ, threads, lds_bytes;
     GemmKernel pass[3];   // indexed by FFTCONV_FPROP / BPROP / ACCGRAD
 };
 
@@ -65,22 +65,35 @@ struct GemmEntry {
 //   fprop   A = Xh [S][f]  K contiguous,  B = Wh [fo][f] K contiguous, conj B
 //   bprop   A = Gh [S][fo] K contiguous,  B = Wh [fo][f] K outer
 //   accGrad A = Gh [S][fo] K outer, conj A,  B = Xh [S][f] K outer
-#define GEMM_ENTRY(mt, nt, wm, wn)                                                         \
-    {mt, nt, GemmTile<mt, nt, wm, wn>::THREADS, GemmTile<mt, nt, wm, wn>::LDS_BYTES,         \
-     {bin_cgemm_kernel<GemmTile<mt, nt, wm, wn>, true, true, false, true>,                   \
-      bin_cgemm_kernel<GemmTile<mt, nt, wm, wn>, true, false, false, false>,                 \
-      bin_cgemm_kernel<GemmTile<mt, nt, wm, wn>, false, false, true, false>}}
+#define GEMM_ENTRY(it, jt, wm, wn, occ)                                                       \
+    {GemmTile<it, jt, wm, wn>::MT, GemmTile<it, jt, wm, wn>::NT, it * jt, wm * wn, occ,          \
+     GemmTile<it, jt, wm, wn>::THREADS, GemmTile<it, jt, wm, wn>::LDS_BYTES,                     \
+     {bin_cgemm_kernel<GemmTile<it, jt, wm, wn>, true, true, false, true>,                       \
+      bin_cgemm_kernel<GemmTile<it, jt, wm, wn>, true, false, false, false>,                     \
+      bin_cgemm_kernel<GemmTile<it, jt, wm, wn>, false, false, true, false>}}
+// (32x32 tiles per wave along M and N, waves along M and N, resident waves per SIMD)
 const GemmEntry kGemmTable[] = {
-    GEMM_ENTRY(128, 128, 2, 2), GEMM_ENTRY(64, 128, 2, 2), GEMM_ENTRY(128, 64, 2, 2),
-    GEMM_ENTRY(64, 64, 2, 2),   GEMM_ENTRY(128, 96, 4, 1), GEMM_ENTRY(64, 96, 2, 1),
-    GEMM_ENTRY(32, 32, 1, 1),
+    GEMM_ENTRY(2, 1, 2, 2, 3),   //  0: 128 x  64
+    GEMM_ENTRY(1, 2, 2, 2, 3),   //  1:  64 x 128
+    GEMM_ENTRY(1, 1, 2, 2, 4),   //  2:  64 x  64
+    GEMM_ENTRY(2, 1, 1, 3, 3),   //  3:  64 x  96
+    GEMM_ENTRY(2, 1, 2, 3, 3),   //  4: 128 x  96
+    GEMM_ENTRY(1, 1, 2, 3, 4),   //  5:  64 x  96 (32 x 32 per wave)
+    GEMM_ENTRY(1, 1, 1, 1, 4),   //  6:  32 x  32
+    GEMM_ENTRY(1, 1, 4, 1, 4),   //  7: 128 x  32
+    GEMM_ENTRY(2, 1, 2, 1, 3),   //  8: 128 x  32 (64 x 32 per wave)
+    GEMM_ENTRY(2, 2, 2, 2, 1),   //  9: 128 x 128
+    GEMM_ENTRY(1, 3, 2, 1, 2),   // 10:  64 x  96 (32 x 96 per wave)
 };
 #undef GEMM_ENTRY
 constexpr int kNumGemm = sizeof(kGemmTable) / sizeof(kGemmTable[0]);
 
-// Estimated relative time of a tile shape: the busiest CU's share of the padded
-// MFMA work, with a mild penalty for small tiles (more operand traffic per flop).
-int choose_gemm_tile(int Md, int Nd, int bins)
+// Picks the tile shape with the smallest estimated time.  Model: every wave owns
+// `wave_tiles` 32x32 tiles (3 MFMAs of 64 cycles each per K pair), `occ` waves share a
+// SIMD's matrix core; workgroups are handed out dynamically, so the run is the full
+// rounds at the shared rate plus a last partial round in which a lone wave cannot
+// keep the pipe full.
+int choose_gemm_tile(int Md, int Nd, int Kd, int bins)
 {
     if (const char *env = std::getenv("FFTCONV_GEMM_TILE")) {
         const int v = std::atoi(env);
@@ -90,10 +103,19 @@ int choose_gemm_tile(int Md, int Nd, int bins)
     double best_cost = 1e300;
     for (int i = 0; i < kNumGemm; ++i) {
         const GemmEntry &e = kGemmTable[i];
-        const long tiles = (long)((Md + e.MT - 1) / e.MT) * ((Nd + e.NT - 1) / e.NT) * bins;
-        const long per_cu = (tiles + kNumCUs - 1) / kNumCUs;
-        const double traffic_penalty = 1.0 + 8.0 * (1.0 / e.MT + 1.0 / e.NT);
-        const double cost = (double)per_cu * e.MT * e.NT * traffic_penalty;
+        const long items = (long)((Md + e.MT - 1) / e.MT) * ((Nd + e.NT - 1) / e.NT) * bins;
+        const double wave_work = (double)e.wave_tiles * ((Kd + kKT - 1) / kKT * kKT);   // per-wave MFMA time units
+        const long wgs_per_cu = (4L * e.occ) / e.waves > 0 ? (4L * e.occ) / e.waves : 1;
+        const long slots = kNumCUs * wgs_per_cu;
+        const long full = items / slots, rem = items % slots;
+        const double waves_per_simd = (double)wgs_per_cu * e.waves / 4.0;
+        double cost = (double)full * waves_per_simd * wave_work / 0.9;
+        if (rem) {
+            const double rem_waves = (double)((rem + kNumCUs - 1) / kNumCUs) * e.waves / 4.0;
+            const double shared = rem_waves * wave_work / 0.9, solo = wave_work / 0.7;
+            cost += shared > solo ? shared : solo;
+        }
+        cost *= 1.0 + 2.0 * (1.0 / e.MT + 1.0 / e.NT);   // operand traffic per flop
         if (cost < best_cost) { best_cost = cost; best = i; }
     }
     return best;
@@ -290,7 +312,7 @@ int fftconv_plan(fftconv_plan_t *out, const fftconv_desc *d)
     p->d = *d;
     p->no = d->n - d->k + 1;
     p->N = fft_size_for(d->n);
-    p->B = (p->N / 2 + 1) * p->N;
+    p->B = p->N * p->N / 2 + 2;
     p->maps_x = maps_x;
     p->maps_w = maps_w;
     p->maps_g = maps_g;
@@ -307,7 +329,7 @@ int fftconv_plan(fftconv_plan_t *out, const fftconv_desc *d)
     for (int pass = 0; pass < 3; ++pass) {
         int Md, Nd, Kd, sa, sb;
         pass_dims(p, pass, Md, Nd, Kd, sa, sb);
-        p->gemm_tile[pass] = choose_gemm_tile(Md, Nd, p->B);
+        p->gemm_tile[pass] = choose_gemm_tile(Md, Nd, Kd, p->B);
     }
     *out = p;
     return FFTCONV_OK;
@@ -447,7 +469,7 @@ size_t fftconv_paper_ram_bytes(int S, int n, int f, int fo)
 double fftconv_contraction_flops(fftconv_plan_t p)
 {
     if (!p) return 0.0;
-    return 8.0 * p->d.S * p->d.f * p->d.fo * p->B;
+    return 6.0 * p->d.S * p->d.f * p->d.fo * p->B;
 }
 
 }  // extern "C"

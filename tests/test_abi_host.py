@@ -42,7 +42,7 @@ def test_signatures_carry_no_torch_types():
 def test_fft_size_is_next_power_of_two(fc, n, N):
     # Sec. 4: sizes that are not a power of two are padded to the next one (34 -> 64)
     p = fc.Plan(2, 3, 4, n, 1)
-    assert p.fft_size == N and p.num_bins == (N // 2 + 1) * N
+    assert p.fft_size == N and p.num_bins == N * N // 2 + 2
 
 
 def test_workspace_layout(fc):
@@ -58,7 +58,7 @@ def test_workspace_layout(fc):
     # the three cached spectra are the S f + S f' + f f' frequency representations of Sec. 2.3
     assert p.slot_offset(fc.SPEC_OUT) == 8 * B * (128 * 96 + 128 * 256 + 96 * 256)
     assert p.slot_maps(3) == -1
-    assert p.contraction_flops == 8.0 * 128 * 96 * 256 * B
+    assert B == 514 and p.contraction_flops == 6.0 * 128 * 96 * 256 * B
 
 
 @pytest.mark.parametrize("args,status", [
@@ -115,11 +115,12 @@ def test_paper_ram_closed_form_and_table(fc):
     assert fc.paper_ram_bytes(0, 1, 1, 1) == 0
 
 
-def test_stored_bins_exceed_paper_count_only_by_the_extra_half_rows(fc):
-    # paper counts n(n+1)/2 complex per map; N/2+1 full rows store N(N/2+1): N/2 more
+def test_stored_bins_are_the_non_redundant_half(fc):
+    # paper counts n(n+1)/2 complex per map; exactly N*N/2 + 2 bins are not conjugates of one
+    # another (N*N real degrees of freedom: N*N/2 - 2 complex bins plus 4 real ones)
     for n in (16, 32, 64):
         p = fc.Plan(1, 1, 1, n, 3)
-        assert p.num_bins - n * (n + 1) // 2 == n // 2
+        assert p.num_bins == n * n // 2 + 2 <= n * (n + 1) // 2
 
 
 def test_workloads_are_seeded_and_shaped():

@@ -9,6 +9,8 @@ import ctypes
 import numpy as np
 import pytest
 
+from spectrum_layout import reference_spectrum, stored_bins
+
 
 @pytest.fixture(scope="module")
 def replay():
@@ -22,7 +24,7 @@ FP = ctypes.POINTER(ctypes.c_float)
 
 def forward(lib, src, N):
     M, ext, _ = src.shape
-    B = (N // 2 + 1) * N
+    B = N * N // 2 + 2
     spec = np.full((B, M, 2), np.nan, np.float32)
     assert lib.replay_fft2d_r2c(N, src.ctypes.data_as(FP), spec.ctypes.data_as(FP), M, ext) == 0
     return spec[..., 0].astype(np.float64) + 1j * spec[..., 1]
@@ -59,10 +61,11 @@ def test_forward_matches_naive_dft_and_fft2(replay, N):
             src = rng.uniform(-1, 1, (M, ext, ext)).astype(np.float32)
             pad = np.zeros((M, N, N)); pad[:, :ext, :ext] = src
             got = forward(replay, src, N)
-            ref = np.fft.fft2(pad)[:, :N // 2 + 1, :].reshape(M, -1).T
+            ref = reference_spectrum(src, N)
             assert np.abs(got - ref).max() <= 3e-6 * max(np.abs(ref).max(), 1), (N, ext, M)
             if N <= 16 and M == 1:
-                nv = naive_dft2(pad)[:, :N // 2 + 1, :].reshape(M, -1).T
+                ky, kx = stored_bins(N)
+                nv = naive_dft2(pad)[:, ky, kx].T
                 assert np.abs(got - nv).max() <= 3e-6 * max(np.abs(nv).max(), 1)
 
 
@@ -73,7 +76,7 @@ def test_inverse_crops_scales_and_accumulates(replay, N):
     for crop in sorted({1, 3, N // 4, N // 4 + 1, N // 2 + 1, N - 2, N}):
         for M in (2, T + 1):
             full = rng.uniform(-1, 1, (M, N, N))
-            spec = np.fft.fft2(full)[:, :N // 2 + 1, :].reshape(M, -1).T
+            spec = reference_spectrum(full, N)
             got = inverse(replay, spec, N, crop)
             assert np.abs(got - full[:, :crop, :crop]).max() < 3e-6, (N, crop, M)
             base = rng.uniform(-1, 1, (M, crop, crop)).astype(np.float32)

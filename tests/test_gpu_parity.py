@@ -8,6 +8,7 @@ import pytest
 import torch
 
 from oracle import direct
+from spectrum_layout import reference_spectrum, stored_bins
 from paper_1312_5851_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
@@ -110,16 +111,14 @@ def test_spectrum_stage_against_fft2(fc):
     x, w, g = wl.make_inputs(layer)
     plan = fc.Plan(layer.S, layer.f, layer.fo, layer.n, layer.k)
     N = plan.fft_size
-    assert N == 32 and plan.num_bins == (N // 2 + 1) * N
+    assert N == 32 and plan.num_bins == N * N // 2 + 2
     for slot, arr in ((fc.SPEC_X, x), (fc.SPEC_W, w), (fc.SPEC_G, g)):
         plan.forward_transform(slot, dev(arr))
         torch.cuda.synchronize()
         spec = plan.slot_view(slot).cpu().numpy().astype(np.float64)
         spec = spec[..., 0] + 1j * spec[..., 1]
         maps = arr.reshape(-1, arr.shape[-2], arr.shape[-1]).astype(np.float64)
-        pad = np.zeros((maps.shape[0], N, N))
-        pad[:, :maps.shape[1], :maps.shape[2]] = maps
-        ref = np.fft.fft2(pad)[:, :N // 2 + 1, :].reshape(maps.shape[0], -1).T
+        ref = reference_spectrum(maps, N)
         err = np.abs(spec - ref).max() / np.abs(ref).max()
         print(f"slot {slot}: rel max err {err:.3e}", flush=True)
         assert err < 2e-6
@@ -133,15 +132,17 @@ def test_spectrum_stage_against_fft2(fc):
     plan16.forward_transform(fc.SPEC_X, torch.ones((2, 3, 16, 16), device="cuda")); torch.cuda.synchronize()
     s = plan16.slot_view(fc.SPEC_X).cpu().numpy()
     assert np.array_equal(s[0, :, 0], np.full(6, 256.0, np.float32)) and np.abs(s[1:]).max() < 1e-4
-    # Hermitian symmetry inside the stored rows ky = 0 and ky = N/2, and Parseval on one map
+    # the four self-conjugate bins are exactly real, and Parseval holds with the stored bins
+    # (every stored bin except those four stands for itself and its conjugate)
     plan.forward_transform(fc.SPEC_X, dev(x)); torch.cuda.synchronize()
     s = plan.slot_view(fc.SPEC_X).cpu().numpy().astype(np.float64)
-    z = (s[..., 0] + 1j * s[..., 1]).reshape(N // 2 + 1, N, -1)
-    for ky in (0, N // 2):
-        assert np.array_equal(z[ky, 1:], np.conj(z[ky, :0:-1]))
-    full = np.abs(z[1:N // 2]) ** 2
-    energy = (np.abs(z[0]) ** 2).sum(0) + (np.abs(z[N // 2]) ** 2).sum(0) + 2 * full.sum((0, 1))
-    np.testing.assert_allclose(energy / (N * N), (x.astype(np.float64) ** 2).reshape(-1, layer.n ** 2).sum(1), rtol=1e-5)
+    z = s[..., 0] + 1j * s[..., 1]
+    ky, kx = stored_bins(N)
+    self_conj = ((ky == 0) | (ky == N // 2)) & ((kx == 0) | (kx == N // 2))
+    assert self_conj.sum() == 4 and np.all(z[self_conj].imag == 0)
+    weight = np.where(self_conj, 1.0, 2.0)[:, None]
+    energy = (weight * np.abs(z) ** 2).sum(0) / (N * N)
+    np.testing.assert_allclose(energy, (x.astype(np.float64) ** 2).reshape(-1, layer.n ** 2).sum(1), rtol=1e-5)
 
 
 def test_cache_bits_invalidate_and_accumulate(fc):
