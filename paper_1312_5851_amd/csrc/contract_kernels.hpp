@@ -63,6 +63,7 @@ struct TileLoader {
     static constexpr int SP = ROWS + 1;
 
     cf regs[PER_THREAD];
+    unsigned okmask;   // bit p: element p of this thread lies inside the matrix
 
     __device__ __forceinline__ static void coords(int tid, int p, int &r, int &kk)
     {
@@ -71,20 +72,23 @@ struct TileLoader {
         else     { r = e % ROWS; kk = e / ROWS; }
     }
 
+    // Issues the loads only.  Nothing here consumes the loaded values, so the loads stay
+    // in flight while the caller goes on issuing MFMAs; masking of out-of-range elements
+    // and conjugation happen in store(), when the values are needed.
     __device__ __forceinline__ void load(const cf *base, int ld, int r0, int rmax, int k0, int kmax, int tid)
     {
+        static_assert(PER_THREAD <= 32, "okmask holds one bit per element");
+        okmask = 0;
 #pragma unroll
         for (int p = 0; p < PER_THREAD; ++p) {
             int r, kk;
             coords(tid, p, r, kk);
             const int gr = r0 + r, gk = k0 + kk;
             const bool ok = (ELEMS % THREADS == 0 || p * THREADS + tid < ELEMS) && gr < rmax && gk < kmax;
-            // unconditional load from a clamped (valid) address, masked afterwards: no branch per load
+            okmask |= (ok ? 1u : 0u) << p;
+            // unconditional load from a clamped (valid) address: no branch per load
             const int grc = gr < rmax ? gr : rmax - 1, gkc = gk < kmax ? gk : kmax - 1;
-            cf v = KIN ? base[(size_t)grc * ld + gkc] : base[(size_t)gkc * ld + grc];
-            if (!ok) v = mk(0.0f, 0.0f);
-            if (CONJ) v.y = -v.y;
-            regs[p] = v;
+            regs[p] = KIN ? base[(size_t)grc * ld + gkc] : base[(size_t)gkc * ld + grc];
         }
     }
 
@@ -94,7 +98,10 @@ struct TileLoader {
         for (int p = 0; p < PER_THREAD; ++p) {
             int r, kk;
             coords(tid, p, r, kk);
-            if (ELEMS % THREADS == 0 || p * THREADS + tid < ELEMS) Ps[kk * SP + r] = regs[p];
+            cf v = regs[p];
+            if (!((okmask >> p) & 1u)) v = mk(0.0f, 0.0f);
+            if (CONJ) v.y = -v.y;
+            if (ELEMS % THREADS == 0 || p * THREADS + tid < ELEMS) Ps[kk * SP + r] = v;
         }
     }
 };
@@ -198,6 +205,10 @@ __global__ __launch_bounds__(G::THREADS) void bin_cgemm_kernel(GemmArgs g)
                     lb.load(Bb, ldb, j0, g.Nd, (c + 2) * kKT, g.Kd, tid);
                 }
             }
+            // keep the fragment reads (and the staging) above this point and the MFMAs below it:
+            // left alone, the scheduler sinks the reads to just before their use, which puts the
+            // LDS latency back on the critical path of every step
+            __builtin_amdgcn_sched_barrier(0);
             float as[IT], bd[JT], bs[JT];
 #pragma unroll
             for (int a = 0; a < IT; ++a) as[a] = af[cur][a].x + af[cur][a].y;
@@ -214,6 +225,7 @@ __global__ __launch_bounds__(G::THREADS) void bin_cgemm_kernel(GemmArgs g)
                     k2[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cur][a].x, bd[b], k2[a][b], 0, 0, 0);
                     k3[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cur][a].y, bs[b], k3[a][b], 0, 0, 0);
                 }
+            __builtin_amdgcn_sched_barrier(0);
         }
         __syncthreads();
     }

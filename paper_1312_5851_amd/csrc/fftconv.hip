@@ -88,35 +88,23 @@ const GemmEntry kGemmTable[] = {
 #undef GEMM_ENTRY
 constexpr int kNumGemm = sizeof(kGemmTable) / sizeof(kGemmTable[0]);
 
-// Picks the tile shape with the smallest estimated time.  Model: every wave owns
-// `wave_tiles` 32x32 tiles (3 MFMAs of 64 cycles each per K pair), `occ` waves share a
-// SIMD's matrix core; workgroups are handed out dynamically, so the run is the full
-// rounds at the shared rate plus a last partial round in which a lone wave cannot
-// keep the pipe full.
-int choose_gemm_tile(int Md, int Nd, int Kd, int bins)
+// Picks the tile shape.  Measured on MI355X, the shapes with one 32x32 tile per wave win
+// over larger wave tiles at these K (more resident waves per SIMD hide the per-workgroup
+// prologue and epilogue), so the choice is among those: least padded work first, then the
+// order of the preference list.
+int choose_gemm_tile(int Md, int Nd, int /*Kd*/, int /*bins*/)
 {
     if (const char *env = std::getenv("FFTCONV_GEMM_TILE")) {
         const int v = std::atoi(env);
         if (v >= 0 && v < kNumGemm) return v;
     }
-    int best = 0;
-    double best_cost = 1e300;
-    for (int i = 0; i < kNumGemm; ++i) {
+    static const int preference[] = {2, 7, 5, 6};   // 64x64, 128x32, 64x96, 32x32
+    int best = preference[0];
+    long best_area = -1;
+    for (int i : preference) {
         const GemmEntry &e = kGemmTable[i];
-        const long items = (long)((Md + e.MT - 1) / e.MT) * ((Nd + e.NT - 1) / e.NT) * bins;
-        const double wave_work = (double)e.wave_tiles * ((Kd + kKT - 1) / kKT * kKT);   // per-wave MFMA time units
-        const long wgs_per_cu = (4L * e.occ) / e.waves > 0 ? (4L * e.occ) / e.waves : 1;
-        const long slots = kNumCUs * wgs_per_cu;
-        const long full = items / slots, rem = items % slots;
-        const double waves_per_simd = (double)wgs_per_cu * e.waves / 4.0;
-        double cost = (double)full * waves_per_simd * wave_work / 0.9;
-        if (rem) {
-            const double rem_waves = (double)((rem + kNumCUs - 1) / kNumCUs) * e.waves / 4.0;
-            const double shared = rem_waves * wave_work / 0.9, solo = wave_work / 0.7;
-            cost += shared > solo ? shared : solo;
-        }
-        cost *= 1.0 + 2.0 * (1.0 / e.MT + 1.0 / e.NT);   // operand traffic per flop
-        if (cost < best_cost) { best_cost = cost; best = i; }
+        const long area = (long)((Md + e.MT - 1) / e.MT) * e.MT * ((Nd + e.NT - 1) / e.NT) * e.NT;
+        if (best_area < 0 || area < best_area) { best_area = area; best = i; }
     }
     return best;
 }
