@@ -72,6 +72,8 @@ def main():
     ap.add_argument("--workload", default="mid", help="layer name from paper_1312_5851_amd.workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stage-events", action="store_true", help="do not bracket kernels with HIP events")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy three times (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (every box has one); --gpus must be 1")
@@ -97,6 +99,15 @@ def main():
         plan.bprop(gd, wd, dx)
         plan.accgrad(gd, xd, dw)
 
+    if args.calibration_copy:
+        # a copy of known size in the same process: rocprofv3's FETCH_SIZE / WRITE_SIZE readings for
+        # it give the factor that turns the counters into bytes
+        src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
