@@ -181,10 +181,18 @@ __global__ __launch_bounds__(G::THREADS) void bin_cgemm_kernel(GemmArgs g)
         const cf *Af = lds + (c & 1) * G::STAGE + a_off;
         const cf *Bf = lds + (c & 1) * G::STAGE + b_off;
         cf af[2][IT], bf[2][JT];
+        float as[2][IT], bd[2][JT], bs[2][JT];   // ar + ai, bi - br, br + bi
 #pragma unroll
-        for (int a = 0; a < IT; ++a) af[0][a] = Af[a * 32];
+        for (int a = 0; a < IT; ++a) {
+            af[0][a] = Af[a * 32];
+            as[0][a] = af[0][a].x + af[0][a].y;
+        }
 #pragma unroll
-        for (int b = 0; b < JT; ++b) bf[0][b] = Bf[b * 32];
+        for (int b = 0; b < JT; ++b) {
+            bf[0][b] = Bf[b * 32];
+            bd[0][b] = bf[0][b].y - bf[0][b].x;
+            bs[0][b] = bf[0][b].x + bf[0][b].y;
+        }
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             const int cur = ks & 1, nxt = cur ^ 1;
@@ -205,26 +213,29 @@ __global__ __launch_bounds__(G::THREADS) void bin_cgemm_kernel(GemmArgs g)
                     lb.load(Bb, ldb, j0, g.Nd, (c + 2) * kKT, g.Kd, tid);
                 }
             }
-            // keep the fragment reads (and the staging) above this point and the MFMAs below it:
-            // left alone, the scheduler sinks the reads to just before their use, which puts the
-            // LDS latency back on the critical path of every step
+            // Order within a step: fragment reads (and staging) first, then this step's MFMAs,
+            // then the operand sums of the NEXT step.  Left alone, the scheduler sinks the reads to
+            // just before their use (LDS latency back on the critical path), and a sum computed right
+            // before the MFMA that consumes it holds up the matrix pipe.
             __builtin_amdgcn_sched_barrier(0);
-            float as[IT], bd[JT], bs[JT];
-#pragma unroll
-            for (int a = 0; a < IT; ++a) as[a] = af[cur][a].x + af[cur][a].y;
-#pragma unroll
-            for (int b = 0; b < JT; ++b) {
-                bd[b] = bf[cur][b].y - bf[cur][b].x;
-                bs[b] = bf[cur][b].x + bf[cur][b].y;
-            }
 #pragma unroll
             for (int a = 0; a < IT; ++a)
 #pragma unroll
                 for (int b = 0; b < JT; ++b) {
-                    k1[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(as[a], bf[cur][b].x, k1[a][b], 0, 0, 0);
-                    k2[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cur][a].x, bd[b], k2[a][b], 0, 0, 0);
-                    k3[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cur][a].y, bs[b], k3[a][b], 0, 0, 0);
+                    k1[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(as[cur][a], bf[cur][b].x, k1[a][b], 0, 0, 0);
+                    k2[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cur][a].x, bd[cur][b], k2[a][b], 0, 0, 0);
+                    k3[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cur][a].y, bs[cur][b], k3[a][b], 0, 0, 0);
                 }
+            __builtin_amdgcn_sched_barrier(0);
+            if (ks + 1 < KS) {
+#pragma unroll
+                for (int a = 0; a < IT; ++a) as[nxt][a] = af[nxt][a].x + af[nxt][a].y;
+#pragma unroll
+                for (int b = 0; b < JT; ++b) {
+                    bd[nxt][b] = bf[nxt][b].y - bf[nxt][b].x;
+                    bs[nxt][b] = bf[nxt][b].x + bf[nxt][b].y;
+                }
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
         __syncthreads();
