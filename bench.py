@@ -64,28 +64,13 @@ def cpu_baseline(layer, x, w, g, budget_s=18.0):
     }
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="mid", help="layer name from paper_1312_5851_amd.workloads")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-stage-events", action="store_true", help="do not bracket kernels with HIP events")
-    ap.add_argument("--calibration-copy", action="store_true",
-                    help="also run a plain 256 MiB device copy three times (reference for HBM byte counters)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py: this build runs on exactly one GPU (every box has one); --gpus must be 1")
-
+def measure(layer, args, inputs=None):
+    """Times args.steps steps of the whole hot path on one layer; returns the JSON record."""
     import torch
     from paper_1312_5851_amd import fftconv as fc
     from paper_1312_5851_amd import workloads as wl
 
-    if not torch.cuda.is_available():
-        sys.exit("bench.py: no GPU visible")
-    layer = wl.by_name(args.workload)
-    x, w, g = wl.make_inputs(layer)
+    x, w, g = inputs if inputs is not None else wl.make_inputs(layer)
     xd, wd, gd = (torch.from_numpy(a).cuda() for a in (x, w, g))
     plan = fc.Plan(layer.S, layer.f, layer.fo, layer.n, layer.k)
     plan.alloc_workspace()
@@ -214,10 +199,69 @@ def main():
         "stages": stage_report,
         "roofline": roofline,
     }
+    return out
+
+
+def write_report(args):
+    """Per-point numbers for every layer: ms per pass (warm / cold), direct-equivalent GFLOP/s, stage fractions."""
+    import copy
+    from paper_1312_5851_amd import workloads as wl
+    a = copy.copy(args)
+    a.steps, a.warmup, a.calibration_copy = 20, 3, False
+    layers = list(wl.CONFIGS.values()) + wl.sweep_layers() + wl.paper_table_layers()
+    recs = []
+    for layer in layers:
+        log(f"report: {layer.name}")
+        r = measure(layer, a)
+        r.pop("roofline", None)
+        recs.append(r)
+    json.dump(recs, open(args.report + ".json", "w"), indent=1)
+    lines = ["| layer | S,f,f',n,k | step ms | direct-equiv TFLOP/s (step) | fprop warm/cold ms | bprop warm/cold ms | "
+             "accGrad warm/cold ms | FFT stages % of 8 TB/s (x,w,g / y,dx,dw) | contraction % of 157.3 TFLOP/s (algorithmic) |",
+             "|---|---|---|---|---|---|---|---|---|"]
+    for layer, r in zip(layers, recs):
+        st, ps = r["stages"], r["passes"]
+        pct = lambda n: f"{100 * st[n].get('frac_hbm_peak', st[n].get('frac_mfma_peak', 0)):.0f}"
+        lines.append(f"| {layer.name} | {layer.S},{layer.f},{layer.fo},{layer.n},{layer.k} | {r['ms_per_step']:.3f} | "
+                     f"{r['value'] / 1e3:.1f} | " +
+                     " | ".join(f"{ps[p]['warm_ms']:.3f} / {ps[p]['cold_ms']:.3f}" for p in ("fprop", "bprop", "accgrad")) +
+                     f" | {pct('fft_x')},{pct('fft_w')},{pct('fft_g')} / {pct('ifft_y')},{pct('ifft_dx')},{pct('ifft_dw')} | "
+                     f"{pct('cgemm_fprop')},{pct('cgemm_bprop')},{pct('cgemm_accgrad')} |")
+    open(args.report + ".md", "w").write("\n".join(lines) + "\n")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="mid", help="layer name from paper_1312_5851_amd.workloads")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-stage-events", action="store_true", help="do not bracket kernels with HIP events")
+    ap.add_argument("--report", metavar="PATH", help="also measure BASELINE's four layers, the n x k sweep and the "
+                    "paper's table columns (fewer steps each) and write PATH.json and PATH.md")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy three times (reference for HBM byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (every box has one); --gpus must be 1")
+
+    import torch
+    from paper_1312_5851_amd import fftconv as fc
+    from paper_1312_5851_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    layer = wl.by_name(args.workload)
+    inputs = wl.make_inputs(layer)
+    out = measure(layer, args, inputs)
+    x, w, g = inputs
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a bounded sample ...")
         out["cpu_baseline"] = cpu_baseline(layer, x, w, g)
     print(json.dumps(out), flush=True)
+    if args.report:
+        write_report(args)
 
 
 if __name__ == "__main__":

@@ -105,6 +105,37 @@ def test_sampled_parity_full_size(fc, name):
     assert abs(a - b) <= 1e-5 * scale and abs(a - c) <= 1e-5 * scale
 
 
+def sampled_check(fc, layer, counts):
+    x, w, g = wl.make_inputs(layer)
+    plan, y, dx, dw = run_three(fc, layer, x, w, g)
+    S, f, fo, n, k, no = layer.S, layer.f, layer.fo, layer.n, layer.k, layer.no
+    u = wl.sample_units(S * fo, counts[0], layer.seed)
+    check(y.reshape(S * fo, no, no)[u], direct.fprop(x, w, u), f"{layer.name} fprop sample")
+    u = wl.sample_units(S * f, counts[1], layer.seed + 1)
+    check(dx.reshape(S * f, n, n)[u], direct.bprop(g, w, n, u), f"{layer.name} bprop sample")
+    u = wl.sample_units(fo * f, counts[2], layer.seed + 2)
+    check(dw.reshape(fo * f, k, k)[u], direct.accgrad(g, x, k, u), f"{layer.name} accgrad sample")
+
+
+@pytest.mark.parametrize("name", ["sweep_n16_k13", "sweep_n32_k11", "sweep_n64_k3", "sweep_n64_k13"])
+def test_sampled_parity_sweep_corners(fc, name):
+    """Corners of the n x k sweep (S=128, f=f'=256) at full size; the oracle evaluates a seeded
+    sample of whole output maps / kernels, sized so that each pass compares >= 1e4 elements."""
+    layer = wl.by_name(name)
+    print(f"\ncase {layer}", flush=True)
+    per_unit = (layer.no ** 2, layer.n ** 2, layer.k ** 2)
+    counts = tuple(max(8, min(96, -(-10000 // e))) for e in per_unit)
+    sampled_check(fc, layer, counts)
+
+
+@pytest.mark.parametrize("idx", range(5))
+def test_sampled_parity_paper_table_columns(fc, idx):
+    """The five (k, n, f, f') columns of the paper's per-layer timing table at S=128."""
+    layer = wl.paper_table_layers()[idx]
+    print(f"\ncase {layer}", flush=True)
+    sampled_check(fc, layer, (64, 64, 96))
+
+
 def test_spectrum_stage_against_fft2(fc):
     """Forward stage alone: slot contents equal the half spectrum of the zero-padded maps."""
     layer = wl.Layer("stage", 3, 5, 4, 20, 6, 0.1, 31)
