@@ -84,14 +84,19 @@ const GemmEntry kGemmTable[] = {
     GEMM_ENTRY(2, 1, 2, 1, 3),   //  8: 128 x  32 (64 x 32 per wave)
     GEMM_ENTRY(2, 2, 2, 2, 1),   //  9: 128 x 128
     GEMM_ENTRY(1, 3, 2, 1, 2),   // 10:  64 x  96 (32 x 96 per wave)
+    GEMM_ENTRY(1, 1, 4, 2, 4),   // 11: 128 x  64, 8 waves
+    GEMM_ENTRY(1, 1, 2, 4, 4),   // 12:  64 x 128, 8 waves
+    GEMM_ENTRY(1, 1, 4, 4, 4),   // 13: 128 x 128, 16 waves
+    GEMM_ENTRY(1, 1, 4, 3, 4),   // 14: 128 x  96, 12 waves
 };
 #undef GEMM_ENTRY
 constexpr int kNumGemm = sizeof(kGemmTable) / sizeof(kGemmTable[0]);
 
-// Picks the tile shape.  Measured on MI355X, the shapes with one 32x32 tile per wave win
-// over larger wave tiles at these K (more resident waves per SIMD hide the per-workgroup
-// prologue and epilogue), so the choice is among those: least padded work first, then the
-// order of the preference list.
+// Picks the tile shape.  Measured inside the full step on MI355X (operands coming from HBM,
+// not from a cache warmed by the previous launch), the 4-wave shapes with one 32x32 tile per
+// wave win over larger wave tiles and over 8- or 16-wave workgroups at these K: more
+// independent workgroups per CU hide the per-tile prologue, epilogue and barrier waits.
+// So the choice is among those: least padded work first, then the preference order.
 int choose_gemm_tile(int Md, int Nd, int /*Kd*/, int /*bins*/)
 {
     if (const char *env = std::getenv("FFTCONV_GEMM_TILE")) {
