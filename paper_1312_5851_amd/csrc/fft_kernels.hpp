@@ -28,11 +28,15 @@
 //            window, scaled by 1/N^2.
 //
 // Between the phases the data sits in LDS as lds[r][x][m] (m fastest) with
-// strides padded so that both phases touch distinct banks.
+// strides padded so that both phases touch distinct banks.  With ROUNDS = 2 the
+// rows go through LDS in two halves (the y-phase keeps its column in registers
+// and hands over rows [0, N/4) first, then [N/4, N/2); half of the lanes run the
+// x-phase of each half): LDS per workgroup halves, which at N = 64 is what lets
+// two workgroups share a CU so that one's loads overlap the other's arithmetic.
 //
-// Each phase is a plain function of (thread id, block id): the device kernels
-// call them around __syncthreads(), and a host build replays them in loops to
-// check the index arithmetic without a GPU.
+// Each phase step is a plain function of (thread id, block id, per-lane state):
+// the device kernels call them around __syncthreads(), and a host build replays
+// them in loops to check the index arithmetic without a GPU.
 #pragma once
 #include "fft_core.hpp"
 
@@ -53,84 +57,105 @@ struct InvArgs {
     float scale;        // 1 / N^2
 };
 
-template <int N_, int T_, int NX_>
+template <int N_, int T_, int NX_, int ROUNDS_ = 1>
 struct TileGeom {
     static constexpr int N = N_;     // transform size
     static constexpr int T = T_;     // maps per workgroup (even)
     static constexpr int NX = NX_;   // columns that can be non-zero (forward) / are needed (inverse)
+    static constexpr int ROUNDS = ROUNDS_;             // LDS hand-overs between the phases
     static constexpr int ROWS = N / 2;                 // packed row 0 + rows 1..N/2-1
-    static constexpr int THREADS = T * ROWS;           // one lane per (row, map) in the x-phase
+    static constexpr int RPR = ROWS / ROUNDS;          // rows per round
+    static constexpr int THREADS = T * ROWS;           // lanes per workgroup
+    static constexpr int XTHREADS = T * RPR;           // lanes active in one round of the x-phase: (row, map)
     static constexpr int SX = T + 1;                   // complex elements between consecutive x
     static constexpr int SR_BASE = NX * SX;
     // row stride: congruent to T modulo 32 complex (= 64 dwords) so that the row groups
     // sharing a half-wave in the x-phase start T complex apart in bank space
     static constexpr int SR = SR_BASE + ((((T - SR_BASE) % 32) + 32) % 32);
-    static constexpr int LDS_ELEMS = ROWS * SR;
+    static constexpr int LDS_ELEMS = RPR * SR;
     static constexpr int LDS_BYTES = LDS_ELEMS * 8;
-    static constexpr int YITEMS = (T / 2) * NX;        // work items of the y-phase
+    static constexpr int YITEMS = (T / 2) * NX;        // lanes active in the y-phase: (map pair, column)
+    // waves per SIMD the register allocation should allow (what LDS lets a CU hold):
+    // N = 64 needs 128 registers for one transform alone, so two; N = 32 fits four
+    static constexpr int WAVES_PER_SIMD = N >= 64 ? 2 : (N == 32 && ROUNDS == 2 ? 4 : 1);
     static_assert(T % 2 == 0, "maps are processed in pairs");
     static_assert(NX <= N, "extent class cannot exceed the transform size");
+    static_assert(ROWS % ROUNDS == 0 && YITEMS <= THREADS, "geometry");
 };
 
 // ------------------------------------------------------------------ forward
 
+// y-phase, step 1: load the two columns of a map pair, transform along y.  Leaves the
+// bit-reversed transform in z.  Returns false for lanes without a column.
 template <class G>
-FC_HD void fwd_phase_y(int tid, int blk, const FwdArgs &a, cf *lds)
+FC_HD bool fwd_y_compute(int tid, int blk, const FwdArgs &a, cf (&z)[G::N])
 {
     constexpr int N = G::N, NX = G::NX;
-    const int m0 = blk * G::T;
-    for (int item = tid; item < G::YITEMS; item += G::THREADS) {
-        const int p = item / NX, x = item % NX;
-        const int ma = m0 + 2 * p, mb = ma + 1;
-        // Loads are unconditional from clamped (always valid) addresses and masked
-        // afterwards, so that they issue back to back; rows beyond the extent are
-        // skipped by a wave-uniform branch.
-        const bool va = (ma < a.M) && (x < a.ext), vb = (mb < a.M) && (x < a.ext);
-        const int xc = x < a.ext ? x : a.ext - 1;
-        const int mac = ma < a.M ? ma : a.M - 1, mbc = mb < a.M ? mb : a.M - 1;
-        const float *pa = a.src + ((size_t)mac * a.ext) * a.ext + xc;
-        const float *pb = a.src + ((size_t)mbc * a.ext) * a.ext + xc;
-        float fa[NX], fb[NX];
-        static_for<0, NX>([&](auto yi) {
-            constexpr int y = decltype(yi)::value;
-            if (y < a.ext) {
-                fa[y] = pa[y * a.ext];
-                fb[y] = pb[y * a.ext];
-            } else {
-                fa[y] = 0.0f;
-                fb[y] = 0.0f;
-            }
-        });
-        cf z[N];
-        static_for<0, NX>([&](auto yi) {
-            constexpr int y = decltype(yi)::value;
-            z[y] = mk(va ? fa[y] : 0.0f, vb ? fb[y] : 0.0f);
-        });
-        fft_dif<N, false, ~low_mask(NX)>(z);
-        cf *base = lds + x * G::SX + 2 * p;
-        {   // packed row 0: (ky = 0, ky = N/2), both real for a real map
+    if (tid >= G::YITEMS) return false;
+    const int p = tid / NX, x = tid % NX;
+    const int ma = blk * G::T + 2 * p, mb = ma + 1;
+    // Loads are unconditional from clamped (always valid) addresses and masked
+    // afterwards, so that they issue back to back; rows beyond the extent are
+    // skipped by a wave-uniform branch.
+    const bool va = (ma < a.M) && (x < a.ext), vb = (mb < a.M) && (x < a.ext);
+    const int xc = x < a.ext ? x : a.ext - 1;
+    const int mac = ma < a.M ? ma : a.M - 1, mbc = mb < a.M ? mb : a.M - 1;
+    const float *pa = a.src + ((size_t)mac * a.ext) * a.ext + xc;
+    const float *pb = a.src + ((size_t)mbc * a.ext) * a.ext + xc;
+    float fa[NX], fb[NX];
+    static_for<0, NX>([&](auto yi) {
+        constexpr int y = decltype(yi)::value;
+        if (y < a.ext) {
+            fa[y] = pa[y * a.ext];
+            fb[y] = pb[y * a.ext];
+        } else {
+            fa[y] = 0.0f;
+            fb[y] = 0.0f;
+        }
+    });
+    static_for<0, NX>([&](auto yi) {
+        constexpr int y = decltype(yi)::value;
+        z[y] = mk(va ? fa[y] : 0.0f, vb ? fb[y] : 0.0f);
+    });
+    fft_dif<N, false, ~low_mask(NX)>(z);
+    return true;
+}
+
+// y-phase, step 2: split the packed transform into the two maps' half spectra and hand
+// rows [round * RPR, (round + 1) * RPR) to LDS.
+template <class G, int ROUND>
+FC_HD void fwd_y_write(int tid, const cf (&z)[G::N], cf *lds)
+{
+    constexpr int N = G::N, NX = G::NX;
+    const int p = tid / NX, x = tid % NX;
+    cf *base = lds + x * G::SX + 2 * p;
+    static_for<ROUND * G::RPR, (ROUND + 1) * G::RPR>([&](auto ri) {
+        constexpr int r = decltype(ri)::value;
+        constexpr int slot = r - ROUND * G::RPR;
+        if constexpr (r == 0) {   // packed row 0: (ky = 0, ky = N/2), both real for a real map
             const cf z0 = z[brev<N>(0)], zh = z[brev<N>(N / 2)];
             base[0] = mk(z0.x, zh.x);
             base[1] = mk(z0.y, zh.y);
-        }
-        static_for<1, N / 2>([&](auto ri) {
-            constexpr int r = decltype(ri)::value;
+        } else {
             const cf zk = z[brev<N>(r)], zn = z[brev<N>(N - r)];
             // A = (Z[k] + conj Z[N-k]) / 2,  B = (Z[k] - conj Z[N-k]) / (2i)
-            base[r * G::SR + 0] = mk(0.5f * (zk.x + zn.x), 0.5f * (zk.y - zn.y));
-            base[r * G::SR + 1] = mk(0.5f * (zk.y + zn.y), 0.5f * (zn.x - zk.x));
-        });
-    }
+            base[slot * G::SR + 0] = mk(0.5f * (zk.x + zn.x), 0.5f * (zk.y - zn.y));
+            base[slot * G::SR + 1] = mk(0.5f * (zk.y + zn.y), 0.5f * (zn.x - zk.x));
+        }
+    });
 }
 
+// x-phase of one round: transform a row of one map along x, store bin-major.
 template <class G>
-FC_HD void fwd_phase_x(int tid, int blk, const FwdArgs &a, const cf *lds)
+FC_HD void fwd_x(int tid, int blk, int round, const FwdArgs &a, const cf *lds)
 {
     constexpr int N = G::N, NX = G::NX;
-    const int r = tid / G::T, m = tid % G::T;
+    if (tid >= G::XTHREADS) return;
+    const int slot = tid / G::T, m = tid % G::T;
+    const int r = round * G::RPR + slot;
     const int mg = blk * G::T + m;
     cf v[N];
-    const cf *base = lds + r * G::SR + m;
+    const cf *base = lds + slot * G::SR + m;
     static_for<0, NX>([&](auto xi) {
         constexpr int x = decltype(xi)::value;
         v[x] = base[x * G::SX];
@@ -158,11 +183,15 @@ FC_HD void fwd_phase_x(int tid, int blk, const FwdArgs &a, const cf *lds)
 
 // ------------------------------------------------------------------ inverse
 
+// x-phase of one round: load a row of one map's spectrum, inverse transform along kx,
+// hand the needed columns to LDS.
 template <class G>
-FC_HD void inv_phase_x(int tid, int blk, const InvArgs &a, cf *lds)
+FC_HD void inv_x(int tid, int blk, int round, const InvArgs &a, cf *lds)
 {
     constexpr int N = G::N, NX = G::NX;
-    const int r = tid / G::T, m = tid % G::T;
+    if (tid >= G::XTHREADS) return;
+    const int slot = tid / G::T, m = tid % G::T;
+    const int r = round * G::RPR + slot;
     const int mg = blk * G::T + m;
     // Lanes beyond the last map read the last map's bins (valid memory) instead of
     // branching around each load; what they compute is never stored.
@@ -192,10 +221,34 @@ FC_HD void inv_phase_x(int tid, int blk, const InvArgs &a, cf *lds)
         });
     }
     fft_dif<N, true, 0, first_outputs_mask<N>(NX)>(v);
-    cf *base = lds + r * G::SR + m;
+    cf *base = lds + slot * G::SR + m;
     static_for<0, NX>([&](auto xi) {
         constexpr int x = decltype(xi)::value;
         base[x * G::SX] = v[brev<N>(x)];
+    });
+}
+
+// y-phase, step 1 (per round): collect rows [round * RPR, (round + 1) * RPR) of the map pair's
+// column from LDS into the packed spectrum z (natural order).
+template <class G, int ROUND>
+FC_HD void inv_y_gather(int tid, const cf *lds, cf (&z)[G::N])
+{
+    constexpr int N = G::N, NX = G::NX;
+    if (tid >= G::YITEMS) return;
+    const int p = tid / NX, x = tid % NX;
+    const cf *base = lds + x * G::SX + 2 * p;
+    static_for<ROUND * G::RPR, (ROUND + 1) * G::RPR>([&](auto ri) {
+        constexpr int r = decltype(ri)::value;
+        constexpr int slot = r - ROUND * G::RPR;
+        if constexpr (r == 0) {
+            const cf ra = base[0], rb = base[1];    // (row 0, row N/2) of map a / map b, all real
+            z[0] = mk(ra.x, rb.x);
+            z[N / 2] = mk(ra.y, rb.y);
+        } else {
+            const cf A = base[slot * G::SR + 0], B = base[slot * G::SR + 1];
+            z[r] = mk(A.x - B.y, A.y + B.x);        // A + i B
+            z[N - r] = mk(A.x + B.y, B.x - A.y);    // conj A + i conj B
+        }
     });
 }
 
@@ -221,59 +274,70 @@ FC_HD void store_column(float *col, bool valid, const InvArgs &a, Get &&get)
     });
 }
 
+// y-phase, step 2: inverse transform along y of the packed pair, store the cropped columns.
 template <class G, bool ACC>
-FC_HD void inv_phase_y(int tid, int blk, const InvArgs &a, const cf *lds)
+FC_HD void inv_y_finish(int tid, int blk, const InvArgs &a, cf (&z)[G::N])
 {
     constexpr int N = G::N, NX = G::NX;
-    const int m0 = blk * G::T;
-    for (int item = tid; item < G::YITEMS; item += G::THREADS) {
-        const int p = item / NX, x = item % NX;
-        const int ma = m0 + 2 * p, mb = ma + 1;
-        const cf *base = lds + x * G::SX + 2 * p;
-        cf z[N];
-        {
-            const cf ra = base[0], rb = base[1];    // (row 0, row N/2) of map a / map b, all real
-            z[0] = mk(ra.x, rb.x);
-            z[N / 2] = mk(ra.y, rb.y);
-        }
-        static_for<1, N / 2>([&](auto ri) {
-            constexpr int r = decltype(ri)::value;
-            const cf A = base[r * G::SR + 0], B = base[r * G::SR + 1];
-            z[r] = mk(A.x - B.y, A.y + B.x);        // A + i B
-            z[N - r] = mk(A.x + B.y, B.x - A.y);    // conj A + i conj B
-        });
-        fft_dif<N, true, 0, first_outputs_mask<N>(NX)>(z);
-        if (x >= a.crop) continue;
-        store_column<G, ACC>(a.dst + ((size_t)ma * a.crop) * a.crop + x, ma < a.M, a, [&](auto yi) {
-            return z[brev<N>(decltype(yi)::value)].x;
-        });
-        store_column<G, ACC>(a.dst + ((size_t)mb * a.crop) * a.crop + x, mb < a.M, a, [&](auto yi) {
-            return z[brev<N>(decltype(yi)::value)].y;
-        });
+    if (tid >= G::YITEMS) return;
+    const int p = tid / NX, x = tid % NX;
+    const int ma = blk * G::T + 2 * p, mb = ma + 1;
+    fft_dif<N, true, 0, first_outputs_mask<N>(NX)>(z);
+    if (x >= a.crop) return;
+    store_column<G, ACC>(a.dst + ((size_t)ma * a.crop) * a.crop + x, ma < a.M, a, [&](auto yi) {
+        return z[brev<N>(decltype(yi)::value)].x;
+    });
+    store_column<G, ACC>(a.dst + ((size_t)mb * a.crop) * a.crop + x, mb < a.M, a, [&](auto yi) {
+        return z[brev<N>(decltype(yi)::value)].y;
+    });
+}
+
+// The order of steps and barriers of one workgroup, shared by the device kernels and the
+// host replay.  `Sync` is __syncthreads() on the device; the host replay runs every step for
+// all lanes before the next one, which is what a barrier after each step guarantees.
+//   forward: y_compute | round 0: y_write, barrier, x | round 1: barrier, y_write, barrier, x
+//   inverse: round 0: x, barrier, y_gather | round 1: barrier, x, barrier, y_gather | y_finish
+
+#if defined(__HIPCC__)
+// Device kernels.  Launch with G::THREADS threads, ceil(M / G::T) blocks and G::LDS_BYTES
+// of dynamic LDS.
+// (the second launch bound is the number of waves per SIMD the register budget must allow)
+template <class G>
+__global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void fft2d_r2c_kernel(FwdArgs a)
+{
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    cf *lds = reinterpret_cast<cf *>(lds_raw);
+    const int tid = (int)threadIdx.x, blk = (int)blockIdx.x;
+    cf z[G::N];
+    const bool has = fwd_y_compute<G>(tid, blk, a, z);
+    if (has) fwd_y_write<G, 0>(tid, z, lds);
+    __syncthreads();
+    fwd_x<G>(tid, blk, 0, a, lds);
+    if constexpr (G::ROUNDS == 2) {
+        __syncthreads();
+        if (has) fwd_y_write<G, 1>(tid, z, lds);
+        __syncthreads();
+        fwd_x<G>(tid, blk, 1, a, lds);
     }
 }
 
-#if defined(__HIPCC__)
-// Device kernels: the two phases around one workgroup barrier.  Launch with
-// G::THREADS threads, ceil(M / G::T) blocks and G::LDS_BYTES of dynamic LDS.
-template <class G>
-__global__ __launch_bounds__(G::THREADS) void fft2d_r2c_kernel(FwdArgs a)
-{
-    extern __shared__ __align__(16) unsigned char lds_raw[];
-    cf *lds = reinterpret_cast<cf *>(lds_raw);
-    fwd_phase_y<G>((int)threadIdx.x, (int)blockIdx.x, a, lds);
-    __syncthreads();
-    fwd_phase_x<G>((int)threadIdx.x, (int)blockIdx.x, a, lds);
-}
-
 template <class G, bool ACC>   // ACC: dst += result instead of dst = result
-__global__ __launch_bounds__(G::THREADS) void ifft2d_c2r_crop_kernel(InvArgs a)
+__global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void ifft2d_c2r_crop_kernel(InvArgs a)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     cf *lds = reinterpret_cast<cf *>(lds_raw);
-    inv_phase_x<G>((int)threadIdx.x, (int)blockIdx.x, a, lds);
+    const int tid = (int)threadIdx.x, blk = (int)blockIdx.x;
+    cf z[G::N];
+    inv_x<G>(tid, blk, 0, a, lds);
     __syncthreads();
-    inv_phase_y<G, ACC>((int)threadIdx.x, (int)blockIdx.x, a, lds);
+    inv_y_gather<G, 0>(tid, lds, z);
+    if constexpr (G::ROUNDS == 2) {
+        __syncthreads();
+        inv_x<G>(tid, blk, 1, a, lds);
+        __syncthreads();
+        inv_y_gather<G, 1>(tid, lds, z);
+    }
+    inv_y_finish<G, ACC>(tid, blk, a, z);
 }
 #endif
 

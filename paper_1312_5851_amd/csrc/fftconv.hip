@@ -42,9 +42,10 @@ struct FftEntry {
 };
 
 #define X(n_, t_, nx_)                                                                          \
-    {n_, t_, nx_, TileGeom<n_, t_, nx_>::THREADS, TileGeom<n_, t_, nx_>::LDS_BYTES,              \
-     fft2d_r2c_kernel<TileGeom<n_, t_, nx_>>, ifft2d_c2r_crop_kernel<TileGeom<n_, t_, nx_>, false>,   \
-     ifft2d_c2r_crop_kernel<TileGeom<n_, t_, nx_>, true>},
+    {n_, t_, nx_, TileGeom<n_, t_, nx_, rounds_for(n_)>::THREADS, TileGeom<n_, t_, nx_, rounds_for(n_)>::LDS_BYTES, \
+     fft2d_r2c_kernel<TileGeom<n_, t_, nx_, rounds_for(n_)>>,                                    \
+     ifft2d_c2r_crop_kernel<TileGeom<n_, t_, nx_, rounds_for(n_)>, false>,                       \
+     ifft2d_c2r_crop_kernel<TileGeom<n_, t_, nx_, rounds_for(n_)>, true>},
 const FftEntry kFftTable[] = {FFTCONV_FOR_EACH_GEOM(X)};
 #undef X
 
