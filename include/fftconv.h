@@ -135,12 +135,14 @@ int fftconv_inverse_transform(fftconv_plan_t p, int pass, float *dst, void *ws, 
 
 /* ---- stage timing ------------------------------------------------------- */
 
-/* When enabled, every kernel launch is bracketed by HIP events on the launch
- * stream (up to 4096 launches between reads).  fftconv_profile_read waits for
- * the recorded events, adds each stage's elapsed milliseconds and launch count
- * into the caller's arrays of FFTCONV_NUM_STAGES entries (host memory), and
- * clears the record. */
-int fftconv_profile_enable(fftconv_plan_t p, int enable);
+/* Launches of the stages selected by `stage_mask` (bit s = stage s of the list above,
+ * FFTCONV_PROFILE_ALL = every stage, 0 = none) are bracketed by HIP events on the launch
+ * stream (up to 4096 launches between reads; a bracket costs a few microseconds of queue
+ * time).  fftconv_profile_read waits for the recorded events, adds each stage's elapsed
+ * milliseconds and launch count into the caller's arrays of FFTCONV_NUM_STAGES entries
+ * (host memory), and clears the record. */
+#define FFTCONV_PROFILE_ALL 0x1ffu
+int fftconv_profile_enable(fftconv_plan_t p, unsigned stage_mask);
 int fftconv_profile_read(fftconv_plan_t p, double *ms_sum, long *launches);
 
 /* ---- helpers ------------------------------------------------------------ */

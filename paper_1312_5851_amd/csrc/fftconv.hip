@@ -125,7 +125,7 @@ struct fftconv_plan_s {
     unsigned valid;
     void *last_ws;
     int gemm_tile[3];
-    bool profiling;
+    unsigned profiling;   // stage mask
     std::vector<ProfileRecord> records;
     std::vector<hipEvent_t> free_events;
 };
@@ -140,7 +140,7 @@ struct StageTimer {
     int status;
     StageTimer(fftconv_plan_t p_, int stage, hipStream_t s) : p(p_), stream(s), stop(nullptr), active(false), status(FFTCONV_OK)
     {
-        if (!p->profiling || (int)p->records.size() >= kMaxProfileRecords) return;
+        if (((p->profiling >> stage) & 1u) == 0 || (int)p->records.size() >= kMaxProfileRecords) return;
         hipEvent_t ev[2];
         for (int i = 0; i < 2; ++i) {
             if (!p->free_events.empty()) {
@@ -319,7 +319,7 @@ int fftconv_plan(fftconv_plan_t *out, const fftconv_desc *d)
     p->ws_bytes = p->off_out + align_up(per_map * p->maps_out);
     p->valid = 0;
     p->last_ws = nullptr;
-    p->profiling = false;
+    p->profiling = 0;
     for (int pass = 0; pass < 3; ++pass) {
         int Md, Nd, Kd, sa, sb;
         pass_dims(p, pass, Md, Nd, Kd, sa, sb);
@@ -415,10 +415,10 @@ int fftconv_inverse_transform(fftconv_plan_t p, int pass, float *dst, void *ws, 
     return launch_inverse(p, pass, dst, ws, static_cast<hipStream_t>(stream), accumulate);
 }
 
-int fftconv_profile_enable(fftconv_plan_t p, int enable)
+int fftconv_profile_enable(fftconv_plan_t p, unsigned stage_mask)
 {
-    if (!p) return FFTCONV_EINVAL;
-    p->profiling = enable != 0;
+    if (!p || (stage_mask & ~FFTCONV_PROFILE_ALL) != 0) return FFTCONV_EINVAL;
+    p->profiling = stage_mask;
     return FFTCONV_OK;
 }
 

@@ -19,6 +19,7 @@ FFTCONV_OK = 0
 SPEC_X, SPEC_W, SPEC_G, SPEC_OUT = 1, 2, 4, 8
 FPROP, BPROP, ACCGRAD = 0, 1, 2
 NUM_STAGES = 9
+PROFILE_ALL = 0x1FF
 STAGE_NAMES = ("fft_x", "fft_w", "fft_g", "cgemm_fprop", "cgemm_bprop", "cgemm_accgrad",
                "ifft_y", "ifft_dx", "ifft_dw")
 
@@ -65,7 +66,7 @@ def _load() -> ctypes.CDLL:
         "fftconv_forward_transform": (ip, [vp, ip, vp, vp, vp]),
         "fftconv_contract": (ip, [vp, ip, vp, vp]),
         "fftconv_inverse_transform": (ip, [vp, ip, vp, vp, vp, ip]),
-        "fftconv_profile_enable": (ip, [vp, ip]),
+        "fftconv_profile_enable": (ip, [vp, ctypes.c_uint]),
         "fftconv_profile_read": (ip, [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_long)]),
         "fftconv_strerror": (ctypes.c_char_p, [ip]),
         "fftconv_paper_ram_bytes": (sz, [ip, ip, ip, ip]),
@@ -209,8 +210,15 @@ class Plan:
                                               1 if accumulate else 0), "fftconv_inverse_transform")
 
     # -- stage timing --------------------------------------------------------
-    def profile_enable(self, on: bool = True):
-        _check(_lib.fftconv_profile_enable(self._h, 1 if on else 0), "fftconv_profile_enable")
+    def profile_enable(self, stages=True):
+        """stages: True (all), False (none) or an iterable of stage names to bracket with events."""
+        if stages is True:
+            mask = PROFILE_ALL
+        elif not stages:
+            mask = 0
+        else:
+            mask = sum(1 << STAGE_NAMES.index(s) for s in stages)
+        _check(_lib.fftconv_profile_enable(self._h, mask), "fftconv_profile_enable")
 
     def profile_read(self):
         """Returns {stage name: (total ms, launches)} since the last read."""
