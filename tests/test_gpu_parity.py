@@ -136,6 +136,92 @@ def test_sampled_parity_paper_table_columns(fc, idx):
     sampled_check(fc, layer, (64, 64, 96))
 
 
+EDGE_LAYERS = [
+    wl.Layer("n64_k1", 2, 3, 2, 64, 1, 0.1, 61),          # largest transform, k = 1
+    wl.Layer("n64_k64", 2, 2, 3, 64, 64, 0.05, 62),       # k = n = 64: one output pixel
+    wl.Layer("n33", 2, 3, 2, 33, 2, 0.1, 63),             # just above 32 -> N = 64 with a lot of padding
+    wl.Layer("n17_k17", 3, 2, 2, 17, 17, 0.1, 64),        # N = 32, k = n
+    wl.Layer("n8_k3", 5, 3, 4, 8, 3, 0.1, 65),            # N = 8
+    wl.Layer("n5_k2", 3, 2, 2, 5, 2, 0.1, 66),            # n below the smallest transform
+    wl.Layer("n1", 4, 3, 2, 1, 1, 0.1, 67),               # 1x1 maps
+    wl.Layer("S1_f1", 1, 1, 5, 20, 7, 0.1, 68),
+    wl.Layer("many_maps_tail", 7, 37, 41, 32, 3, 0.05, 69),   # map counts 259 / 1517 / 287: ragged FFT tiles
+    wl.Layer("gemm_tails", 130, 65, 97, 16, 3, 0.05, 70),     # every GEMM dimension one past a tile multiple
+]
+
+
+@pytest.mark.parametrize("layer", EDGE_LAYERS, ids=lambda l: l.name)
+def test_full_parity_edge_shapes(fc, layer):
+    print(f"\ncase {layer}", flush=True)
+    x, w, g = wl.make_inputs(layer)
+    plan, y, dx, dw = run_three(fc, layer, x, w, g)
+    check(y, direct.fprop(x, w), f"{layer.name} fprop")
+    check(dx, direct.bprop(g, w, layer.n), f"{layer.name} bprop")
+    check(dw, direct.accgrad(g, x, layer.k), f"{layer.name} accgrad")
+
+
+def test_outputs_have_no_stray_writes(fc):
+    """Each pass writes exactly its output tensor: guard bands around y, dx, dw stay untouched."""
+    layer = wl.Layer("guards", 3, 5, 7, 29, 6, 0.05, 71)
+    x, w, g = wl.make_inputs(layer)
+    plan = fc.Plan(layer.S, layer.f, layer.fo, layer.n, layer.k)
+    xd, wd, gd = dev(x), dev(w), dev(g)
+    G = 4096
+    outs = []
+    for shape in (layer.shapes()[2], layer.shapes()[0], layer.shapes()[1]):
+        numel = int(np.prod(shape))
+        buf = torch.full((numel + 2 * G,), 12345.0, dtype=torch.float32, device="cuda")
+        outs.append((buf, buf[G:G + numel].view(shape)))
+    plan.fprop(xd, wd, outs[0][1])
+    plan.bprop(gd, wd, outs[1][1])
+    plan.accgrad(gd, xd, outs[2][1])
+    torch.cuda.synchronize()
+    for buf, view in outs:
+        assert torch.all(buf[:G] == 12345.0) and torch.all(buf[-G:] == 12345.0)
+        assert not torch.any(view == 12345.0)
+    check(outs[0][1].cpu().numpy(), direct.fprop(x, w), "guards fprop")
+    check(outs[1][1].cpu().numpy(), direct.bprop(g, w, layer.n), "guards bprop")
+    check(outs[2][1].cpu().numpy(), direct.accgrad(g, x, layer.k), "guards accgrad")
+
+
+def test_passes_in_any_order_and_on_a_side_stream(fc):
+    """accGrad first (transforms g and x), then bprop (reuses g), then fprop (reuses x and w),
+    all enqueued on a non-default stream."""
+    layer = wl.Layer("order", 6, 10, 12, 16, 5, 0.05, 72)
+    x, w, g = wl.make_inputs(layer)
+    plan = fc.Plan(layer.S, layer.f, layer.fo, layer.n, layer.k)
+    xd, wd, gd = dev(x), dev(w), dev(g)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        plan.alloc_workspace()
+        dw = plan.accgrad(gd, xd)
+        assert plan.valid_slots() == fc.SPEC_G | fc.SPEC_X
+        dx = plan.bprop(gd, wd)
+        y = plan.fprop(xd, wd)
+        assert plan.valid_slots() == fc.SPEC_G | fc.SPEC_X | fc.SPEC_W
+    side.synchronize()
+    check(y.cpu().numpy(), direct.fprop(x, w), "order fprop")
+    check(dx.cpu().numpy(), direct.bprop(g, w, layer.n), "order bprop")
+    check(dw.cpu().numpy(), direct.accgrad(g, x, layer.k), "order accgrad")
+
+
+def test_stage_calls_compose_to_a_pass(fc):
+    layer = wl.Layer("stages", 4, 6, 5, 32, 7, 0.05, 73)
+    x, w, g = wl.make_inputs(layer)
+    plan = fc.Plan(layer.S, layer.f, layer.fo, layer.n, layer.k)
+    xd, wd = dev(x), dev(w)
+    plan.forward_transform(fc.SPEC_X, xd)
+    plan.forward_transform(fc.SPEC_W, wd)
+    plan.contract(fc.FPROP)
+    y = torch.empty(layer.shapes()[2], dtype=torch.float32, device="cuda")
+    plan.inverse_transform(fc.FPROP, y)
+    y2 = plan.fprop(xd, wd)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2)
+    check(y.cpu().numpy(), direct.fprop(x, w), "stages fprop")
+
+
 def test_spectrum_stage_against_fft2(fc):
     """Forward stage alone: slot contents equal the half spectrum of the zero-padded maps."""
     layer = wl.Layer("stage", 3, 5, 4, 20, 6, 0.1, 31)
