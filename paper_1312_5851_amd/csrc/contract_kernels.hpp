@@ -116,11 +116,13 @@ struct GemmTile {
     static constexpr int STAGE = kKT * (SA + SB);       // complex elements of one chunk (A then B)
     static constexpr int LDS_BYTES = 2 * STAGE * 8;     // two chunks
     static constexpr int ACC_REGS = 3 * IT * JT * 16;
+    // waves per SIMD the register allocation must allow (the accumulators alone take ACC_REGS of 512)
+    static constexpr int WAVES_PER_SIMD = ACC_REGS <= 48 ? 4 : (ACC_REGS <= 96 ? 2 : 1);
 };
 
 // Launch: grid = bins * tiles_m * tiles_n blocks of G::THREADS threads, G::LDS_BYTES dynamic LDS.
 template <class G, bool A_KIN, bool B_KIN, bool CONJ_A, bool CONJ_B>
-__global__ __launch_bounds__(G::THREADS) void bin_cgemm_kernel(GemmArgs g)
+__global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void bin_cgemm_kernel(GemmArgs g)
 {
     constexpr int IT = G::IT, JT = G::JT, KS = kKT / 2;
     extern __shared__ __align__(16) unsigned char lds_raw[];
