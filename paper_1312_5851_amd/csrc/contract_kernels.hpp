@@ -117,7 +117,7 @@ struct GemmTile {
     static constexpr int LDS_BYTES = 2 * STAGE * 8;     // two chunks
     static constexpr int ACC_REGS = 3 * IT * JT * 16;
     // waves per SIMD the register allocation must allow (the accumulators alone take ACC_REGS of 512)
-    static constexpr int WAVES_PER_SIMD = ACC_REGS <= 48 ? 4 : (ACC_REGS <= 96 ? 2 : 1);
+    static constexpr int WAVES_PER_SIMD = ACC_REGS <= 48 ? (WM * WN >= 4 ? 4 : 3) : (ACC_REGS <= 96 ? 2 : 1);
 };
 
 // Launch: grid = bins * tiles_m * tiles_n blocks of G::THREADS threads, G::LDS_BYTES dynamic LDS.
