@@ -65,6 +65,23 @@ def cpu_baseline(layer, x, w, g, budget_s=18.0):
     }
 
 
+def copy_bandwidth():
+    """Read+write rate of a plain 1 GiB device copy (larger than the 256 MB memory-side cache):
+    what a kernel that only moves data gets out of HBM on this machine, as context for the FFT stages."""
+    import torch
+    n = 256 * 1024 * 1024
+    src = torch.empty(n, dtype=torch.float32, device="cuda").fill_(1.0)
+    dst = torch.empty_like(src)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(2):
+        dst.copy_(src)
+    ev0.record()
+    for _ in range(5):
+        dst.copy_(src)
+    ev1.record(); ev1.synchronize()
+    return 5 * 2 * 4 * n / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+
+
 def measure(layer, args, inputs=None):
     """Times args.steps steps of the whole hot path on one layer; returns the JSON record."""
     import torch
@@ -269,6 +286,7 @@ def main():
     layer = wl.by_name(args.workload)
     inputs = wl.make_inputs(layer)
     out = measure(layer, args, inputs)
+    out["hbm_copy_GBps"] = copy_bandwidth()
     x, w, g = inputs
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a bounded sample ...")
