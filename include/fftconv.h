@@ -40,13 +40,22 @@ typedef struct fftconv_plan_s *fftconv_plan_t;
 
 typedef struct {
     int S, f, fo, n, k;
-    unsigned flags; /* must be 0 */
+    unsigned flags; /* 0 or FFTCONV_RECOMPUTE */
 } fftconv_desc;
+
+/* Plan flag: the memory-efficient mode all of the paper's own timings assume (Sec. 2.3).
+ * No spectrum is reused: every pass transforms both of its operands again, and the
+ * workspace shrinks to the three slots x, w, g (8*B*(S*f + fo*f + S*fo) bytes, the
+ * count of Sec. 2.3) because a pass writes its result spectrum into the slot it does not
+ * read (Y into g's, dX into x's, dW into w's).  One such workspace can serve every layer
+ * of a network in turn, sized for the largest.  fftconv_valid_slots is 0 after a pass,
+ * and FFTCONV_SPEC_OUT has no offset of its own. */
+enum { FFTCONV_RECOMPUTE = 1 };
 
 enum {
     FFTCONV_OK = 0,
     FFTCONV_EINVAL = 1,       /* null pointer, non-positive size, k > n, bad slot/pass */
-    FFTCONV_EUNSUPPORTED = 2, /* n > 64 (no compiled transform size) or flags != 0 */
+    FFTCONV_EUNSUPPORTED = 2, /* n > 64 (no compiled transform size) or unknown flag bits */
     FFTCONV_EWORKSPACE = 3,   /* workspace pointer null or not 256-byte aligned */
     FFTCONV_ELAUNCH = 4,      /* the HIP runtime refused a launch or an event call */
     FFTCONV_ENOTREADY = 5     /* a stage-level call needs a spectrum that is not cached */
@@ -70,7 +79,7 @@ enum {
 
 /* Validates the layer and fixes N, the bin count and the workspace layout.
  * Errors: EINVAL for null arguments, sizes < 1 or k > n; EUNSUPPORTED for n > 64
- * or non-zero flags.  *out is written only on success. */
+ * or unknown flag bits.  *out is written only on success. */
 int fftconv_plan(fftconv_plan_t *out, const fftconv_desc *d);
 int fftconv_plan_destroy(fftconv_plan_t p);
 
@@ -82,7 +91,8 @@ int fftconv_num_bins(fftconv_plan_t p);
 
 /* Bytes of device workspace the passes need: the x, w and g spectra (8*B bytes
  * per map for S*f + fo*f + S*fo maps, the count of Sec. 2.3) plus one result
- * spectrum of 8*B*max(S*fo, S*f, fo*f) bytes; each slot 256-byte aligned. */
+ * spectrum of 8*B*max(S*fo, S*f, fo*f) bytes; each slot 256-byte aligned.
+ * With FFTCONV_RECOMPUTE: the three slots only. */
 size_t fftconv_workspace_bytes(fftconv_plan_t p);
 
 /* Layout of one slot inside the workspace: byte offset and number of maps M.
@@ -93,7 +103,7 @@ size_t fftconv_workspace_bytes(fftconv_plan_t p);
  * m is the map index in the tensor's own order (s*f+i for x, j*f+i for w,
  * s*fo+j for g).  FFTCONV_SPEC_OUT holds the spectrum
  * of the last pass's result, laid out like that result.  Returns (size_t)-1 /
- * -1 for a bad slot. */
+ * -1 for a bad slot (and for FFTCONV_SPEC_OUT under FFTCONV_RECOMPUTE). */
 size_t fftconv_slot_offset(fftconv_plan_t p, int slot);
 long   fftconv_slot_maps(fftconv_plan_t p, int slot);
 
@@ -126,11 +136,13 @@ int fftconv_accgrad(fftconv_plan_t p, const float *g, const float *x, float *dw,
  * unconditionally; marks the slot valid. */
 int fftconv_forward_transform(fftconv_plan_t p, int slot, const float *src, void *ws, void *stream);
 
-/* Per-bin contraction of a pass on cached spectra into the OUT slot.
+/* Per-bin contraction of a pass on cached spectra into the OUT slot (under
+ * FFTCONV_RECOMPUTE into the slot the pass does not read, which stops being valid).
  * ENOTREADY if an operand slot is not valid for this workspace. */
 int fftconv_contract(fftconv_plan_t p, int pass, void *ws, void *stream);
 
-/* Inverse transform + crop of the OUT slot into the pass's result tensor. */
+/* Inverse transform + crop of the pass's result spectrum (where fftconv_contract
+ * put it) into the pass's result tensor. */
 int fftconv_inverse_transform(fftconv_plan_t p, int pass, float *dst, void *ws, void *stream, int accumulate);
 
 /* ---- stage timing ------------------------------------------------------- */
@@ -151,7 +163,7 @@ const char *fftconv_strerror(int status);
 
 /* The paper's closed form for frequency-domain memory, Sec. 2.3:
  * 4 n (n+1) (S f + S fo + f fo) bytes (it counts n(n+1)/2 complex numbers per
- * map; the workspace query above counts the (N/2+1)*N actually stored). */
+ * map; the workspace query above counts the B = N*N/2 + 2 actually stored). */
 size_t fftconv_paper_ram_bytes(int S, int n, int f, int fo);
 
 /* Matrix-core floating-point operations the contraction of one pass issues:

@@ -185,6 +185,21 @@ int bind_workspace(fftconv_plan_t p, void *ws)
     return FFTCONV_OK;
 }
 
+bool recompute_mode(fftconv_plan_t p) { return (p->d.flags & FFTCONV_RECOMPUTE) != 0; }
+
+// Slot that receives a pass's result spectrum.  With the spectral cache it is the separate
+// OUT slot; in the memory-efficient mode it is the one of the three slots the pass does not
+// read, which has exactly the result's shape (Y like g, dX like x, dW like w).
+int result_slot(fftconv_plan_t p, int pass)
+{
+    if (!recompute_mode(p)) return FFTCONV_SPEC_OUT;
+    switch (pass) {
+        case FFTCONV_FPROP: return FFTCONV_SPEC_G;
+        case FFTCONV_BPROP: return FFTCONV_SPEC_X;
+        default:            return FFTCONV_SPEC_W;
+    }
+}
+
 cf *slot_ptr(fftconv_plan_t p, void *ws, int slot)
 {
     size_t off = 0;
@@ -238,7 +253,8 @@ int launch_contract(fftconv_plan_t p, int pass, void *ws, hipStream_t stream)
     GemmArgs g;
     g.A = slot_ptr(p, ws, sa);
     g.B = slot_ptr(p, ws, sb);
-    g.C = slot_ptr(p, ws, FFTCONV_SPEC_OUT);
+    const int sc = result_slot(p, pass);
+    g.C = slot_ptr(p, ws, sc);
     g.Md = Md; g.Nd = Nd; g.Kd = Kd;
     g.bins = p->B;
     g.tiles_m = (Md + e.MT - 1) / e.MT;
@@ -250,6 +266,7 @@ int launch_contract(fftconv_plan_t p, int pass, void *ws, hipStream_t stream)
     StageTimer timer(p, FFTCONV_STAGE_CGEMM_FPROP + pass, stream);
     hipLaunchKernelGGL(e.pass[pass], dim3((unsigned)blocks), dim3(e.threads), e.lds_bytes, stream, g);
     if (int rc = check_launch()) return rc;
+    if (sc != FFTCONV_SPEC_OUT) p->valid &= ~(unsigned)sc;   // an operand slot now holds a result spectrum
     return timer.finish();
 }
 
@@ -266,7 +283,7 @@ int launch_inverse(fftconv_plan_t p, int pass, float *dst, void *ws, hipStream_t
     if (!e) return FFTCONV_EUNSUPPORTED;
     InvKernel kernel = accumulate ? e->inv_acc : e->inv;
     if (int rc = allow_lds(kernel, e->lds_bytes)) return rc;
-    InvArgs a{slot_ptr(p, ws, FFTCONV_SPEC_OUT), dst, (int)M, crop, 1.0f / ((float)p->N * (float)p->N)};
+    InvArgs a{slot_ptr(p, ws, result_slot(p, pass)), dst, (int)M, crop, 1.0f / ((float)p->N * (float)p->N)};
     const unsigned blocks = (unsigned)((M + e->T - 1) / e->T);
     StageTimer timer(p, FFTCONV_STAGE_IFFT_Y + pass, stream);
     hipLaunchKernelGGL(kernel, dim3(blocks), dim3(e->threads), e->lds_bytes, stream, a);
@@ -282,12 +299,15 @@ int run_pass(fftconv_plan_t p, int pass, const float *src_a, const float *src_b,
     hipStream_t s = static_cast<hipStream_t>(stream);
     int Md, Nd, Kd, sa, sb;
     pass_dims(p, pass, Md, Nd, Kd, sa, sb);
+    if (recompute_mode(p)) p->valid = 0;   // every pass transforms both of its operands
     if ((p->valid & (unsigned)sa) == 0)
         if (int rc = launch_forward(p, sa, src_a, ws, s)) return rc;
     if ((p->valid & (unsigned)sb) == 0)
         if (int rc = launch_forward(p, sb, src_b, ws, s)) return rc;
     if (int rc = launch_contract(p, pass, ws, s)) return rc;
-    return launch_inverse(p, pass, dst, ws, s, accumulate);
+    const int rc = launch_inverse(p, pass, dst, ws, s, accumulate);
+    if (recompute_mode(p)) p->valid = 0;
+    return rc;
 }
 
 }  // namespace
@@ -298,7 +318,7 @@ int fftconv_plan(fftconv_plan_t *out, const fftconv_desc *d)
 {
     if (!out || !d) return FFTCONV_EINVAL;
     if (d->S < 1 || d->f < 1 || d->fo < 1 || d->n < 1 || d->k < 1 || d->k > d->n) return FFTCONV_EINVAL;
-    if (d->flags != 0 || d->n > 64) return FFTCONV_EUNSUPPORTED;
+    if ((d->flags & ~(unsigned)FFTCONV_RECOMPUTE) != 0 || d->n > 64) return FFTCONV_EUNSUPPORTED;
     const long maps_x = (long)d->S * d->f, maps_w = (long)d->fo * d->f, maps_g = (long)d->S * d->fo;
     if (maps_x > 0x7fffffffL || maps_w > 0x7fffffffL || maps_g > 0x7fffffffL) return FFTCONV_EUNSUPPORTED;
     fftconv_plan_s *p = new (std::nothrow) fftconv_plan_s();
@@ -317,6 +337,11 @@ int fftconv_plan(fftconv_plan_t *out, const fftconv_desc *d)
     p->off_g = p->off_w + align_up(per_map * maps_w);
     p->off_out = p->off_g + align_up(per_map * maps_g);
     p->ws_bytes = p->off_out + align_up(per_map * p->maps_out);
+    if (recompute_mode(p)) {   // three slots only: a pass writes its result into the one it does not read
+        p->ws_bytes = p->off_out;
+        p->off_out = (size_t)-1;
+        p->maps_out = -1;
+    }
     p->valid = 0;
     p->last_ws = nullptr;
     p->profiling = 0;
@@ -446,7 +471,7 @@ const char *fftconv_strerror(int status)
     switch (status) {
         case FFTCONV_OK: return "ok";
         case FFTCONV_EINVAL: return "invalid argument";
-        case FFTCONV_EUNSUPPORTED: return "unsupported layer (n > 64 or non-zero flags)";
+        case FFTCONV_EUNSUPPORTED: return "unsupported layer (n > 64 or unknown flags)";
         case FFTCONV_EWORKSPACE: return "workspace pointer null or not 256-byte aligned";
         case FFTCONV_ELAUNCH: return "HIP launch or event call failed";
         case FFTCONV_ENOTREADY: return "operand spectrum not cached for this workspace";

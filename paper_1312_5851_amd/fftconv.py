@@ -18,6 +18,7 @@ from . import build as _build
 FFTCONV_OK = 0
 SPEC_X, SPEC_W, SPEC_G, SPEC_OUT = 1, 2, 4, 8
 FPROP, BPROP, ACCGRAD = 0, 1, 2
+RECOMPUTE = 1   # plan flag: memory-efficient mode (no spectral cache, three-slot workspace)
 NUM_STAGES = 9
 PROFILE_ALL = 0x1FF
 STAGE_NAMES = ("fft_x", "fft_w", "fft_g", "cgemm_fprop", "cgemm_bprop", "cgemm_accgrad",
@@ -169,8 +170,10 @@ class Plan:
 
     def slot_view(self, slot: int):
         """The slot's spectrum as a [B, M, 2] fp32 view of the workspace."""
-        base = self._ws_ptr().value - self.ws.data_ptr() + self.slot_offset(slot)
         B, M = self.num_bins, self.slot_maps(slot)
+        if M < 0:
+            raise ValueError(f"slot {slot} has no place of its own in this plan's workspace")
+        base = self._ws_ptr().value - self.ws.data_ptr() + self.slot_offset(slot)
         return self.ws[base:base + 8 * B * M].view(torch.float32).view(B, M, 2)
 
     # -- passes ------------------------------------------------------------

@@ -72,10 +72,25 @@ def paper_table_layers():
             for i, (k, n, f, fo) in enumerate(cols)]
 
 
+def fig3_layers():
+    """The three axes of the paper's speed figure (Sec. 3): image size, kernel size and
+    minibatch size, each varied alone around f=96, f'=256.  The figure's tick values are
+    not given in the text; the points here bracket the table's layers and include image
+    sizes that are not a power of two (padded up, Sec. 4)."""
+    out = []
+    for i, n in enumerate((8, 12, 16, 24, 32, 48, 64)):
+        out.append(Layer(f"fig3_n{n}", 128, 96, 256, n, 5, 0.02, BASE_SEED + 300 + i))
+    for i, k in enumerate((3, 7, 9, 11, 13)):          # k = 5 is the n = 32 point above
+        out.append(Layer(f"fig3_k{k}", 128, 96, 256, 32, k, 0.02, BASE_SEED + 320 + i))
+    for i, S in enumerate((16, 32, 64, 256)):          # S = 128 is the n = 32 point above
+        out.append(Layer(f"fig3_S{S}", S, 96, 256, 32, 5, 0.02, BASE_SEED + 340 + i))
+    return out
+
+
 def by_name(name: str) -> Layer:
     if name in CONFIGS:
         return CONFIGS[name]
-    for lay in sweep_layers() + paper_table_layers():
+    for lay in sweep_layers() + paper_table_layers() + fig3_layers():
         if lay.name == name:
             return lay
     raise KeyError(name)

@@ -72,12 +72,30 @@ def test_plan_rejects_bad_layers(fc, args, status):
 
 
 def test_plan_rejects_flags_and_nulls(fc):
-    with pytest.raises(fc.FftconvError) as ei:
-        fc.Plan(1, 1, 1, 8, 3, flags=1)
-    assert ei.value.status == 2
+    for flags in (2, 4, 3, 0x80000000):
+        with pytest.raises(fc.FftconvError) as ei:
+            fc.Plan(1, 1, 1, 8, 3, flags=flags)
+        assert ei.value.status == 2
     assert fc._lib.fftconv_plan(None, None) == 1
     assert fc._lib.fftconv_plan_destroy(None) == 1
     assert fc._lib.fftconv_fft_size(None) == -1
+
+
+def test_memory_efficient_plan_has_three_slots(fc):
+    """Sec. 2.3: S f + S f' + f f' frequency representations and nothing else."""
+    S, f, fo, n, k = 128, 96, 256, 32, 5
+    cached, lean = fc.Plan(S, f, fo, n, k), fc.Plan(S, f, fo, n, k, flags=fc.RECOMPUTE)
+    B = lean.num_bins
+    assert B == cached.num_bins == 514
+    assert lean.workspace_bytes == 8 * B * (S * f + fo * f + S * fo)       # every slot size is a multiple of 256 here
+    assert cached.workspace_bytes == lean.workspace_bytes + 8 * B * max(S * f, fo * f, S * fo)
+    for slot in (fc.SPEC_X, fc.SPEC_W, fc.SPEC_G):
+        assert lean.slot_offset(slot) == cached.slot_offset(slot) and lean.slot_maps(slot) == cached.slot_maps(slot)
+    assert lean.slot_maps(fc.SPEC_OUT) == -1 and lean.slot_offset(fc.SPEC_OUT) == 2 ** 64 - 1
+    # below the paper's own closed form (it counts n(n+1)/2 complex numbers per map, more than the B stored here)
+    assert lean.workspace_bytes <= fc.paper_ram_bytes(S, n, f, fo)
+    assert lean.valid_slots() == 0
+    assert fc._lib.fftconv_contract(lean._h, 0, ctypes.c_void_p(256), None) == 5
 
 
 def test_invalidate_bookkeeping_and_null_pointer_errors(fc):
@@ -131,7 +149,10 @@ def test_workloads_are_seeded_and_shaped():
     assert x.dtype == np.float32 and x.shape == (4, 8, 16, 16) and w.shape == (8, 8, 5, 5) and g.shape == (4, 8, 12, 12)
     assert np.abs(x).max() <= 1 and abs(w.std() - 0.05) < 0.01 and abs(g.std() - 1) < 0.1
     assert wl.MID.direct_flops == 2 * 128 * 96 * 256 * 28 * 28 * 25
-    assert len(wl.sweep_layers()) == 18 and len(wl.paper_table_layers()) == 5
-    assert wl.by_name("sweep_n32_k7").k == 7
+    assert len(wl.sweep_layers()) == 18 and len(wl.paper_table_layers()) == 5 and len(wl.fig3_layers()) == 16
+    assert wl.by_name("sweep_n32_k7").k == 7 and wl.by_name("fig3_S256").S == 256
+    every = list(wl.CONFIGS.values()) + wl.sweep_layers() + wl.paper_table_layers() + wl.fig3_layers()
+    assert len({l.name for l in every}) == len(every) == len({l.seed for l in every})
+    assert all(1 <= l.k <= l.n <= 64 for l in every)
     u = wl.sample_units(100, 10, 3)
     assert len(set(u.tolist())) == 10 and np.array_equal(u, wl.sample_units(100, 10, 3))

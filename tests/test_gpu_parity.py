@@ -136,6 +136,61 @@ def test_sampled_parity_paper_table_columns(fc, idx):
     sampled_check(fc, layer, (64, 64, 96))
 
 
+@pytest.mark.parametrize("name", ["fig3_n12", "fig3_n24", "fig3_n48", "fig3_k13", "fig3_S16", "fig3_S256"])
+def test_sampled_parity_figure_axes(fc, name):
+    """Points of the paper's speed figure axes (image size incl. sizes that are padded up,
+    kernel size, minibatch size; f=96, f'=256) at full size, oracle on a seeded sample."""
+    layer = wl.by_name(name)
+    print(f"\ncase {layer}", flush=True)
+    per_unit = (layer.no ** 2, layer.n ** 2, layer.k ** 2)
+    counts = tuple(max(8, min(96, -(-10000 // e))) for e in per_unit)
+    sampled_check(fc, layer, counts)
+
+
+@pytest.mark.parametrize("layer", [wl.TINY, SMALL_LAYERS[5], SMALL_LAYERS[7], wl.Layer("lean_wide", 9, 40, 70, 16, 3, 0.05, 81)],
+                         ids=lambda l: l.name)
+def test_memory_efficient_mode_parity(fc, layer):
+    """Plan flag RECOMPUTE (Sec. 2.3's memory-efficient mode): three-slot workspace, every pass
+    transforms its operands again and writes its result spectrum into the slot it does not read.
+    Passes in an order in which a stale or clobbered slot would be used if anything were reused."""
+    print(f"\ncase {layer} (recompute)", flush=True)
+    x, w, g = wl.make_inputs(layer)
+    plan = fc.Plan(layer.S, layer.f, layer.fo, layer.n, layer.k, flags=fc.RECOMPUTE)
+    plan.alloc_workspace()
+    # the workspace tensor is exactly the three slots (+ alignment slack): guard what lies behind them
+    assert plan.ws.numel() == plan.workspace_bytes + 256
+    xd, wd, gd = dev(x), dev(w), dev(g)
+    for _ in range(2):
+        dw = plan.accgrad(gd, xd)
+        assert plan.valid_slots() == 0
+        y = plan.fprop(xd, wd)
+        dx = plan.bprop(gd, wd)
+        assert plan.valid_slots() == 0
+    dw2 = plan.accgrad(gd, xd, dw.clone(), accumulate=True)
+    torch.cuda.synchronize()
+    check(y.cpu().numpy(), direct.fprop(x, w), f"{layer.name} fprop (recompute)")
+    check(dx.cpu().numpy(), direct.bprop(g, w, layer.n), f"{layer.name} bprop (recompute)")
+    ref_dw = direct.accgrad(g, x, layer.k)
+    check(dw.cpu().numpy(), ref_dw, f"{layer.name} accgrad (recompute)")
+    check(dw2.cpu().numpy(), 2 * ref_dw, f"{layer.name} accgrad accumulate (recompute)")
+    with pytest.raises(ValueError):
+        plan.slot_view(fc.SPEC_OUT)
+
+
+def test_memory_efficient_mode_matches_cached_mode_at_full_size(fc):
+    """Config mid: both modes run the same kernels on the same data, so the results are bit-identical."""
+    layer = wl.MID
+    x, w, g = wl.make_inputs(layer)
+    xd, wd, gd = dev(x), dev(w), dev(g)
+    cached = fc.Plan(layer.S, layer.f, layer.fo, layer.n, layer.k)
+    lean = fc.Plan(layer.S, layer.f, layer.fo, layer.n, layer.k, flags=fc.RECOMPUTE)
+    for name, run in (("fprop", lambda p: p.fprop(xd, wd)), ("bprop", lambda p: p.bprop(gd, wd)),
+                      ("accgrad", lambda p: p.accgrad(gd, xd))):
+        a, b = run(cached), run(lean)
+        torch.cuda.synchronize()
+        assert torch.equal(a, b), name
+
+
 EDGE_LAYERS = [
     wl.Layer("n64_k1", 2, 3, 2, 64, 1, 0.1, 61),          # largest transform, k = 1
     wl.Layer("n64_k64", 2, 2, 3, 64, 64, 0.05, 62),       # k = n = 64: one output pixel
