@@ -12,28 +12,38 @@
 using namespace fftconv;
 
 template <class G>
+using LaneRegs = std::vector<std::array<cf, G::N>>;
+
+template <class G>
+static cf (&regs(LaneRegs<G> &r, int tid))[G::N]
+{
+    return reinterpret_cast<cf(&)[G::N]>(*r[tid].data());
+}
+
+template <class G>
 static void replay_forward(const FwdArgs &a)
 {
     std::vector<cf> lds(G::LDS_ELEMS);
-    std::vector<std::array<cf, G::N>> z(G::THREADS);
+    LaneRegs<G> z(G::THREADS), v(G::THREADS);
     std::vector<char> has(G::THREADS);
     const int blocks = (a.M + G::T - 1) / G::T;
     for (int blk = 0; blk < blocks; ++blk) {
-        // poison: an x-phase read of something the y-phase did not write shows up as NaN
-        std::memset(lds.data(), 0xFF, sizeof(cf) * lds.size());
         for (int tid = 0; tid < G::THREADS; ++tid) {
+            // poison: a read of something an earlier step did not write shows up as NaN
             std::memset(z[tid].data(), 0xFF, sizeof(cf) * G::N);
-            has[tid] = fwd_y_compute<G>(tid, blk, a, reinterpret_cast<cf(&)[G::N]>(*z[tid].data()));
+            std::memset(v[tid].data(), 0xFF, sizeof(cf) * G::N);
+            has[tid] = fwd_y_compute<G>(tid, blk, a, regs<G>(z, tid));
         }
-        for (int tid = 0; tid < G::THREADS; ++tid)
-            if (has[tid]) fwd_y_write<G, 0>(tid, reinterpret_cast<cf(&)[G::N]>(*z[tid].data()), lds.data());
-        for (int tid = 0; tid < G::THREADS; ++tid) fwd_x<G>(tid, blk, 0, a, lds.data());
-        if constexpr (G::ROUNDS == 2) {
+        static_for<0, G::ROUNDS>([&](auto ri) {
+            constexpr int r = decltype(ri)::value;
             std::memset(lds.data(), 0xFF, sizeof(cf) * lds.size());
             for (int tid = 0; tid < G::THREADS; ++tid)
-                if (has[tid]) fwd_y_write<G, 1>(tid, reinterpret_cast<cf(&)[G::N]>(*z[tid].data()), lds.data());
-            for (int tid = 0; tid < G::THREADS; ++tid) fwd_x<G>(tid, blk, 1, a, lds.data());
-        }
+                if (has[tid]) fwd_y_write<G, r>(tid, regs<G>(z, tid), lds.data());
+            for (int tid = 0; tid < G::THREADS; ++tid)
+                if (tid / G::XTHREADS == r) fwd_x_read<G>(tid % G::XTHREADS, lds.data(), regs<G>(v, tid));
+        });
+        for (int tid = 0; tid < G::THREADS; ++tid)
+            fwd_x_finish<G>(tid % G::XTHREADS, blk, tid / G::XTHREADS, a, regs<G>(v, tid));
     }
 }
 
@@ -41,23 +51,24 @@ template <class G>
 static void replay_inverse(const InvArgs &a, bool acc)
 {
     std::vector<cf> lds(G::LDS_ELEMS);
-    std::vector<std::array<cf, G::N>> z(G::THREADS);
+    LaneRegs<G> z(G::THREADS), v(G::THREADS);
     const int blocks = (a.M + G::T - 1) / G::T;
     for (int blk = 0; blk < blocks; ++blk) {
-        std::memset(lds.data(), 0xFF, sizeof(cf) * lds.size());
-        for (int tid = 0; tid < G::THREADS; ++tid) std::memset(z[tid].data(), 0xFF, sizeof(cf) * G::N);
-        for (int tid = 0; tid < G::THREADS; ++tid) inv_x<G>(tid, blk, 0, a, lds.data());
-        for (int tid = 0; tid < G::THREADS; ++tid)
-            inv_y_gather<G, 0>(tid, lds.data(), reinterpret_cast<cf(&)[G::N]>(*z[tid].data()));
-        if constexpr (G::ROUNDS == 2) {
-            std::memset(lds.data(), 0xFF, sizeof(cf) * lds.size());
-            for (int tid = 0; tid < G::THREADS; ++tid) inv_x<G>(tid, blk, 1, a, lds.data());
-            for (int tid = 0; tid < G::THREADS; ++tid)
-                inv_y_gather<G, 1>(tid, lds.data(), reinterpret_cast<cf(&)[G::N]>(*z[tid].data()));
-        }
         for (int tid = 0; tid < G::THREADS; ++tid) {
-            if (acc) inv_y_finish<G, true>(tid, blk, a, reinterpret_cast<cf(&)[G::N]>(*z[tid].data()));
-            else inv_y_finish<G, false>(tid, blk, a, reinterpret_cast<cf(&)[G::N]>(*z[tid].data()));
+            std::memset(z[tid].data(), 0xFF, sizeof(cf) * G::N);
+            std::memset(v[tid].data(), 0xFF, sizeof(cf) * G::N);
+            inv_x_compute<G>(tid % G::XTHREADS, blk, tid / G::XTHREADS, a, regs<G>(v, tid));
+        }
+        static_for<0, G::ROUNDS>([&](auto ri) {
+            constexpr int r = decltype(ri)::value;
+            std::memset(lds.data(), 0xFF, sizeof(cf) * lds.size());
+            for (int tid = 0; tid < G::THREADS; ++tid)
+                if (tid / G::XTHREADS == r) inv_x_write<G>(tid % G::XTHREADS, lds.data(), regs<G>(v, tid));
+            for (int tid = 0; tid < G::THREADS; ++tid) inv_y_gather<G, r>(tid, lds.data(), regs<G>(z, tid));
+        });
+        for (int tid = 0; tid < G::THREADS; ++tid) {
+            if (acc) inv_y_finish<G, true>(tid, blk, a, regs<G>(z, tid));
+            else inv_y_finish<G, false>(tid, blk, a, regs<G>(z, tid));
         }
     }
 }

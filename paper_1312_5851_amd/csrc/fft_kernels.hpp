@@ -29,10 +29,13 @@
 //
 // Between the phases the data sits in LDS as lds[r][x][m] (m fastest) with
 // strides padded so that both phases touch distinct banks.  With ROUNDS = 2 the
-// rows go through LDS in two halves (the y-phase keeps its column in registers
-// and hands over rows [0, N/4) first, then [N/4, N/2); half of the lanes run the
-// x-phase of each half): LDS per workgroup halves, which at N = 64 is what lets
-// two workgroups share a CU so that one's loads overlap the other's arithmetic.
+// rows go through LDS in two halves, rows [0, N/4) first, then [N/4, N/2), which
+// halves the LDS of a workgroup (at N = 64 the whole tile would not fit).  The
+// lanes form two teams, one per half.  LDS is only a hand-over point: forward,
+// a team copies its rows from LDS into registers and the next half can be written
+// at once, so both teams run their x-transforms and stores side by side; inverse,
+// both teams load and transform their rows side by side and only take turns
+// writing them to LDS.
 //
 // Each phase step is a plain function of (thread id, block id, per-lane state):
 // the device kernels call them around __syncthreads(), and a host build replays
@@ -66,7 +69,7 @@ struct TileGeom {
     static constexpr int ROWS = N / 2;                 // packed row 0 + rows 1..N/2-1
     static constexpr int RPR = ROWS / ROUNDS;          // rows per round
     static constexpr int THREADS = T * ROWS;           // lanes per workgroup
-    static constexpr int XTHREADS = T * RPR;           // lanes active in one round of the x-phase: (row, map)
+    static constexpr int XTHREADS = T * RPR;           // lanes of one x-phase team: (row of its half, map)
     static constexpr int SX = T + 1;                   // complex elements between consecutive x
     static constexpr int SR_BASE = NX * SX;
     // row stride: congruent to T modulo 32 complex (= 64 dwords) so that the row groups
@@ -145,21 +148,26 @@ FC_HD void fwd_y_write(int tid, const cf (&z)[G::N], cf *lds)
     });
 }
 
-// x-phase of one round: transform a row of one map along x, store bin-major.
+// x-phase, step 1: lane xt = (slot, map) of its team copies its row from LDS into registers.
 template <class G>
-FC_HD void fwd_x(int tid, int blk, int round, const FwdArgs &a, const cf *lds)
+FC_HD void fwd_x_read(int xt, const cf *lds, cf (&v)[G::N])
 {
-    constexpr int N = G::N, NX = G::NX;
-    if (tid >= G::XTHREADS) return;
-    const int slot = tid / G::T, m = tid % G::T;
-    const int r = round * G::RPR + slot;
-    const int mg = blk * G::T + m;
-    cf v[N];
+    const int slot = xt / G::T, m = xt % G::T;
     const cf *base = lds + slot * G::SR + m;
-    static_for<0, NX>([&](auto xi) {
+    static_for<0, G::NX>([&](auto xi) {
         constexpr int x = decltype(xi)::value;
         v[x] = base[x * G::SX];
     });
+}
+
+// x-phase, step 2: transform the row along x, store bin-major.  `round` is the team's half.
+template <class G>
+FC_HD void fwd_x_finish(int xt, int blk, int round, const FwdArgs &a, cf (&v)[G::N])
+{
+    constexpr int N = G::N, NX = G::NX;
+    const int slot = xt / G::T, m = xt % G::T;
+    const int r = round * G::RPR + slot;
+    const int mg = blk * G::T + m;
     fft_dif<N, false, ~low_mask(NX)>(v);
     if (mg >= a.M) return;
     cf *out = a.spec + mg;
@@ -183,21 +191,19 @@ FC_HD void fwd_x(int tid, int blk, int round, const FwdArgs &a, const cf *lds)
 
 // ------------------------------------------------------------------ inverse
 
-// x-phase of one round: load a row of one map's spectrum, inverse transform along kx,
-// hand the needed columns to LDS.
+// x-phase, step 1: lane xt = (slot, map) of its team loads a row of one map's spectrum and
+// inverse-transforms it along kx.  Leaves the bit-reversed transform in v.
 template <class G>
-FC_HD void inv_x(int tid, int blk, int round, const InvArgs &a, cf *lds)
+FC_HD void inv_x_compute(int xt, int blk, int round, const InvArgs &a, cf (&v)[G::N])
 {
     constexpr int N = G::N, NX = G::NX;
-    if (tid >= G::XTHREADS) return;
-    const int slot = tid / G::T, m = tid % G::T;
+    const int slot = xt / G::T, m = xt % G::T;
     const int r = round * G::RPR + slot;
     const int mg = blk * G::T + m;
     // Lanes beyond the last map read the last map's bins (valid memory) instead of
     // branching around each load; what they compute is never stored.
     const cf *in = a.spec + (mg < a.M ? mg : a.M - 1);
     const size_t M = (size_t)a.M;
-    cf v[N];
     if (r != 0) {
         static_for<0, N>([&](auto ki) {
             constexpr int kx = decltype(ki)::value;
@@ -221,8 +227,16 @@ FC_HD void inv_x(int tid, int blk, int round, const InvArgs &a, cf *lds)
         });
     }
     fft_dif<N, true, 0, first_outputs_mask<N>(NX)>(v);
+}
+
+// x-phase, step 2: hand the needed columns of the row to LDS.
+template <class G>
+FC_HD void inv_x_write(int xt, cf *lds, const cf (&v)[G::N])
+{
+    constexpr int N = G::N;
+    const int slot = xt / G::T, m = xt % G::T;
     cf *base = lds + slot * G::SR + m;
-    static_for<0, NX>([&](auto xi) {
+    static_for<0, G::NX>([&](auto xi) {
         constexpr int x = decltype(xi)::value;
         base[x * G::SX] = v[brev<N>(x)];
     });
@@ -293,10 +307,11 @@ FC_HD void inv_y_finish(int tid, int blk, const InvArgs &a, cf (&z)[G::N])
 }
 
 // The order of steps and barriers of one workgroup, shared by the device kernels and the
-// host replay.  `Sync` is __syncthreads() on the device; the host replay runs every step for
+// host replay.  `sync` is __syncthreads() on the device; the host replay runs every step for
 // all lanes before the next one, which is what a barrier after each step guarantees.
-//   forward: y_compute | round 0: y_write, barrier, x | round 1: barrier, y_write, barrier, x
-//   inverse: round 0: x, barrier, y_gather | round 1: barrier, x, barrier, y_gather | y_finish
+// Lane tid belongs to team tid / XTHREADS and is lane xt = tid % XTHREADS of it.
+//   forward: y_compute | per round r: (barrier,) y_write<r>, barrier, team r: x_read | x_finish
+//   inverse: x_compute | per round r: (barrier,) team r: x_write, barrier, y_gather<r> | y_finish
 
 #if defined(__HIPCC__)
 // Device kernels.  Launch with G::THREADS threads, ceil(M / G::T) blocks and G::LDS_BYTES
@@ -308,17 +323,17 @@ __global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void fft2d_r2c_kerne
     extern __shared__ __align__(16) unsigned char lds_raw[];
     cf *lds = reinterpret_cast<cf *>(lds_raw);
     const int tid = (int)threadIdx.x, blk = (int)blockIdx.x;
-    cf z[G::N];
+    const int team = tid / G::XTHREADS, xt = tid % G::XTHREADS;
+    cf z[G::N], v[G::N];
     const bool has = fwd_y_compute<G>(tid, blk, a, z);
-    if (has) fwd_y_write<G, 0>(tid, z, lds);
-    __syncthreads();
-    fwd_x<G>(tid, blk, 0, a, lds);
-    if constexpr (G::ROUNDS == 2) {
+    static_for<0, G::ROUNDS>([&](auto ri) {
+        constexpr int r = decltype(ri)::value;
+        if constexpr (r > 0) __syncthreads();   // the previous team has its rows in registers
+        if (has) fwd_y_write<G, r>(tid, z, lds);
         __syncthreads();
-        if (has) fwd_y_write<G, 1>(tid, z, lds);
-        __syncthreads();
-        fwd_x<G>(tid, blk, 1, a, lds);
-    }
+        if (team == r) fwd_x_read<G>(xt, lds, v);
+    });
+    fwd_x_finish<G>(xt, blk, team, a, v);
 }
 
 template <class G, bool ACC>   // ACC: dst += result instead of dst = result
@@ -327,16 +342,16 @@ __global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void ifft2d_c2r_crop
     extern __shared__ __align__(16) unsigned char lds_raw[];
     cf *lds = reinterpret_cast<cf *>(lds_raw);
     const int tid = (int)threadIdx.x, blk = (int)blockIdx.x;
-    cf z[G::N];
-    inv_x<G>(tid, blk, 0, a, lds);
-    __syncthreads();
-    inv_y_gather<G, 0>(tid, lds, z);
-    if constexpr (G::ROUNDS == 2) {
+    const int team = tid / G::XTHREADS, xt = tid % G::XTHREADS;
+    cf z[G::N], v[G::N];
+    inv_x_compute<G>(xt, blk, team, a, v);
+    static_for<0, G::ROUNDS>([&](auto ri) {
+        constexpr int r = decltype(ri)::value;
+        if constexpr (r > 0) __syncthreads();   // every lane has gathered the previous rows
+        if (team == r) inv_x_write<G>(xt, lds, v);
         __syncthreads();
-        inv_x<G>(tid, blk, 1, a, lds);
-        __syncthreads();
-        inv_y_gather<G, 1>(tid, lds, z);
-    }
+        inv_y_gather<G, r>(tid, lds, z);
+    });
     inv_y_finish<G, ACC>(tid, blk, a, z);
 }
 #endif

@@ -358,10 +358,10 @@ int fftconv_plan_destroy(fftconv_plan_t p)
 {
     if (!p) return FFTCONV_EINVAL;
     for (ProfileRecord &r : p->records) {
-        hipEventDestroy(r.start);
-        hipEventDestroy(r.stop);
+        (void)hipEventDestroy(r.start);
+        (void)hipEventDestroy(r.stop);
     }
-    for (hipEvent_t e : p->free_events) hipEventDestroy(e);
+    for (hipEvent_t e : p->free_events) (void)hipEventDestroy(e);
     delete p;
     return FFTCONV_OK;
 }
