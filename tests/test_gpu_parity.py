@@ -261,6 +261,46 @@ def test_passes_in_any_order_and_on_a_side_stream(fc):
     check(dw.cpu().numpy(), direct.accgrad(g, x, layer.k), "order accgrad")
 
 
+@pytest.mark.parametrize("layer", [SMALL_LAYERS[5], SMALL_LAYERS[7]], ids=lambda l: l.name)
+def test_step_can_be_captured_in_a_graph(fc, layer):
+    """The passes only enqueue kernels on the given stream (no allocation, no host sync, no
+    memset), so a caller may capture a whole step in a HIP graph.  Every replay, with eager
+    work of the same plan in between, must reproduce the eager result bit for bit."""
+    x, w, g = wl.make_inputs(layer)
+    xd, wd, gd = dev(x), dev(w), dev(g)
+    plan = fc.Plan(layer.S, layer.f, layer.fo, layer.n, layer.k)
+    plan.alloc_workspace()
+    y = torch.empty(layer.shapes()[2], dtype=torch.float32, device="cuda")
+    dx, dw = torch.empty_like(xd), torch.empty_like(wd)
+
+    def step():
+        plan.invalidate()
+        plan.fprop(xd, wd, y)
+        plan.bprop(gd, wd, dx)
+        plan.accgrad(gd, xd, dw)
+
+    step()
+    torch.cuda.synchronize()
+    ref = (y.clone(), dx.clone(), dw.clone())
+    check(ref[0].cpu().numpy(), direct.fprop(x, w), f"{layer.name} fprop (eager)")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    for i in range(3):
+        for t in (y, dx, dw):
+            t.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, ref[0]) and torch.equal(dx, ref[1]) and torch.equal(dw, ref[2]), f"replay {i}"
+        # eager work of the same plan between replays: other inputs through the same workspace
+        plan.invalidate()
+        plan.fprop(xd * 2.0, wd, y)
+        torch.cuda.synchronize()
+        assert torch.equal(y, 2.0 * ref[0])
+
+
 def test_stage_calls_compose_to_a_pass(fc):
     layer = wl.Layer("stages", 4, 6, 5, 32, 7, 0.05, 73)
     x, w, g = wl.make_inputs(layer)
