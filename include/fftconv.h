@@ -8,7 +8,8 @@
  * "*" is read as the cross-correlation of neural-network layers.
  *
  * Every pass follows Sec. 2.2: each 2-D map is Fourier-transformed once (zero
- * padded to N x N, N = n rounded up to a power of two, Sec. 4), the products are
+ * padded to N x N, N = the smallest of 8, 12, 16, 24, 32, 48, 64 that is >= n;
+ * Sec. 4 pads to a power of two, the sizes 3 * 2^m cut its padding waste), the products are
  * accumulated per frequency bin over the summed index, and the result is
  * inverse-transformed and cropped.  The spectra of x, w and dL/dy are kept in a
  * caller-owned workspace and reused by later passes (the "keep the Fourier
@@ -83,7 +84,7 @@ enum {
 int fftconv_plan(fftconv_plan_t *out, const fftconv_desc *d);
 int fftconv_plan_destroy(fftconv_plan_t p);
 
-/* Transform size N (power of two, >= n) and number of stored bins B = N*N/2 + 2:
+/* Transform size N (2^m or 3 * 2^m, >= n) and number of stored bins B = N*N/2 + 2:
  * the part of the spectrum a real map determines (Sec. 2.3), i.e. every bin that
  * is not the complex conjugate of another stored bin. */
 int fftconv_fft_size(fftconv_plan_t p);

@@ -1,8 +1,10 @@
-// In-register power-of-two complex FFTs with compile-time indexing.
+// In-register complex FFTs of size 2^m or 3 * 2^m with compile-time indexing.
 //
 // Every array index below is a compile-time constant after template expansion,
 // so an N-point transform lives entirely in N complex registers of one lane
-// (no scratch memory).  The same header compiles for gfx950 device code and,
+// (no scratch memory).  Sizes with a factor 3 (12, 24, 48) exist so that an
+// input need not be padded all the way to the next power of two, the limitation
+// the paper points out in Sec. 4.  The same header compiles for gfx950 device code and,
 // without HIP, for a host build that replays the kernels' phases on the CPU.
 //
 // The 1-D transforms are the row / column building blocks of the 2-D
@@ -74,22 +76,68 @@ constexpr double sin64(int j) { return cos64(j + 48); }   // sin(t) = cos(t - pi
 
 constexpr int ilog2(int n) { return n <= 1 ? 0 : 1 + ilog2(n >> 1); }
 
-// Bit reversal of i within log2(N) bits.
-template <int N>
-constexpr int brev(int i)
+// N = radix3_part(N) * pow2_part(N) with radix3_part in {1, 3}.
+constexpr int radix3_part(int N) { return N % 3 == 0 ? 3 : 1; }
+constexpr int pow2_part(int N) { return N / radix3_part(N); }
+constexpr bool fft_size_ok(int N) { const int M = pow2_part(N); return M >= 2 && (M & (M - 1)) == 0 && N <= 64; }
+
+// Bit reversal of i within log2(M) bits.
+constexpr int bitrev(int i, int M)
 {
     int r = 0;
-    for (int b = 0; b < ilog2(N); ++b)
-        if (i & (1 << b)) r |= 1 << (ilog2(N) - 1 - b);
+    for (int b = 0; b < ilog2(M); ++b)
+        if (i & (1 << b)) r |= 1 << (ilog2(M) - 1 - b);
     return r;
 }
+
+// Position at which fft_dif leaves output X[k].  For N = 2^m the bit reversal of k; for
+// N = 3 * M the radix-3 stage sends the outputs k = 3 q + r to block r, whose M-point
+// transform leaves X[3 q + r] at bit-reversed q.
+template <int N>
+constexpr int brev(int k)
+{
+    constexpr int R = radix3_part(N), M = pow2_part(N);
+    return (k % R) * M + bitrev(k / R, M);
+}
+
+// cos / sin of 2*pi*p/d for angles that are not multiples of pi/32, evaluated at compile
+// time in double precision (series on an angle reduced to at most pi/4).
+constexpr double kPi = 3.141592653589793238462643383279502884;
+constexpr double series_cos(double x)
+{
+    double term = 1.0, sum = 1.0;
+    for (int i = 1; i <= 14; ++i) { term *= -x * x / ((2 * i - 1) * (2 * i)); sum += term; }
+    return sum;
+}
+constexpr double series_sin(double x)
+{
+    double term = x, sum = x;
+    for (int i = 1; i <= 14; ++i) { term *= -x * x / ((2 * i) * (2 * i + 1)); sum += term; }
+    return sum;
+}
+constexpr double cos_ratio(long p, long d)   // cos(2 pi p / d)
+{
+    p %= d;
+    if (p < 0) p += d;
+    if (2 * p > d) p = d - p;                               // angle in [0, pi]
+    if (4 * p > d) return -cos_ratio(d - 2 * p, 2 * d);     // cos(t) = -cos(pi - t)
+    if (4 * p == d) return 0.0;
+    if (8 * p > d) return series_sin(2.0 * kPi * (double)(d - 4 * p) / (double)(4 * d));   // cos(t) = sin(pi/2 - t)
+    return series_cos(2.0 * kPi * (double)p / (double)d);
+}
+
+// cos / sin of 2*pi*q/N: from the table when the angle is a multiple of 2*pi/64, else computed.
+template <int N>
+constexpr double cos_n(int q) { return 64 % N == 0 ? cos64(q * (64 / N)) : cos_ratio(q, N); }
+template <int N>
+constexpr double sin_n(int q) { return 64 % N == 0 ? sin64(q * (64 / N)) : cos_ratio(4L * q - N, 4L * N); }
 
 // Multiply v by exp(-/+ 2*pi*i*Q/N) (minus for forward, plus for inverse) with
 // the trivial angles done without multiplications.
 template <int N, int Q, bool INV>
 FC_HD cf twiddle_mul(cf v)
 {
-    static_assert(N <= 64 && (64 % N) == 0, "twiddle table covers N up to 64");
+    static_assert(fft_size_ok(N), "transform sizes are 2^m or 3 * 2^m, at most 64");
     constexpr int q = ((Q % N) + N) % N;
     if constexpr (q == 0) {
         return v;
@@ -100,8 +148,8 @@ FC_HD cf twiddle_mul(cf v)
     } else if constexpr (4 * q == 3 * N) {       // +i (forward) or -i (inverse)
         return INV ? mk(v.y, -v.x) : mk(-v.y, v.x);
     } else {
-        constexpr float wr = (float)cos64(q * (64 / N));
-        constexpr float wi = (float)(INV ? sin64(q * (64 / N)) : -sin64(q * (64 / N)));
+        constexpr float wr = (float)cos_n<N>(q);
+        constexpr float wi = (float)(INV ? sin_n<N>(q) : -sin_n<N>(q));
         if constexpr (8 * q == N || 8 * q == 3 * N || 8 * q == 5 * N || 8 * q == 7 * N) {
             // |wr| == |wi| == sqrt(1/2): two adds and two multiplies
             constexpr float c = (float)kCos64[8];
@@ -118,7 +166,20 @@ FC_HD cf twiddle_mul(cf v)
 // "element i is known to be exactly zero at compile time".
 constexpr uint64_t low_mask(int n) { return n >= 64 ? ~0ull : ((1ull << n) - 1ull); }
 
-// Mask after one decimation-in-frequency stage with half-span h.
+// Mask after the radix-3 stage of an N = 3 M point transform: output r of butterfly j
+// (position r M + j) is zero iff all three inputs j, j + M, j + 2 M are.
+template <int N>
+constexpr uint64_t radix3_stage_mask(uint64_t zm)
+{
+    constexpr int M = N / 3;
+    uint64_t out = 0;
+    for (int j = 0; j < M; ++j)
+        if (((zm >> j) & 1) && ((zm >> (j + M)) & 1) && ((zm >> (j + 2 * M)) & 1))
+            out |= (1ull << j) | (1ull << (j + M)) | (1ull << (j + 2 * M));
+    return out;
+}
+
+// Mask after one radix-2 decimation-in-frequency stage with half-span h.
 template <int N>
 constexpr uint64_t dif_stage_mask(uint64_t zm, int h)
 {
@@ -131,10 +192,12 @@ constexpr uint64_t dif_stage_mask(uint64_t zm, int h)
     return out;
 }
 
+// Known zeros in front of radix-2 stage `stage` (after the radix-3 stage, if N has one).
 template <int N>
 constexpr uint64_t dif_mask_before_stage(uint64_t zm, int stage)
 {
-    int h = N / 2;
+    if (radix3_part(N) == 3) zm = radix3_stage_mask<N>(zm);
+    int h = pow2_part(N) / 2;
     for (int s = 0; s < stage; ++s) {
         zm = dif_stage_mask<N>(zm, h);
         h /= 2;
@@ -143,15 +206,17 @@ constexpr uint64_t dif_mask_before_stage(uint64_t zm, int stage)
 }
 
 // Output pruning: bit i of a "need" mask set means "position i is read after
-// the transform" (positions are the bit-reversed ones the DIF leaves its
-// results in).  need_after_stage<N>(final, s) is the set of positions whose
-// value after stage s is still needed by some requested output.
+// the transform" (positions are the ones brev<N> names).  need_after_stage<N>(final, s)
+// is the set of positions whose value after radix-2 stage s is still needed by some
+// requested output; s = -1 gives what is needed in front of the first radix-2 stage,
+// i.e. of the radix-3 stage's outputs.
 template <int N>
 constexpr uint64_t need_after_stage(uint64_t need_final, int stage)
 {
+    constexpr int M = pow2_part(N);
     uint64_t need = need_final;
-    for (int st = ilog2(N) - 1; st > stage; --st) {
-        const int h = N >> (st + 1);
+    for (int st = ilog2(M) - 1; st > stage; --st) {
+        const int h = M >> (st + 1);
         uint64_t prev = 0;
         for (int s = 0; s < N; s += 2 * h)
             for (int j = 0; j < h; ++j)
@@ -162,7 +227,7 @@ constexpr uint64_t need_after_stage(uint64_t need_final, int stage)
     return need;
 }
 
-// Positions (bit-reversed) that hold natural-order outputs 0..count-1.
+// Positions that hold natural-order outputs 0..count-1.
 template <int N>
 constexpr uint64_t first_outputs_mask(int count)
 {
@@ -171,8 +236,34 @@ constexpr uint64_t first_outputs_mask(int count)
     return m;
 }
 
-// Radix-2 decimation-in-frequency FFT, in place, natural-order input,
-// BIT-REVERSED output: X[k] = v[brev<N>(k)].
+// Radix-3 decimation-in-frequency butterfly j of an N = 3 M point transform, in place on
+// a = v[j], b = v[j + M], c = v[j + 2 M]:
+//     y_r = (a + w^r b + w^{2r} c) * exp(-/+ 2 pi i r j / N),   w = exp(-/+ 2 pi i / 3)
+// ZB / ZC: b / c known to be zero (zero padding fills a map from the high indices down, so a
+// known-zero b implies a known-zero c).  N0..N2: which outputs are read later.
+template <int N, bool INV, int J, bool ZB, bool ZC, bool N0, bool N1, bool N2>
+FC_HD void radix3_butterfly(cf &a, cf &b, cf &c)
+{
+    static_assert(!ZB || ZC, "zero padding is a suffix");
+    constexpr float kHalfSqrt3 = 0.8660254037844386f;
+    if constexpr (ZB) {           // only a: y_r = a * twiddle
+        if constexpr (N1) b = twiddle_mul<N, J, INV>(a);
+        if constexpr (N2) c = twiddle_mul<N, 2 * J, INV>(a);
+    } else {
+        cf s, d;                  // b + c, b - c
+        if constexpr (ZC) { s = b; d = b; }
+        else { s = b + c; d = b - c; }
+        const cf t = mk(a.x - 0.5f * s.x, a.y - 0.5f * s.y);
+        const cf e = mk(kHalfSqrt3 * d.y, -kHalfSqrt3 * d.x);   // -i sqrt(3)/2 (b - c)
+        if constexpr (N0) a = a + s;
+        if constexpr (N1) b = twiddle_mul<N, J, INV>(INV ? t - e : t + e);
+        if constexpr (N2) c = twiddle_mul<N, 2 * J, INV>(INV ? t + e : t - e);
+    }
+}
+
+// Decimation-in-frequency FFT, in place, natural-order input, outputs left at the
+// positions brev<N> names: X[k] = v[brev<N>(k)].  One radix-3 stage first if N = 3 * 2^m,
+// then radix-2 stages.
 // ZMASK marks inputs known to be zero (their registers are never read), which
 // removes the arithmetic a zero-padded map does not need.  NEED marks the
 // output positions that will be read; the others are left undefined, which
@@ -180,9 +271,22 @@ constexpr uint64_t first_outputs_mask(int count)
 template <int N, bool INV, uint64_t ZMASK = 0, uint64_t NEED = ~0ull>
 FC_HD void fft_dif(cf (&v)[N])
 {
-    static_for<0, ilog2(N)>([&](auto st) {
+    static_assert(fft_size_ok(N), "transform sizes are 2^m or 3 * 2^m, at most 64");
+    constexpr int M = pow2_part(N);
+    if constexpr (radix3_part(N) == 3) {
+        constexpr uint64_t nd = need_after_stage<N>(NEED, -1);
+        static_for<0, M>([&](auto ji) {
+            constexpr int j = decltype(ji)::value;
+            constexpr bool za = (ZMASK >> j) & 1, zb = (ZMASK >> (j + M)) & 1, zc = (ZMASK >> (j + 2 * M)) & 1;
+            static_assert(!za || (zb && zc), "zero padding is a suffix");
+            if constexpr (!za)
+                radix3_butterfly<N, INV, j, zb, zc, (nd >> j) & 1, (nd >> (j + M)) & 1, (nd >> (j + 2 * M)) & 1>(
+                    v[j], v[j + M], v[j + 2 * M]);
+        });
+    }
+    static_for<0, ilog2(M)>([&](auto st) {
         constexpr int stage = decltype(st)::value;
-        constexpr int h = N >> (stage + 1);
+        constexpr int h = M >> (stage + 1);
         constexpr uint64_t zm = dif_mask_before_stage<N>(ZMASK, stage);
         constexpr uint64_t nd = need_after_stage<N>(NEED, stage);
         static_for<0, N / 2>([&](auto bi) {
@@ -203,7 +307,7 @@ FC_HD void fft_dif(cf (&v)[N])
             } else {
                 const cf a = v[ia], c = v[ib];
                 if constexpr (na) v[ia] = a + c;
-                if constexpr (nb) v[ib] = twiddle_mul<N, Q, INV>(a - c);
+                if constexpr (nb) v[ib] = twiddle_mul<N, Q + 0, INV>(a - c);
             }
         });
     });

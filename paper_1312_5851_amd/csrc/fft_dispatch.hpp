@@ -7,29 +7,34 @@
 namespace fftconv {
 
 // X(N, T, NX): transform size, maps per workgroup, non-zero / needed extent class.
-// T * N / 2 lanes: 256, except 512 at N = 64 (16 maps, so that a bin is still stored as one
-// full 128-byte run).
+// T * N / 2 lanes.  T is at least 16 so that a bin is stored as a full 128-byte run.
 #define FFTCONV_FOR_EACH_GEOM(X) \
     X(8, 64, 8)   X(8, 64, 4)                 \
+    X(12, 32, 12) X(12, 32, 6)                \
     X(16, 32, 16) X(16, 32, 8)  X(16, 32, 4)  \
+    X(24, 16, 24) X(24, 16, 12) X(24, 16, 6)  \
     X(32, 16, 32) X(32, 16, 16) X(32, 16, 8)  \
+    X(48, 16, 48) X(48, 16, 24) X(48, 16, 12) \
     X(64, 16, 64) X(64, 16, 32) X(64, 16, 16)
 
-// Transform size for an n x n input: n rounded up to a power of two (Sec. 4 of
-// the paper: sizes that are not a power of two are padded to the next one).
+// Transform size for an n x n input: the smallest of 8, 12, 16, 24, 32, 48, 64 that holds
+// it.  The paper pads to the next power of two and names the waste for sizes just above
+// one as its limitation (Sec. 4); the sizes 3 * 2^m halve the worst-case padding.
 inline int fft_size_for(int n)
 {
-    int N = 8;
-    while (N < n) N *= 2;
-    return N;
+    static const int sizes[] = {8, 12, 16, 24, 32, 48, 64};
+    for (int N : sizes)
+        if (N >= n) return N;
+    return -1;
 }
 
-inline int maps_per_block(int N) { return N >= 64 ? 16 : 512 / N; }
+constexpr int maps_per_block(int N) { return N <= 8 ? 64 : (N <= 16 ? 32 : 16); }
 
-// LDS hand-overs between the two phases: two at N = 64, where one would not fit the 160 KB
-// of LDS.  (At N = 32 two rounds let four workgroups share a CU instead of two; inside the
-// full step that measured the same as one round, so N = 32 keeps the simpler single round.)
-constexpr int rounds_for(int N) { return N >= 64 ? 2 : 1; }
+// LDS hand-overs between the two phases: two from N = 48 up, where one would not fit the
+// 160 KB of LDS or would leave room for a single workgroup per CU.  (At N = 32 two rounds
+// let four workgroups share a CU instead of two; inside the full step that measured the same
+// as one round, so N = 32 keeps the simpler single round.)
+constexpr int rounds_for(int N) { return N >= 48 ? 2 : 1; }
 
 // Smallest compiled extent class that covers `ext` columns of an N-point transform.
 inline int extent_class(int N, int ext)

@@ -77,8 +77,9 @@ extern "C" {
 
 int replay_fft_size(int n) { return fft_size_for(n); }
 int replay_extent_class(int N, int ext) { return extent_class(N, ext); }
+int replay_maps_per_block(int N) { return maps_per_block(N); }
 
-// src: [M][ext][ext] floats; spec: [B][M] complex (2 floats each), B = (N/2+1)*N.
+// src: [M][ext][ext] floats; spec: [B][M] complex (2 floats each), B = N*N/2 + 2.
 int replay_fft2d_r2c(int N, const float *src, float *spec, int M, int ext)
 {
     FwdArgs a{src, reinterpret_cast<cf *>(spec), M, ext};

@@ -38,9 +38,11 @@ def test_signatures_carry_no_torch_types():
     assert "torch" not in text.lower() and "at::" not in text and "hipStream_t stream" not in text
 
 
-@pytest.mark.parametrize("n,N", [(1, 8), (8, 8), (9, 16), (16, 16), (17, 32), (32, 32), (33, 64), (34, 64), (64, 64)])
-def test_fft_size_is_next_power_of_two(fc, n, N):
-    # Sec. 4: sizes that are not a power of two are padded to the next one (34 -> 64)
+@pytest.mark.parametrize("n,N", [(1, 8), (8, 8), (9, 12), (12, 12), (13, 16), (16, 16), (17, 24), (24, 24), (25, 32),
+                                 (32, 32), (33, 48), (34, 48), (48, 48), (49, 64), (64, 64)])
+def test_fft_size_is_smallest_compiled_size(fc, n, N):
+    # Sec. 4 pads sizes that are not a power of two to the next one (34 -> 64) and names that as the
+    # method's limitation; here the sizes 3 * 2^m are compiled as well (34 -> 48)
     p = fc.Plan(2, 3, 4, n, 1)
     assert p.fft_size == N and p.num_bins == N * N // 2 + 2
 

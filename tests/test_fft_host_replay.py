@@ -46,16 +46,24 @@ def naive_dft2(pad):
     return np.einsum("ky,myx,lx->mkl", W, pad, W)
 
 
+SIZES = [8, 12, 16, 24, 32, 48, 64]
+
+
 def test_size_rules(replay):
-    assert [replay.replay_fft_size(n) for n in (1, 8, 9, 16, 17, 34, 64)] == [8, 8, 16, 16, 32, 64, 64]
+    assert [replay.replay_fft_size(n) for n in (1, 8, 9, 12, 13, 16, 17, 24, 25, 32, 33, 34, 48, 49, 64)] == \
+        [8, 8, 12, 12, 16, 16, 24, 24, 32, 32, 48, 48, 48, 64, 64]
+    assert replay.replay_fft_size(65) == -1
+    assert [replay.replay_maps_per_block(N) for N in SIZES] == [64, 32, 32, 16, 16, 16, 16]
+    assert replay.replay_extent_class(12, 3) == 6 and replay.replay_extent_class(24, 5) == 6
+    assert replay.replay_extent_class(48, 13) == 24 and replay.replay_extent_class(48, 25) == 48
     assert replay.replay_extent_class(32, 5) == 8 and replay.replay_extent_class(32, 9) == 16
     assert replay.replay_extent_class(32, 28) == 32 and replay.replay_extent_class(8, 2) == 4
 
 
-@pytest.mark.parametrize("N", [8, 16, 32, 64])
+@pytest.mark.parametrize("N", SIZES)
 def test_forward_matches_naive_dft_and_fft2(replay, N):
     rng = np.random.default_rng(N)
-    T = 512 // N
+    T = replay.replay_maps_per_block(N)
     for ext in sorted({1, 3, N // 4, N // 4 + 1, N // 2, N // 2 + 1, N - 3, N}):
         for M in (1, T - 1, T + 3):
             src = rng.uniform(-1, 1, (M, ext, ext)).astype(np.float32)
@@ -63,16 +71,16 @@ def test_forward_matches_naive_dft_and_fft2(replay, N):
             got = forward(replay, src, N)
             ref = reference_spectrum(src, N)
             assert np.abs(got - ref).max() <= 3e-6 * max(np.abs(ref).max(), 1), (N, ext, M)
-            if N <= 16 and M == 1:
+            if N <= 24 and M == 1:
                 ky, kx = stored_bins(N)
                 nv = naive_dft2(pad)[:, ky, kx].T
                 assert np.abs(got - nv).max() <= 3e-6 * max(np.abs(nv).max(), 1)
 
 
-@pytest.mark.parametrize("N", [8, 16, 32, 64])
+@pytest.mark.parametrize("N", SIZES)
 def test_inverse_crops_scales_and_accumulates(replay, N):
     rng = np.random.default_rng(100 + N)
-    T = 512 // N
+    T = replay.replay_maps_per_block(N)
     for crop in sorted({1, 3, N // 4, N // 4 + 1, N // 2 + 1, N - 2, N}):
         for M in (2, T + 1):
             full = rng.uniform(-1, 1, (M, N, N))
@@ -84,8 +92,8 @@ def test_inverse_crops_scales_and_accumulates(replay, N):
             assert np.abs(acc - (base + full[:, :crop, :crop])).max() < 3e-6
 
 
-def test_impulse_constant_and_round_trip(replay):
-    N = 16
+@pytest.mark.parametrize("N", [16, 24])
+def test_impulse_constant_and_round_trip(replay, N):
     imp = np.zeros((3, N, N), np.float32); imp[:, 0, 0] = 1
     s = forward(replay, imp, N)
     assert np.array_equal(s, np.ones_like(s))

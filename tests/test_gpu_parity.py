@@ -59,7 +59,7 @@ SMALL_LAYERS = [
     wl.Layer("ragged16", 3, 5, 7, 13, 4, 0.1, 11),      # N=16, odd map counts, ragged tiles
     wl.Layer("k1", 2, 3, 4, 16, 1, 0.1, 12),            # k = 1
     wl.Layer("k_eq_n", 2, 3, 2, 8, 8, 0.1, 13),         # k = n, single output pixel, N=8
-    wl.Layer("n9", 2, 2, 3, 9, 3, 0.1, 14),             # n just above a power of two -> N=16
+    wl.Layer("n9", 2, 2, 3, 9, 3, 0.1, 14),             # n just above a power of two -> N=12
     wl.Layer("ragged32", 5, 7, 9, 29, 6, 0.05, 15),     # N=32, nothing a multiple of anything
     wl.Layer("n32k13", 4, 6, 5, 32, 13, 0.05, 16),
     wl.Layer("ragged64", 3, 3, 5, 50, 11, 0.05, 17),    # N=64
@@ -194,8 +194,16 @@ def test_memory_efficient_mode_matches_cached_mode_at_full_size(fc):
 EDGE_LAYERS = [
     wl.Layer("n64_k1", 2, 3, 2, 64, 1, 0.1, 61),          # largest transform, k = 1
     wl.Layer("n64_k64", 2, 2, 3, 64, 64, 0.05, 62),       # k = n = 64: one output pixel
-    wl.Layer("n33", 2, 3, 2, 33, 2, 0.1, 63),             # just above 32 -> N = 64 with a lot of padding
-    wl.Layer("n17_k17", 3, 2, 2, 17, 17, 0.1, 64),        # N = 32, k = n
+    wl.Layer("n33", 2, 3, 2, 33, 2, 0.1, 63),             # just above 32 -> N = 48
+    wl.Layer("n49", 2, 3, 2, 49, 4, 0.1, 72),             # just above 48 -> N = 64 with a lot of padding
+    wl.Layer("n17_k17", 3, 2, 2, 17, 17, 0.1, 64),        # N = 24, k = n
+    wl.Layer("n25_k25", 3, 2, 2, 25, 25, 0.1, 73),        # N = 32, k = n
+    wl.Layer("n48_k48", 2, 2, 3, 48, 48, 0.05, 74),       # N = 48 with no padding, k = n
+    wl.Layer("n24_k2", 3, 4, 5, 24, 2, 0.1, 75),          # N = 24 with no padding
+    wl.Layer("n12_k12", 5, 3, 2, 12, 12, 0.1, 76),        # N = 12, k = n
+    wl.Layer("n11_k4", 35, 3, 2, 11, 4, 0.1, 77),         # N = 12, 105 / 70 maps: ragged tiles of 32
+    wl.Layer("n40_k9", 2, 9, 4, 40, 9, 0.05, 78),         # N = 48, w in the smallest extent class
+    wl.Layer("n44_k20", 2, 3, 9, 44, 20, 0.05, 79),       # N = 48, middle extent classes
     wl.Layer("n8_k3", 5, 3, 4, 8, 3, 0.1, 65),            # N = 8
     wl.Layer("n5_k2", 3, 2, 2, 5, 2, 0.1, 66),            # n below the smallest transform
     wl.Layer("n1", 4, 3, 2, 1, 1, 0.1, 67),               # 1x1 maps
@@ -317,13 +325,14 @@ def test_stage_calls_compose_to_a_pass(fc):
     check(y.cpu().numpy(), direct.fprop(x, w), "stages fprop")
 
 
-def test_spectrum_stage_against_fft2(fc):
+@pytest.mark.parametrize("n,N_expected", [(20, 24), (28, 32), (11, 12), (40, 48), (52, 64)])
+def test_spectrum_stage_against_fft2(fc, n, N_expected):
     """Forward stage alone: slot contents equal the half spectrum of the zero-padded maps."""
-    layer = wl.Layer("stage", 3, 5, 4, 20, 6, 0.1, 31)
+    layer = wl.Layer("stage", 3, 5, 4, n, 6, 0.1, 31)
     x, w, g = wl.make_inputs(layer)
     plan = fc.Plan(layer.S, layer.f, layer.fo, layer.n, layer.k)
     N = plan.fft_size
-    assert N == 32 and plan.num_bins == N * N // 2 + 2
+    assert N == N_expected and plan.num_bins == N * N // 2 + 2
     for slot, arr in ((fc.SPEC_X, x), (fc.SPEC_W, w), (fc.SPEC_G, g)):
         plan.forward_transform(slot, dev(arr))
         torch.cuda.synchronize()
