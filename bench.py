@@ -204,7 +204,7 @@ def measure(layer, args, inputs=None):
     # and per stored bin.  The kernel issues fewer matrix-core flops than that (three real
     # products per complex product instead of four), reported next to it as "issued".
     B = plan.num_bins
-    algo_flops = 8.0 * layer.S * layer.f * layer.fo * B
+    algo_flops = plan.contraction_flops * 8.0 / 6.0   # = 8 S f f' B for a layer that is not tiled
     roofline = None
     if all(gemm_live[n] for n in gemm_names):
         gemm_ms = float(np.mean([gemm_live[n] for n in gemm_names]))
@@ -224,24 +224,30 @@ def measure(layer, args, inputs=None):
                     "issued_frac": issued / PEAK_FP32_MFMA_TFLOPS}
         # With few maps on one side (f = 3) the product has less arithmetic per byte than the chip's
         # ridge point: the same launches are then bound by HBM, and that is the roof to price them against.
-        min_bytes = 8.0 * B * (layer.S * layer.f + layer.f * layer.fo + layer.S * layer.fo)
+        min_bytes = 8.0 * B * (plan.slot_maps(fc.SPEC_X) + plan.slot_maps(fc.SPEC_W) + plan.slot_maps(fc.SPEC_G))
         roofline["min_bytes_per_launch"] = min_bytes
         if algo_flops / min_bytes < PEAK_FP32_MFMA_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
             gbs = min_bytes / (gemm_ms * 1e-3) / 1e9
             roofline.update({"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                              "frac": gbs / PEAK_HBM_GBS, "mfma_TFLOPs": achieved})
     # HBM-side view of the transform stages: algorithmic bytes = unpadded real map + stored half spectrum
-    ext = {"fft_x": (layer.n, layer.S * layer.f), "fft_w": (layer.k, layer.fo * layer.f),
-           "fft_g": (layer.no, layer.S * layer.fo), "ifft_y": (layer.no, layer.S * layer.fo),
-           "ifft_dx": (layer.n, layer.S * layer.f), "ifft_dw": (layer.k, layer.fo * layer.f)}
+    # (images, image extent, transforms): a layer with n > 64 runs one transform per tile
+    L, nt, nt2 = plan.tiling
+    T, T2 = nt * nt, nt2 * nt2
+    ext = {"fft_x": (layer.S * layer.f, layer.n, layer.S * layer.f * T),
+           "fft_w": (layer.fo * layer.f, layer.k, layer.fo * layer.f),
+           "fft_g": (layer.S * layer.fo, layer.no, layer.S * layer.fo * (T + T2) / 2 if L else layer.S * layer.fo),
+           "ifft_y": (layer.S * layer.fo, layer.no, layer.S * layer.fo * T),
+           "ifft_dx": (layer.S * layer.f, layer.n, layer.S * layer.f * T2),
+           "ifft_dw": (layer.fo * layer.f, layer.k, layer.fo * layer.f)}
     stage_report = {}
     for name, ms in stages.items():
         if ms is None:
             continue
         rec = {"avg_ms": ms}
         if name in ext:
-            e, M = ext[name]
-            nbytes = M * (4 * e * e + 8 * B)
+            images, e, transforms = ext[name]
+            nbytes = images * 4 * e * e + transforms * 8 * B
             rec["algorithmic_bytes"] = nbytes
             rec["GBps"] = nbytes / (ms * 1e-3) / 1e9
             rec["frac_hbm_peak"] = rec["GBps"] / PEAK_HBM_GBS
@@ -258,7 +264,8 @@ def measure(layer, args, inputs=None):
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{layer.name}: S={layer.S} f={layer.f} f'={layer.fo} n={layer.n} k={layer.k} "
-                               f"(N={plan.fft_size}, {B} bins); step = FFT(x,w,dL/dy) + 3 contractions + 3 inverse+crop",
+                               f"(N={plan.fft_size}, {B} bins" + (f", {nt}x{nt} / {nt2}x{nt2} tiles of {L}" if L else "") +
+                               "); step = FFT(x,w,dL/dy) + 3 contractions + 3 inverse+crop",
                    "seed": layer.seed},
         "passes": passes,
         "memory_efficient_mode": memory_efficient,
@@ -274,7 +281,8 @@ def write_report(args):
     from paper_1312_5851_amd import workloads as wl
     a = copy.copy(args)
     a.steps, a.warmup, a.calibration_copy = 20, 3, False
-    layers = list(wl.CONFIGS.values()) + wl.sweep_layers() + wl.paper_table_layers() + wl.fig3_layers()
+    layers = (list(wl.CONFIGS.values()) + wl.sweep_layers() + wl.paper_table_layers() + wl.fig3_layers()
+              + wl.large_layers())
     recs = []
     for layer in layers:
         log(f"report: {layer.name}")

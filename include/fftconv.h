@@ -56,14 +56,16 @@ enum { FFTCONV_RECOMPUTE = 1 };
 enum {
     FFTCONV_OK = 0,
     FFTCONV_EINVAL = 1,       /* null pointer, non-positive size, k > n, bad slot/pass */
-    FFTCONV_EUNSUPPORTED = 2, /* n > 64 (no compiled transform size) or unknown flag bits */
+    FFTCONV_EUNSUPPORTED = 2, /* k > 64 with n > 64, more than 2^31 transforms in a slot, or unknown flag bits */
     FFTCONV_EWORKSPACE = 3,   /* workspace pointer null or not 256-byte aligned */
     FFTCONV_ELAUNCH = 4,      /* the HIP runtime refused a launch or an event call */
     FFTCONV_ENOTREADY = 5     /* a stage-level call needs a spectrum that is not cached */
 };
 
-/* Spectral cache slots (bit flags) and the scratch slot holding a pass's result spectrum. */
-enum { FFTCONV_SPEC_X = 1, FFTCONV_SPEC_W = 2, FFTCONV_SPEC_G = 4, FFTCONV_SPEC_OUT = 8 };
+/* Spectral cache slots (bit flags) and the scratch slot holding a pass's result spectrum.
+ * FFTCONV_SPEC_G2 exists only for tiled layers (n > 64, see fftconv_tiling): the windows
+ * of dL/dy that bprop transforms, which differ from the blocks accGrad transforms. */
+enum { FFTCONV_SPEC_X = 1, FFTCONV_SPEC_W = 2, FFTCONV_SPEC_G = 4, FFTCONV_SPEC_OUT = 8, FFTCONV_SPEC_G2 = 16 };
 
 /* Passes: Eq. (1), (2), (3) of Sec. 2.1. */
 enum { FFTCONV_FPROP = 0, FFTCONV_BPROP = 1, FFTCONV_ACCGRAD = 2 };
@@ -78,9 +80,10 @@ enum {
 
 /* ---- plan (host only) -------------------------------------------------- */
 
-/* Validates the layer and fixes N, the bin count and the workspace layout.
- * Errors: EINVAL for null arguments, sizes < 1 or k > n; EUNSUPPORTED for n > 64
- * or unknown flag bits.  *out is written only on success. */
+/* Validates the layer and fixes N, the bin count, the tiling and the workspace layout.
+ * Errors: EINVAL for null arguments, sizes < 1 or k > n; EUNSUPPORTED for k > 64 with
+ * n > 64, for slots of more than 2^31 transforms, or for unknown flag bits.  *out is
+ * written only on success. */
 int fftconv_plan(fftconv_plan_t *out, const fftconv_desc *d);
 int fftconv_plan_destroy(fftconv_plan_t p);
 
@@ -90,10 +93,23 @@ int fftconv_plan_destroy(fftconv_plan_t p);
 int fftconv_fft_size(fftconv_plan_t p);
 int fftconv_num_bins(fftconv_plan_t p);
 
+/* Layers with n > 64 are cut into tiles (the paper instead pads the whole map to the next
+ * power of two, Sec. 4).  With L = N - k + 1: y and dL/dy are cut into ceil(no / L)^2 blocks
+ * of L x L, dx into ceil(n / L)^2.  fprop transforms the N x N window of x under each
+ * block of y, multiplies and keeps rows / columns [0, L) of the inverse transform; accGrad
+ * multiplies the same windows with the transforms of the zero-padded blocks of dL/dy and
+ * sums over samples and tiles; bprop transforms, for each block of dx, the N x N window of
+ * dL/dy that starts k - 1 rows and columns before it and keeps rows / columns [k-1, N) of
+ * the inverse transform (the part of a circular result that no wrap-around touches).  The
+ * tiles of a sample act as extra samples for the contraction.
+ * *tile = L (0: not tiled), *tiles_y and *tiles_dx = blocks per dimension (1 if not tiled). */
+int fftconv_tiling(fftconv_plan_t p, int *tile, int *tiles_y, int *tiles_dx);
+
 /* Bytes of device workspace the passes need: the x, w and g spectra (8*B bytes
  * per map for S*f + fo*f + S*fo maps, the count of Sec. 2.3) plus one result
  * spectrum of 8*B*max(S*fo, S*f, fo*f) bytes; each slot 256-byte aligned.
- * With FFTCONV_RECOMPUTE: the three slots only. */
+ * With FFTCONV_RECOMPUTE: the three slots only.  Tiled layers hold one transform per
+ * tile (fftconv_slot_maps) and one more slot, FFTCONV_SPEC_G2. */
 size_t fftconv_workspace_bytes(fftconv_plan_t p);
 
 /* Layout of one slot inside the workspace: byte offset and number of maps M.
@@ -102,7 +118,8 @@ size_t fftconv_workspace_bytes(fftconv_plan_t p);
  *   (ky = N/2, kx = c - (N/2+1))     for c in [N/2+1, N+1],
  *   (ky, kx), c = N+2 + (ky-1)*N+kx  for ky in [1, N/2-1], kx in [0, N);
  * m is the map index in the tensor's own order (s*f+i for x, j*f+i for w,
- * s*fo+j for g).  FFTCONV_SPEC_OUT holds the spectrum
+ * s*fo+j for g; tiled layers: (s*tiles+t)*f+i and (s*tiles+t)*fo+j for tile
+ * t = ty*tiles_per_row+tx of sample s).  FFTCONV_SPEC_OUT holds the spectrum
  * of the last pass's result, laid out like that result.  Returns (size_t)-1 /
  * -1 for a bad slot (and for FFTCONV_SPEC_OUT under FFTCONV_RECOMPUTE). */
 size_t fftconv_slot_offset(fftconv_plan_t p, int slot);
@@ -133,8 +150,8 @@ int fftconv_accgrad(fftconv_plan_t p, const float *g, const float *x, float *dw,
 
 /* ---- single stages (same kernels; for stage tests and per-stage timing) - */
 
-/* Forward transform of one tensor into its slot (slot = FFTCONV_SPEC_X, _W or _G),
- * unconditionally; marks the slot valid. */
+/* Forward transform of one tensor into its slot (slot = FFTCONV_SPEC_X, _W, _G, or _G2
+ * for a tiled layer), unconditionally; marks the slot valid. */
 int fftconv_forward_transform(fftconv_plan_t p, int slot, const float *src, void *ws, void *stream);
 
 /* Per-bin contraction of a pass on cached spectra into the OUT slot (under
@@ -169,7 +186,8 @@ size_t fftconv_paper_ram_bytes(int S, int n, int f, int fo);
 
 /* Matrix-core floating-point operations the contraction of one pass issues:
  * 6 * S * f * fo * B (three real multiply-adds per complex product, Gauss's
- * form, over the B stored bins), tile padding not counted. */
+ * form, over the B stored bins), padding of matrix tiles not counted.  For a tiled
+ * layer S counts the tiles too, and the value is the mean over the three passes. */
 double fftconv_contraction_flops(fftconv_plan_t p);
 
 #ifdef __cplusplus

@@ -20,7 +20,7 @@ static cf (&regs(LaneRegs<G> &r, int tid))[G::N]
     return reinterpret_cast<cf(&)[G::N]>(*r[tid].data());
 }
 
-template <class G>
+template <class G, bool TILED = false>
 static void replay_forward(const FwdArgs &a)
 {
     std::vector<cf> lds(G::LDS_ELEMS);
@@ -32,7 +32,8 @@ static void replay_forward(const FwdArgs &a)
             // poison: a read of something an earlier step did not write shows up as NaN
             std::memset(z[tid].data(), 0xFF, sizeof(cf) * G::N);
             std::memset(v[tid].data(), 0xFF, sizeof(cf) * G::N);
-            has[tid] = fwd_y_compute<G>(tid, blk, a, regs<G>(z, tid));
+            has[tid] = TILED ? fwd_y_compute_tiled<G>(tid, blk, a, regs<G>(z, tid))
+                             : fwd_y_compute<G>(tid, blk, a, regs<G>(z, tid));
         }
         static_for<0, G::ROUNDS>([&](auto ri) {
             constexpr int r = decltype(ri)::value;
@@ -47,7 +48,7 @@ static void replay_forward(const FwdArgs &a)
     }
 }
 
-template <class G>
+template <class G, bool TILED = false>
 static void replay_inverse(const InvArgs &a, bool acc)
 {
     std::vector<cf> lds(G::LDS_ELEMS);
@@ -67,7 +68,8 @@ static void replay_inverse(const InvArgs &a, bool acc)
             for (int tid = 0; tid < G::THREADS; ++tid) inv_y_gather<G, r>(tid, lds.data(), regs<G>(z, tid));
         });
         for (int tid = 0; tid < G::THREADS; ++tid) {
-            if (acc) inv_y_finish<G, true>(tid, blk, a, regs<G>(z, tid));
+            if constexpr (TILED) inv_y_finish_tiled<G>(tid, blk, a, regs<G>(z, tid));
+            else if (acc) inv_y_finish<G, true>(tid, blk, a, regs<G>(z, tid));
             else inv_y_finish<G, false>(tid, blk, a, regs<G>(z, tid));
         }
     }
@@ -97,6 +99,32 @@ int replay_ifft2d_c2r_crop(int N, const float *spec, float *dst, int M, int crop
     const int T = maps_per_block(N), NX = extent_class(N, crop);
 #define X(n_, t_, nx_) \
     if (N == n_ && T == t_ && NX == nx_) { replay_inverse<TileGeom<n_, t_, nx_, rounds_for(n_)>>(a, accumulate != 0); return 0; }
+    FFTCONV_FOR_EACH_GEOM(X)
+#undef X
+    return 1;
+}
+
+// Tiled variants: src / dst are [S][C][H][W] images, M = S * tiles * C transforms of size N
+// (the full-extent geometry of N), tile t of an image at (ty * step + org, tx * step + org).
+int replay_fft2d_r2c_tiled(int N, const float *src, float *spec, int M, int ext, int H, int W, int C, int tiles_x,
+                           int tiles, int step, int org)
+{
+    FwdArgs a{src, reinterpret_cast<cf *>(spec), M, ext, {H, W, C, tiles_x, tiles, step, org}};
+    const int T = maps_per_block(N);
+#define X(n_, t_, nx_) \
+    if (N == n_ && T == t_ && n_ == nx_) { replay_forward<TileGeom<n_, t_, nx_, rounds_for(n_)>, true>(a); return 0; }
+    FFTCONV_FOR_EACH_GEOM(X)
+#undef X
+    return 1;
+}
+
+int replay_ifft2d_c2r_tiled(int N, const float *spec, float *dst, int M, int crop, int c0, int H, int W, int C,
+                            int tiles_x, int tiles, int step)
+{
+    InvArgs a{reinterpret_cast<const cf *>(spec), dst, M, crop, 1.0f / (float)(N * N), c0, {H, W, C, tiles_x, tiles, step, 0}};
+    const int T = maps_per_block(N);
+#define X(n_, t_, nx_) \
+    if constexpr (n_ == nx_) { if (N == n_ && T == t_) { replay_inverse<TileGeom<n_, t_, nx_, rounds_for(n_)>, true>(a, false); return 0; } }
     FFTCONV_FOR_EACH_GEOM(X)
 #undef X
     return 1;

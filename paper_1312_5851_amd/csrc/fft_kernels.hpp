@@ -45,20 +45,51 @@
 
 namespace fftconv {
 
+// Maps larger than the largest transform are cut into tiles (overlap-save, see the tiled
+// kernels below).  Transform m of a tiled tensor [S][C][H][W] is tile t of image s * C + c with
+//     m = (s * tiles + t) * C + c,   t = ty * tiles_x + tx,
+// i.e. the tiles of a sample are extra samples for the contraction.  A tile's window starts
+// at (ty * step + org, tx * step + org) of its image.
+struct Tiling {
+    int H, W;           // image size
+    int C;              // images per sample (f or f')
+    int tiles_x, tiles; // tiles per image row, tiles per image
+    int step;           // distance between neighbouring tile origins
+    int org;            // offset of the first origin (0, or -(k-1) for the windows of bprop)
+};
+
 struct FwdArgs {
-    const float *src;   // [M][ext][ext] real maps
+    const float *src;   // [M][ext][ext] real maps (tiled kernels: [S][C][H][W] images)
     cf *spec;           // [B][M] bin-major spectrum, B = N*N/2 + 2 stored bins
-    int M;              // number of maps
-    int ext;            // spatial extent of a map (n, k or n'); everything beyond is zero padding
+    int M;              // number of transforms
+    int ext;            // spatial extent of a map or window; everything beyond is zero padding
+    Tiling t;           // read by the tiled kernels only
 };
 
 struct InvArgs {
     const cf *spec;     // [B][M]
-    float *dst;         // [M][crop][crop]
+    float *dst;         // [M][crop][crop] (tiled kernels: [S][C][H][W] images)
     int M;
-    int crop;           // stored window [0,crop)^2
+    int crop;           // stored window [0,crop)^2 (tiled kernels: [c0, c0 + crop)^2, stored at the tile origin)
     float scale;        // 1 / N^2
+    int c0;             // tiled kernels: first stored row / column of the transform's output
+    Tiling t;           // read by the tiled kernels only
 };
+
+struct TileOrigin {
+    int image, oy, ox;
+};
+
+FC_HD TileOrigin tile_origin(int m, const Tiling &t)
+{
+    const int sp = m / t.C, c = m % t.C;
+    const int s = sp / t.tiles, tile = sp % t.tiles;
+    TileOrigin o;
+    o.image = s * t.C + c;
+    o.oy = (tile / t.tiles_x) * t.step + t.org;
+    o.ox = (tile % t.tiles_x) * t.step + t.org;
+    return o;
+}
 
 template <int N_, int T_, int NX_, int ROUNDS_ = 1>
 struct TileGeom {
@@ -120,6 +151,47 @@ FC_HD bool fwd_y_compute(int tid, int blk, const FwdArgs &a, cf (&z)[G::N])
     static_for<0, NX>([&](auto yi) {
         constexpr int y = decltype(yi)::value;
         z[y] = mk(va ? fa[y] : 0.0f, vb ? fb[y] : 0.0f);
+    });
+    fft_dif<N, false, ~low_mask(NX)>(z);
+    return true;
+}
+
+// Tiled variant of step 1: the column comes from a window of a larger image.  Window rows
+// and columns outside the image (the windows of bprop start k-1 before the tile, the last
+// tiles of a row or column stick out) and beyond `ext` read as zero.  Loads are unconditional
+// from clamped addresses, masked afterwards.
+template <class G>
+FC_HD bool fwd_y_compute_tiled(int tid, int blk, const FwdArgs &a, cf (&z)[G::N])
+{
+    constexpr int N = G::N, NX = G::NX;
+    if (tid >= G::YITEMS) return false;
+    const int p = tid / NX, x = tid % NX;
+    float f[2][NX];
+    static_for<0, 2>([&](auto wi) {
+        constexpr int which = decltype(wi)::value;
+        const int m = blk * G::T + 2 * p + which;
+        const TileOrigin o = tile_origin(m < a.M ? m : a.M - 1, a.t);
+        const int xg = o.ox + x;
+        const bool vx = (m < a.M) && (x < a.ext) && xg >= 0 && xg < a.t.W;
+        const int xc = xg < 0 ? 0 : (xg < a.t.W ? xg : a.t.W - 1);
+        // valid window rows [ylo, yhi)
+        const int ylo = o.oy < 0 ? -o.oy : 0;
+        const int yhi = a.ext < a.t.H - o.oy ? a.ext : a.t.H - o.oy;
+        const float *col = a.src + (size_t)o.image * a.t.H * a.t.W + xc;
+        static_for<0, NX>([&](auto yi) {
+            constexpr int y = decltype(yi)::value;
+            int r = o.oy + (y < ylo ? ylo : (y < yhi ? y : yhi - 1));
+            r = r < 0 ? 0 : (r < a.t.H ? r : a.t.H - 1);
+            f[which][y] = col[(size_t)r * a.t.W];
+        });
+        static_for<0, NX>([&](auto yi) {
+            constexpr int y = decltype(yi)::value;
+            if (!(vx && y >= ylo && y < yhi)) f[which][y] = 0.0f;
+        });
+    });
+    static_for<0, NX>([&](auto yi) {
+        constexpr int y = decltype(yi)::value;
+        z[y] = mk(f[0][y], f[1][y]);
     });
     fft_dif<N, false, ~low_mask(NX)>(z);
     return true;
@@ -307,6 +379,37 @@ FC_HD void inv_y_finish(int tid, int blk, const InvArgs &a, cf (&z)[G::N])
     });
 }
 
+// Tiled variant of step 2: rows and columns [c0, c0 + crop) of the transform's output go to
+// the tile's place in a larger image, clipped at the image border.
+template <class G>
+FC_HD void inv_y_finish_tiled(int tid, int blk, const InvArgs &a, cf (&z)[G::N])
+{
+    constexpr int N = G::N, NX = G::NX;
+    static_assert(NX == N, "tiled transforms keep every output column");
+    if (tid >= G::YITEMS) return;
+    const int p = tid / NX, x = tid % NX;
+    fft_dif<N, true>(z);
+    const int xs = x - a.c0;
+    if (xs < 0 || xs >= a.crop) return;
+    static_for<0, 2>([&](auto wi) {
+        constexpr int which = decltype(wi)::value;
+        const int m = blk * G::T + 2 * p + which;
+        if (m >= a.M) return;
+        const TileOrigin o = tile_origin(m, a.t);
+        if (o.ox + xs >= a.t.W) return;
+        const int rows = a.crop < a.t.H - o.oy ? a.crop : a.t.H - o.oy;
+        float *col = a.dst + ((size_t)o.image * a.t.H + o.oy) * a.t.W + o.ox + xs;
+        static_for<0, N>([&](auto yi) {
+            constexpr int y = decltype(yi)::value;
+            const int ys = y - a.c0;
+            if (ys >= 0 && ys < rows) {
+                const cf v = z[brev<N>(y)];
+                col[(size_t)ys * a.t.W] = (which == 0 ? v.x : v.y) * a.scale;
+            }
+        });
+    });
+}
+
 // The order of steps and barriers of one workgroup, shared by the device kernels and the
 // host replay.  `sync` is __syncthreads() on the device; the host replay runs every step for
 // all lanes before the next one, which is what a barrier after each step guarantees.
@@ -318,7 +421,7 @@ FC_HD void inv_y_finish(int tid, int blk, const InvArgs &a, cf (&z)[G::N])
 // Device kernels.  Launch with G::THREADS threads, ceil(M / G::T) blocks and G::LDS_BYTES
 // of dynamic LDS.
 // (the second launch bound is the number of waves per SIMD the register budget must allow)
-template <class G>
+template <class G, bool TILED = false>
 __global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void fft2d_r2c_kernel(FwdArgs a)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -326,7 +429,7 @@ __global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void fft2d_r2c_kerne
     const int tid = (int)threadIdx.x, blk = (int)blockIdx.x;
     const int team = tid / G::XTHREADS, xt = tid % G::XTHREADS;
     cf z[G::N], v[G::N];
-    const bool has = fwd_y_compute<G>(tid, blk, a, z);
+    const bool has = TILED ? fwd_y_compute_tiled<G>(tid, blk, a, z) : fwd_y_compute<G>(tid, blk, a, z);
     static_for<0, G::ROUNDS>([&](auto ri) {
         constexpr int r = decltype(ri)::value;
         if constexpr (r > 0) __syncthreads();   // the previous team has its rows in registers
@@ -354,6 +457,26 @@ __global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void ifft2d_c2r_crop
         inv_y_gather<G, r>(tid, lds, z);
     });
     inv_y_finish<G, ACC>(tid, blk, a, z);
+}
+
+// Same schedule, output scattered to tiles of a larger image (never accumulating).
+template <class G>
+__global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void ifft2d_c2r_tiled_kernel(InvArgs a)
+{
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    cf *lds = reinterpret_cast<cf *>(lds_raw);
+    const int tid = (int)threadIdx.x, blk = (int)blockIdx.x;
+    const int team = tid / G::XTHREADS, xt = tid % G::XTHREADS;
+    cf z[G::N], v[G::N];
+    inv_x_compute<G>(xt, blk, team, a, v);
+    static_for<0, G::ROUNDS>([&](auto ri) {
+        constexpr int r = decltype(ri)::value;
+        if constexpr (r > 0) __syncthreads();
+        if (team == r) inv_x_write<G>(xt, lds, v);
+        __syncthreads();
+        inv_y_gather<G, r>(tid, lds, z);
+    });
+    inv_y_finish_tiled<G>(tid, blk, a, z);
 }
 #endif
 

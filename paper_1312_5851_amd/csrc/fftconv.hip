@@ -39,13 +39,30 @@ struct FftEntry {
     int N, T, NX, threads, lds_bytes;
     FwdKernel fwd;
     InvKernel inv, inv_acc;
+    FwdKernel fwd_tiled;   // full-extent geometries (NX == N) of the sizes used for tiles only
+    InvKernel inv_tiled;
 };
+
+// Tiles use the full-extent geometry of N >= 16 (smaller transforms would be mostly overlap).
+template <int N, int T, int NX>
+constexpr FwdKernel tiled_fwd_kernel()
+{
+    if constexpr (NX == N && N >= 16) return fft2d_r2c_kernel<TileGeom<N, T, NX, rounds_for(N)>, true>;
+    else return nullptr;
+}
+template <int N, int T, int NX>
+constexpr InvKernel tiled_inv_kernel()
+{
+    if constexpr (NX == N && N >= 16) return ifft2d_c2r_tiled_kernel<TileGeom<N, T, NX, rounds_for(N)>>;
+    else return nullptr;
+}
 
 #define X(n_, t_, nx_)                                                                          \
     {n_, t_, nx_, TileGeom<n_, t_, nx_, rounds_for(n_)>::THREADS, TileGeom<n_, t_, nx_, rounds_for(n_)>::LDS_BYTES, \
      fft2d_r2c_kernel<TileGeom<n_, t_, nx_, rounds_for(n_)>>,                                    \
      ifft2d_c2r_crop_kernel<TileGeom<n_, t_, nx_, rounds_for(n_)>, false>,                       \
-     ifft2d_c2r_crop_kernel<TileGeom<n_, t_, nx_, rounds_for(n_)>, true>},
+     ifft2d_c2r_crop_kernel<TileGeom<n_, t_, nx_, rounds_for(n_)>, true>,                        \
+     tiled_fwd_kernel<n_, t_, nx_>(), tiled_inv_kernel<n_, t_, nx_>()},
 const FftEntry kFftTable[] = {FFTCONV_FOR_EACH_GEOM(X)};
 #undef X
 
@@ -120,8 +137,12 @@ int choose_gemm_tile(int Md, int Nd, int /*Kd*/, int /*bins*/)
 struct fftconv_plan_s {
     fftconv_desc d;
     int no, N, B;
-    long maps_x, maps_w, maps_g, maps_out;
-    size_t off_x, off_w, off_g, off_out, ws_bytes;
+    // Tiling (n > 64 only; otherwise L = 0 and one "tile" per image): tiles are L x L output
+    // blocks, nt per dimension for y (and for the blocks of dL/dy and windows of x), nt2 per
+    // dimension for dx (and for the windows of dL/dy that bprop reads).
+    int L, nt, nt2;
+    long maps_x, maps_w, maps_g, maps_g2, maps_out;   // transforms per slot
+    size_t off_x, off_w, off_g, off_g2, off_out, ws_bytes;
     unsigned valid;
     void *last_ws;
     int gemm_tile[3];
@@ -207,40 +228,64 @@ cf *slot_ptr(fftconv_plan_t p, void *ws, int slot)
         case FFTCONV_SPEC_X: off = p->off_x; break;
         case FFTCONV_SPEC_W: off = p->off_w; break;
         case FFTCONV_SPEC_G: off = p->off_g; break;
+        case FFTCONV_SPEC_G2: off = p->off_g2; break;
         default: off = p->off_out; break;
     }
     return reinterpret_cast<cf *>(static_cast<unsigned char *>(ws) + off);
 }
 
+bool tiled(fftconv_plan_t p) { return p->L > 0; }
+
 int launch_forward(fftconv_plan_t p, int slot, const float *src, void *ws, hipStream_t stream)
 {
     long M;
     int ext, stage;
+    Tiling t{};
     switch (slot) {
-        case FFTCONV_SPEC_X: M = p->maps_x; ext = p->d.n; stage = FFTCONV_STAGE_FFT_X; break;
-        case FFTCONV_SPEC_W: M = p->maps_w; ext = p->d.k; stage = FFTCONV_STAGE_FFT_W; break;
-        case FFTCONV_SPEC_G: M = p->maps_g; ext = p->no; stage = FFTCONV_STAGE_FFT_G; break;
+        case FFTCONV_SPEC_X:   // dense N x N windows of x, one per output tile
+            M = p->maps_x; ext = tiled(p) ? p->N : p->d.n; stage = FFTCONV_STAGE_FFT_X;
+            t = Tiling{p->d.n, p->d.n, p->d.f, p->nt, p->nt * p->nt, p->L, 0};
+            break;
+        case FFTCONV_SPEC_W:   // kernels are never tiled
+            M = p->maps_w; ext = p->d.k; stage = FFTCONV_STAGE_FFT_W;
+            break;
+        case FFTCONV_SPEC_G:   // L x L blocks of dL/dy
+            M = p->maps_g; ext = tiled(p) ? p->L : p->no; stage = FFTCONV_STAGE_FFT_G;
+            t = Tiling{p->no, p->no, p->d.fo, p->nt, p->nt * p->nt, p->L, 0};
+            break;
+        case FFTCONV_SPEC_G2:  // N x N windows of dL/dy starting k-1 before each tile of dx
+            if (!tiled(p)) return FFTCONV_EINVAL;
+            M = p->maps_g2; ext = p->N; stage = FFTCONV_STAGE_FFT_G;
+            t = Tiling{p->no, p->no, p->d.fo, p->nt2, p->nt2 * p->nt2, p->L, -(p->d.k - 1)};
+            break;
         default: return FFTCONV_EINVAL;
     }
-    const FftEntry *e = find_fft(p->N, ext);
-    if (!e) return FFTCONV_EUNSUPPORTED;
-    if (int rc = allow_lds(e->fwd, e->lds_bytes)) return rc;
-    FwdArgs a{src, slot_ptr(p, ws, slot), (int)M, ext};
+    const bool use_tiles = tiled(p) && slot != FFTCONV_SPEC_W;
+    const FftEntry *e = find_fft(p->N, use_tiles ? p->N : ext);
+    if (!e || (use_tiles && !e->fwd_tiled)) return FFTCONV_EUNSUPPORTED;
+    FwdKernel kernel = use_tiles ? e->fwd_tiled : e->fwd;
+    if (int rc = allow_lds(kernel, e->lds_bytes)) return rc;
+    FwdArgs a{src, slot_ptr(p, ws, slot), (int)M, ext, t};
     const unsigned blocks = (unsigned)((M + e->T - 1) / e->T);
     StageTimer timer(p, stage, stream);
-    hipLaunchKernelGGL(e->fwd, dim3(blocks), dim3(e->threads), e->lds_bytes, stream, a);
+    hipLaunchKernelGGL(kernel, dim3(blocks), dim3(e->threads), e->lds_bytes, stream, a);
     if (int rc = check_launch()) return rc;
     if (int rc = timer.finish()) return rc;
     p->valid |= (unsigned)slot;
+    // in the three-slot workspace the blocks and the windows of dL/dy share one slot
+    if (recompute_mode(p) && slot == FFTCONV_SPEC_G) p->valid &= ~(unsigned)FFTCONV_SPEC_G2;
+    if (recompute_mode(p) && slot == FFTCONV_SPEC_G2) p->valid &= ~(unsigned)FFTCONV_SPEC_G;
     return FFTCONV_OK;
 }
 
 void pass_dims(fftconv_plan_t p, int pass, int &Md, int &Nd, int &Kd, int &slot_a, int &slot_b)
 {
+    // the tiles of a sample act as extra samples: S * nt^2 (fprop, accGrad) or S * nt2^2 (bprop)
+    const int St = p->d.S * p->nt * p->nt, St2 = p->d.S * p->nt2 * p->nt2;
     switch (pass) {
-        case FFTCONV_FPROP: Md = p->d.S; Nd = p->d.fo; Kd = p->d.f; slot_a = FFTCONV_SPEC_X; slot_b = FFTCONV_SPEC_W; break;
-        case FFTCONV_BPROP: Md = p->d.S; Nd = p->d.f; Kd = p->d.fo; slot_a = FFTCONV_SPEC_G; slot_b = FFTCONV_SPEC_W; break;
-        default:            Md = p->d.fo; Nd = p->d.f; Kd = p->d.S; slot_a = FFTCONV_SPEC_G; slot_b = FFTCONV_SPEC_X; break;
+        case FFTCONV_FPROP: Md = St; Nd = p->d.fo; Kd = p->d.f; slot_a = FFTCONV_SPEC_X; slot_b = FFTCONV_SPEC_W; break;
+        case FFTCONV_BPROP: Md = St2; Nd = p->d.f; Kd = p->d.fo; slot_a = tiled(p) ? FFTCONV_SPEC_G2 : FFTCONV_SPEC_G; slot_b = FFTCONV_SPEC_W; break;
+        default:            Md = p->d.fo; Nd = p->d.f; Kd = St; slot_a = FFTCONV_SPEC_G; slot_b = FFTCONV_SPEC_X; break;
     }
 }
 
@@ -266,7 +311,10 @@ int launch_contract(fftconv_plan_t p, int pass, void *ws, hipStream_t stream)
     StageTimer timer(p, FFTCONV_STAGE_CGEMM_FPROP + pass, stream);
     hipLaunchKernelGGL(e.pass[pass], dim3((unsigned)blocks), dim3(e.threads), e.lds_bytes, stream, g);
     if (int rc = check_launch()) return rc;
-    if (sc != FFTCONV_SPEC_OUT) p->valid &= ~(unsigned)sc;   // an operand slot now holds a result spectrum
+    if (sc != FFTCONV_SPEC_OUT) {   // an operand slot now holds a result spectrum
+        p->valid &= ~(unsigned)sc;
+        if (sc == FFTCONV_SPEC_G) p->valid &= ~(unsigned)FFTCONV_SPEC_G2;   // same place in the three-slot workspace
+    }
     return timer.finish();
 }
 
@@ -274,16 +322,32 @@ int launch_inverse(fftconv_plan_t p, int pass, float *dst, void *ws, hipStream_t
 {
     long M;
     int crop;
+    InvArgs a{};
     switch (pass) {
-        case FFTCONV_FPROP: M = p->maps_g; crop = p->no; break;
-        case FFTCONV_BPROP: M = p->maps_x; crop = p->d.n; break;
-        default:            M = p->maps_w; crop = p->d.k; break;
+        case FFTCONV_FPROP:   // tiles of y: output rows / columns [0, L) of each transform
+            M = p->maps_g; crop = tiled(p) ? p->L : p->no;
+            a.t = Tiling{p->no, p->no, p->d.fo, p->nt, p->nt * p->nt, p->L, 0};
+            a.c0 = 0;
+            break;
+        case FFTCONV_BPROP:   // tiles of dx: rows / columns [k-1, N), the part of the circular result free of wrap-around
+            M = tiled(p) ? (long)p->d.S * p->nt2 * p->nt2 * p->d.f : p->maps_x; crop = tiled(p) ? p->L : p->d.n;
+            a.t = Tiling{p->d.n, p->d.n, p->d.f, p->nt2, p->nt2 * p->nt2, p->L, 0};
+            a.c0 = p->d.k - 1;
+            break;
+        default:              // dw is never tiled
+            M = p->maps_w; crop = p->d.k;
+            break;
     }
-    const FftEntry *e = find_fft(p->N, crop);
-    if (!e) return FFTCONV_EUNSUPPORTED;
-    InvKernel kernel = accumulate ? e->inv_acc : e->inv;
+    const bool use_tiles = tiled(p) && pass != FFTCONV_ACCGRAD;
+    const FftEntry *e = find_fft(p->N, use_tiles ? p->N : crop);
+    if (!e || (use_tiles && !e->inv_tiled)) return FFTCONV_EUNSUPPORTED;
+    InvKernel kernel = use_tiles ? e->inv_tiled : (accumulate ? e->inv_acc : e->inv);
     if (int rc = allow_lds(kernel, e->lds_bytes)) return rc;
-    InvArgs a{slot_ptr(p, ws, result_slot(p, pass)), dst, (int)M, crop, 1.0f / ((float)p->N * (float)p->N)};
+    a.spec = slot_ptr(p, ws, result_slot(p, pass));
+    a.dst = dst;
+    a.M = (int)M;
+    a.crop = crop;
+    a.scale = 1.0f / ((float)p->N * (float)p->N);
     const unsigned blocks = (unsigned)((M + e->T - 1) / e->T);
     StageTimer timer(p, FFTCONV_STAGE_IFFT_Y + pass, stream);
     hipLaunchKernelGGL(kernel, dim3(blocks), dim3(e->threads), e->lds_bytes, stream, a);
@@ -318,27 +382,59 @@ int fftconv_plan(fftconv_plan_t *out, const fftconv_desc *d)
 {
     if (!out || !d) return FFTCONV_EINVAL;
     if (d->S < 1 || d->f < 1 || d->fo < 1 || d->n < 1 || d->k < 1 || d->k > d->n) return FFTCONV_EINVAL;
-    if ((d->flags & ~(unsigned)FFTCONV_RECOMPUTE) != 0 || d->n > 64) return FFTCONV_EUNSUPPORTED;
-    const long maps_x = (long)d->S * d->f, maps_w = (long)d->fo * d->f, maps_g = (long)d->S * d->fo;
-    if (maps_x > 0x7fffffffL || maps_w > 0x7fffffffL || maps_g > 0x7fffffffL) return FFTCONV_EUNSUPPORTED;
+    if ((d->flags & ~(unsigned)FFTCONV_RECOMPUTE) != 0) return FFTCONV_EUNSUPPORTED;
+    const int no = d->n - d->k + 1;
+    int N = fft_size_for(d->n), L = 0, nt = 1, nt2 = 1;
+    if (N < 0) {
+        // Larger than the largest transform: cut into tiles of L = N - k + 1 outputs per side
+        // (overlap-save).  Pick the tile transform that needs the fewest transformed points over
+        // the tiles of y and of dx together.
+        static const int sizes[] = {16, 24, 32, 48, 64};
+        double best = -1.0;
+        for (int cand : sizes) {
+            const int l = cand - d->k + 1;
+            if (l < 1) continue;
+            const long a = (no + l - 1) / l, b = (d->n + l - 1) / l;
+            const double cost = (double)(a * a + b * b) * cand * cand;
+            if (best < 0.0 || cost < best) { best = cost; N = cand; L = l; nt = (int)a; nt2 = (int)b; }
+        }
+        if (N < 0) return FFTCONV_EUNSUPPORTED;   // k > 64
+    }
+    const long T = (long)nt * nt, T2 = (long)nt2 * nt2;
+    const bool lean = (d->flags & FFTCONV_RECOMPUTE) != 0;
+    // transforms per slot; in the three-slot workspace the x and g slots also take the results
+    // dX and Y and the windows of bprop, whose tile counts can differ
+    const long Tmax = T > T2 ? T : T2;
+    const long maps_x = (long)d->S * d->f * (lean ? Tmax : T), maps_w = (long)d->fo * d->f;
+    const long maps_g = (long)d->S * d->fo * (lean ? Tmax : T), maps_g2 = L > 0 && !lean ? (long)d->S * d->fo * T2 : 0;
+    const long out_y = (long)d->S * d->fo * T, out_dx = (long)d->S * d->f * T2;
+    const long lim = 0x7fffffffL;
+    if (maps_x > lim || maps_w > lim || maps_g > lim || maps_g2 > lim || out_y > lim || out_dx > lim)
+        return FFTCONV_EUNSUPPORTED;
     fftconv_plan_s *p = new (std::nothrow) fftconv_plan_s();
     if (!p) return FFTCONV_EINVAL;
     p->d = *d;
-    p->no = d->n - d->k + 1;
-    p->N = fft_size_for(d->n);
-    p->B = p->N * p->N / 2 + 2;
-    p->maps_x = maps_x;
+    p->no = no;
+    p->N = N;
+    p->B = N * N / 2 + 2;
+    p->L = L;
+    p->nt = nt;
+    p->nt2 = nt2;
+    p->maps_x = (long)d->S * d->f * T;
     p->maps_w = maps_w;
-    p->maps_g = maps_g;
-    p->maps_out = maps_x > maps_w ? (maps_x > maps_g ? maps_x : maps_g) : (maps_w > maps_g ? maps_w : maps_g);
+    p->maps_g = (long)d->S * d->fo * T;
+    p->maps_g2 = (long)d->S * d->fo * T2;
+    p->maps_out = out_y > out_dx ? (out_y > maps_w ? out_y : maps_w) : (out_dx > maps_w ? out_dx : maps_w);
     const size_t per_map = (size_t)8 * p->B;
     p->off_x = 0;
     p->off_w = p->off_x + align_up(per_map * maps_x);
     p->off_g = p->off_w + align_up(per_map * maps_w);
-    p->off_out = p->off_g + align_up(per_map * maps_g);
+    p->off_g2 = p->off_g + align_up(per_map * maps_g);
+    p->off_out = p->off_g2 + align_up(per_map * maps_g2);
     p->ws_bytes = p->off_out + align_up(per_map * p->maps_out);
-    if (recompute_mode(p)) {   // three slots only: a pass writes its result into the one it does not read
-        p->ws_bytes = p->off_out;
+    if (lean) {   // three slots only: a pass writes its result into the one it does not read
+        p->ws_bytes = p->off_g2;
+        p->off_g2 = p->off_g;   // the windows of bprop take the place of the blocks of dL/dy
         p->off_out = (size_t)-1;
         p->maps_out = -1;
     }
@@ -377,6 +473,7 @@ size_t fftconv_slot_offset(fftconv_plan_t p, int slot)
         case FFTCONV_SPEC_X: return p->off_x;
         case FFTCONV_SPEC_W: return p->off_w;
         case FFTCONV_SPEC_G: return p->off_g;
+        case FFTCONV_SPEC_G2: return tiled(p) ? p->off_g2 : (size_t)-1;
         case FFTCONV_SPEC_OUT: return p->off_out;
         default: return (size_t)-1;
     }
@@ -389,6 +486,7 @@ long fftconv_slot_maps(fftconv_plan_t p, int slot)
         case FFTCONV_SPEC_X: return p->maps_x;
         case FFTCONV_SPEC_W: return p->maps_w;
         case FFTCONV_SPEC_G: return p->maps_g;
+        case FFTCONV_SPEC_G2: return tiled(p) ? p->maps_g2 : -1;
         case FFTCONV_SPEC_OUT: return p->maps_out;
         default: return -1;
     }
@@ -397,6 +495,7 @@ long fftconv_slot_maps(fftconv_plan_t p, int slot)
 int fftconv_invalidate(fftconv_plan_t p, unsigned slots)
 {
     if (!p || (slots & ~(unsigned)(FFTCONV_SPEC_X | FFTCONV_SPEC_W | FFTCONV_SPEC_G)) != 0) return FFTCONV_EINVAL;
+    if (slots & FFTCONV_SPEC_G) slots |= FFTCONV_SPEC_G2;   // both are transforms of dL/dy
     p->valid &= ~slots;
     return FFTCONV_OK;
 }
@@ -421,7 +520,8 @@ int fftconv_accgrad(fftconv_plan_t p, const float *g, const float *x, float *dw,
 int fftconv_forward_transform(fftconv_plan_t p, int slot, const float *src, void *ws, void *stream)
 {
     if (!p || !src) return FFTCONV_EINVAL;
-    if (slot != FFTCONV_SPEC_X && slot != FFTCONV_SPEC_W && slot != FFTCONV_SPEC_G) return FFTCONV_EINVAL;
+    if (slot != FFTCONV_SPEC_X && slot != FFTCONV_SPEC_W && slot != FFTCONV_SPEC_G && slot != FFTCONV_SPEC_G2)
+        return FFTCONV_EINVAL;
     if (int rc = bind_workspace(p, ws)) return rc;
     return launch_forward(p, slot, src, ws, static_cast<hipStream_t>(stream));
 }
@@ -471,7 +571,7 @@ const char *fftconv_strerror(int status)
     switch (status) {
         case FFTCONV_OK: return "ok";
         case FFTCONV_EINVAL: return "invalid argument";
-        case FFTCONV_EUNSUPPORTED: return "unsupported layer (n > 64 or unknown flags)";
+        case FFTCONV_EUNSUPPORTED: return "unsupported layer (k > 64 with n > 64, too many maps, or unknown flags)";
         case FFTCONV_EWORKSPACE: return "workspace pointer null or not 256-byte aligned";
         case FFTCONV_ELAUNCH: return "HIP launch or event call failed";
         case FFTCONV_ENOTREADY: return "operand spectrum not cached for this workspace";
@@ -488,7 +588,17 @@ size_t fftconv_paper_ram_bytes(int S, int n, int f, int fo)
 double fftconv_contraction_flops(fftconv_plan_t p)
 {
     if (!p) return 0.0;
-    return 6.0 * p->d.S * p->d.f * p->d.fo * p->B;
+    const double tiles = (2.0 * p->nt * p->nt + (double)p->nt2 * p->nt2) / 3.0;   // mean over the three passes
+    return 6.0 * p->d.S * p->d.f * p->d.fo * p->B * tiles;
+}
+
+int fftconv_tiling(fftconv_plan_t p, int *tile, int *tiles_y, int *tiles_dx)
+{
+    if (!p || !tile || !tiles_y || !tiles_dx) return FFTCONV_EINVAL;
+    *tile = p->L;
+    *tiles_y = p->nt;
+    *tiles_dx = p->nt2;
+    return FFTCONV_OK;
 }
 
 }  // extern "C"

@@ -16,7 +16,7 @@ import torch  # noqa: F401  (loads the HIP runtime the library binds to)
 from . import build as _build
 
 FFTCONV_OK = 0
-SPEC_X, SPEC_W, SPEC_G, SPEC_OUT = 1, 2, 4, 8
+SPEC_X, SPEC_W, SPEC_G, SPEC_OUT, SPEC_G2 = 1, 2, 4, 8, 16
 FPROP, BPROP, ACCGRAD = 0, 1, 2
 RECOMPUTE = 1   # plan flag: memory-efficient mode (no spectral cache, three-slot workspace)
 NUM_STAGES = 9
@@ -30,7 +30,7 @@ EXPORTS = (
     "fftconv_valid_slots", "fftconv_fprop", "fftconv_bprop", "fftconv_accgrad",
     "fftconv_forward_transform", "fftconv_contract", "fftconv_inverse_transform",
     "fftconv_profile_enable", "fftconv_profile_read", "fftconv_strerror",
-    "fftconv_paper_ram_bytes", "fftconv_contraction_flops",
+    "fftconv_paper_ram_bytes", "fftconv_contraction_flops", "fftconv_tiling",
 )
 
 
@@ -72,6 +72,7 @@ def _load() -> ctypes.CDLL:
         "fftconv_strerror": (ctypes.c_char_p, [ip]),
         "fftconv_paper_ram_bytes": (sz, [ip, ip, ip, ip]),
         "fftconv_contraction_flops": (ctypes.c_double, [vp]),
+        "fftconv_tiling": (ip, [vp, ctypes.POINTER(ip), ctypes.POINTER(ip), ctypes.POINTER(ip)]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -144,6 +145,13 @@ class Plan:
     @property
     def contraction_flops(self) -> float:
         return float(_lib.fftconv_contraction_flops(self._h))
+
+    @property
+    def tiling(self):
+        """(L, tiles per dimension of y, tiles per dimension of dx); L = 0 if the layer is not tiled."""
+        a, b, c = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+        _check(_lib.fftconv_tiling(self._h, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)), "fftconv_tiling")
+        return a.value, b.value, c.value
 
     def slot_offset(self, slot: int) -> int:
         return int(_lib.fftconv_slot_offset(self._h, slot))

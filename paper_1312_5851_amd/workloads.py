@@ -87,10 +87,21 @@ def fig3_layers():
     return out
 
 
+def large_layers():
+    """Layers with maps larger than the largest transform (n > 64), which are computed in tiles:
+    the far end of the figure's image-size axis and two image-sized first layers."""
+    return [
+        Layer("large_n96", 128, 96, 256, 96, 5, 0.02, BASE_SEED + 400),
+        Layer("large_n128", 128, 96, 256, 128, 5, 0.02, BASE_SEED + 401),
+        Layer("large_n224_k11_f3", 128, 3, 96, 224, 11, 0.05, BASE_SEED + 402),
+        Layer("large_n112_k3_f64", 32, 64, 64, 112, 3, 0.05, BASE_SEED + 403),
+    ]
+
+
 def by_name(name: str) -> Layer:
     if name in CONFIGS:
         return CONFIGS[name]
-    for lay in sweep_layers() + paper_table_layers() + fig3_layers():
+    for lay in sweep_layers() + paper_table_layers() + fig3_layers() + large_layers():
         if lay.name == name:
             return lay
     raise KeyError(name)

@@ -65,7 +65,8 @@ def test_workspace_layout(fc):
 
 @pytest.mark.parametrize("args,status", [
     ((0, 1, 1, 8, 3), 1), ((1, 0, 1, 8, 3), 1), ((1, 1, 0, 8, 3), 1), ((1, 1, 1, 0, 1), 1),
-    ((1, 1, 1, 8, 0), 1), ((1, 1, 1, 8, 9), 1), ((1, 1, 1, 65, 3), 2), ((1, 1, 1, 128, 3), 2),
+    ((1, 1, 1, 8, 0), 1), ((1, 1, 1, 8, 9), 1), ((1, 1, 1, 200, 65), 2), ((1, 1, 1, 65, 65), 2),
+    ((65536, 65536, 1, 8, 3), 2),            # 2^32 transforms in a slot
 ])
 def test_plan_rejects_bad_layers(fc, args, status):
     with pytest.raises(fc.FftconvError) as ei:
@@ -100,6 +101,47 @@ def test_memory_efficient_plan_has_three_slots(fc):
     assert fc._lib.fftconv_contract(lean._h, 0, ctypes.c_void_p(256), None) == 5
 
 
+def ceil_div(a, b):
+    return -(-a // b)
+
+
+@pytest.mark.parametrize("n,k", [(65, 3), (100, 5), (128, 3), (128, 11), (224, 11), (70, 64), (96, 7)])
+def test_large_maps_are_tiled(fc, n, k):
+    """n > 64: L x L output tiles with L = N - k + 1, the N among 16..64 that needs the fewest
+    transformed points; slots hold one transform per tile; an extra slot for bprop's windows."""
+    S, f, fo = 2, 3, 4
+    p = fc.Plan(S, f, fo, n, k)
+    N, (L, nt, nt2) = p.fft_size, p.tiling
+    no = n - k + 1
+    assert N in (16, 24, 32, 48, 64) and L == N - k + 1 >= 1
+    assert nt == ceil_div(no, L) and nt2 == ceil_div(n, L)
+    cost = lambda c: (ceil_div(no, c - k + 1) ** 2 + ceil_div(n, c - k + 1) ** 2) * c * c
+    assert all(cost(N) <= cost(c) for c in (16, 24, 32, 48, 64) if c - k + 1 >= 1)
+    B = p.num_bins
+    assert B == N * N // 2 + 2
+    assert p.slot_maps(fc.SPEC_X) == S * nt * nt * f and p.slot_maps(fc.SPEC_W) == fo * f
+    assert p.slot_maps(fc.SPEC_G) == S * nt * nt * fo and p.slot_maps(fc.SPEC_G2) == S * nt2 * nt2 * fo
+    assert p.slot_maps(fc.SPEC_OUT) == max(S * nt * nt * fo, S * nt2 * nt2 * f, fo * f)
+    off = 0
+    for slot in (fc.SPEC_X, fc.SPEC_W, fc.SPEC_G, fc.SPEC_G2, fc.SPEC_OUT):
+        assert p.slot_offset(slot) == off
+        off += (8 * B * p.slot_maps(slot) + 255) // 256 * 256
+    assert p.workspace_bytes == off
+    assert p.contraction_flops == 6.0 * S * f * fo * B * (2 * nt * nt + nt2 * nt2) / 3
+    lean = fc.Plan(S, f, fo, n, k, flags=fc.RECOMPUTE)
+    tmax = max(nt, nt2) ** 2
+    sizes = [(8 * B * m + 255) // 256 * 256 for m in (S * f * tmax, fo * f, S * fo * tmax)]
+    assert lean.workspace_bytes == sum(sizes)
+    assert lean.slot_offset(fc.SPEC_G2) == lean.slot_offset(fc.SPEC_G) == sizes[0] + sizes[1]
+
+
+def test_small_maps_are_not_tiled(fc):
+    p = fc.Plan(2, 3, 4, 64, 3)
+    assert p.tiling == (0, 1, 1) and p.slot_maps(fc.SPEC_G2) == -1 and p.slot_offset(fc.SPEC_G2) == 2 ** 64 - 1
+    assert fc._lib.fftconv_forward_transform(p._h, fc.SPEC_G2, ctypes.c_void_p(256), ctypes.c_void_p(256), None) == 1
+    assert fc._lib.fftconv_tiling(p._h, None, None, None) == 1
+
+
 def test_invalidate_bookkeeping_and_null_pointer_errors(fc):
     p = fc.Plan(2, 2, 2, 16, 3)
     assert p.valid_slots() == 0
@@ -113,6 +155,7 @@ def test_invalidate_bookkeeping_and_null_pointer_errors(fc):
     assert lib.fftconv_accgrad(p._h, one, one, one, None, None, 0) == 3       # null workspace
     assert lib.fftconv_accgrad(p._h, one, one, one, ctypes.c_void_p(260), None, 0) == 3  # misaligned
     assert lib.fftconv_forward_transform(p._h, 3, one, one, None) == 1
+    assert lib.fftconv_forward_transform(p._h, fc.SPEC_G2, one, one, None) == 1   # not a tiled layer
     assert lib.fftconv_contract(p._h, 7, one, None) == 1
     assert lib.fftconv_contract(p._h, 0, one, None) == 5                      # nothing cached: launches nothing
     assert lib.fftconv_inverse_transform(p._h, 0, None, one, None, 0) == 1
@@ -154,6 +197,7 @@ def test_workloads_are_seeded_and_shaped():
     assert len(wl.sweep_layers()) == 18 and len(wl.paper_table_layers()) == 5 and len(wl.fig3_layers()) == 16
     assert wl.by_name("sweep_n32_k7").k == 7 and wl.by_name("fig3_S256").S == 256
     every = list(wl.CONFIGS.values()) + wl.sweep_layers() + wl.paper_table_layers() + wl.fig3_layers()
+    assert all(l.n > 64 for l in wl.large_layers())
     assert len({l.name for l in every}) == len(every) == len({l.seed for l in every})
     assert all(1 <= l.k <= l.n <= 64 for l in every)
     u = wl.sample_units(100, 10, 3)

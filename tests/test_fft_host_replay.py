@@ -102,3 +102,74 @@ def test_impulse_constant_and_round_trip(replay, N):
     x = np.random.default_rng(5).uniform(-1, 1, (5, 11, 11)).astype(np.float32)
     back = inverse(replay, forward(replay, x, N), N, 11)
     assert np.abs(back - x).max() < 1e-6
+
+
+# ---------------------------------------------------------------- tiled (overlap-save) variants
+
+def tile_windows(img, N, tiles_x, tiles, step, org, ext):
+    """[S, C, H, W] images -> zero-filled windows [S * tiles * C, N, N] in transform order
+    m = (s * tiles + t) * C + c, window origin (ty * step + org, tx * step + org), extent ext."""
+    S, C, H, W = img.shape
+    out = np.zeros((S * tiles * C, N, N))
+    for s in range(S):
+        for t in range(tiles):
+            oy, ox = (t // tiles_x) * step + org, (t % tiles_x) * step + org
+            for c in range(C):
+                for y in range(ext):
+                    for x in range(ext):
+                        if 0 <= oy + y < H and 0 <= ox + x < W:
+                            out[(s * tiles + t) * C + c, y, x] = img[s, c, oy + y, ox + x]
+    return out
+
+
+@pytest.mark.parametrize("N,H,k", [(16, 37, 5), (24, 50, 3), (32, 70, 11), (48, 65, 4), (64, 100, 9)])
+def test_tiled_forward_windows(replay, N, H, k):
+    """The three kinds of windows a tiled layer transforms: dense N x N windows of x (stride L),
+    L x L blocks of dL/dy, and the windows of dL/dy that start k-1 before a tile of dx."""
+    rng = np.random.default_rng(N + H)
+    L = N - k + 1
+    S, C = 2, 3
+    no = H - k + 1
+    nt, nt2 = -(-no // L), -(-H // L)
+    B = N * N // 2 + 2
+    cases = [("x windows", H, nt, 0, N), ("g blocks", no, nt, 0, L), ("g windows", no, nt2, -(k - 1), N)]
+    for what, size, tx, org, ext in cases:
+        img = rng.uniform(-1, 1, (S, C, size, size)).astype(np.float32)
+        M = S * tx * tx * C
+        spec = np.full((B, M, 2), np.nan, np.float32)
+        rc = replay.replay_fft2d_r2c_tiled(N, img.ctypes.data_as(FP), spec.ctypes.data_as(FP), M, ext, size, size, C,
+                                           tx, tx * tx, L, org)
+        assert rc == 0
+        got = spec[..., 0].astype(np.float64) + 1j * spec[..., 1]
+        ref = reference_spectrum(tile_windows(img, N, tx, tx * tx, L, org, ext), N)
+        assert np.abs(got - ref).max() <= 3e-6 * max(np.abs(ref).max(), 1), (what, N, H, k)
+
+
+@pytest.mark.parametrize("N,H,k,c0", [(16, 37, 5, 0), (16, 37, 5, 4), (24, 50, 3, 2), (48, 65, 4, 0), (64, 100, 9, 8)])
+def test_tiled_inverse_scatters_each_tile_once(replay, N, H, k, c0):
+    """Rows / columns [c0, c0 + L) of every transform's output land at the tile's place;
+    the tiles cover the image exactly once and nothing else is written."""
+    rng = np.random.default_rng(7 * N + c0)
+    L = N - k + 1
+    S, C = 2, 3
+    tx = -(-H // L)
+    M = S * tx * tx * C
+    patches = rng.uniform(-1, 1, (M, N, N))
+    spec = reference_spectrum(patches, N)
+    sp = np.ascontiguousarray(np.stack([spec.real, spec.imag], -1).astype(np.float32))
+    dst = np.full((S, C, H, H), np.nan, np.float32)
+    guard = np.full(64, np.nan, np.float32)
+    buf = np.concatenate([guard, dst.ravel(), guard])
+    view = buf[64:64 + dst.size]
+    rc = replay.replay_ifft2d_c2r_tiled(N, sp.ctypes.data_as(FP), view.ctypes.data_as(FP), M, L, c0, H, H, C, tx, tx * tx, L)
+    assert rc == 0
+    assert np.all(np.isnan(buf[:64])) and np.all(np.isnan(buf[-64:]))
+    got = view.reshape(S, C, H, H)
+    assert not np.isnan(got).any()
+    for s in range(S):
+        for t in range(tx * tx):
+            oy, ox = (t // tx) * L, (t % tx) * L
+            for c in range(C):
+                h, w = min(L, H - oy), min(L, H - ox)
+                ref = patches[(s * tx * tx + t) * C + c, c0:c0 + h, c0:c0 + w]
+                assert np.abs(got[s, c, oy:oy + h, ox:ox + w] - ref).max() < 3e-6

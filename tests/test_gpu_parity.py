@@ -50,7 +50,8 @@ def run_three(fc, layer, x, w, g):
     dx = plan.bprop(gd, wd)
     dw = plan.accgrad(gd, xd)
     torch.cuda.synchronize()
-    assert plan.valid_slots() == fc.SPEC_X | fc.SPEC_W | fc.SPEC_G
+    expect = fc.SPEC_X | fc.SPEC_W | fc.SPEC_G | (fc.SPEC_G2 if plan.tiling[0] else 0)
+    assert plan.valid_slots() == expect
     return plan, y.cpu().numpy(), dx.cpu().numpy(), dw.cpu().numpy()
 
 
@@ -189,6 +190,66 @@ def test_memory_efficient_mode_matches_cached_mode_at_full_size(fc):
         a, b = run(cached), run(lean)
         torch.cuda.synchronize()
         assert torch.equal(a, b), name
+
+
+TILED_LAYERS = [
+    wl.Layer("n65_k3", 2, 3, 2, 65, 3, 0.1, 91),          # one past the largest transform
+    wl.Layer("n100_k5", 2, 3, 4, 100, 5, 0.1, 92),
+    wl.Layer("n128_k3", 1, 2, 3, 128, 3, 0.1, 93),
+    wl.Layer("n96_k11", 2, 2, 2, 96, 11, 0.05, 94),
+    wl.Layer("n70_k40", 1, 2, 2, 70, 40, 0.05, 95),       # large kernel: tiles are mostly overlap
+    wl.Layer("n224_k11_f3", 1, 3, 4, 224, 11, 0.05, 96),  # first-layer-like image size
+    wl.Layer("n80_k1", 2, 2, 2, 80, 1, 0.1, 97),          # k = 1: no overlap at all
+    wl.Layer("n77_k6_ragged", 3, 5, 7, 77, 6, 0.1, 98),   # odd map counts: ragged transform groups
+]
+
+
+@pytest.mark.parametrize("layer", TILED_LAYERS, ids=lambda l: l.name)
+def test_full_parity_tiled_layers(fc, layer):
+    """n > 64: the maps are cut into overlapping tiles (overlap-save); all three passes against the oracle."""
+    print(f"\ncase {layer}", flush=True)
+    x, w, g = wl.make_inputs(layer)
+    plan = fc.Plan(layer.S, layer.f, layer.fo, layer.n, layer.k)
+    L, nt, nt2 = plan.tiling
+    print(f"N={plan.fft_size} L={L} tiles {nt}x{nt} (y), {nt2}x{nt2} (dx)", flush=True)
+    assert L > 0
+    xd, wd, gd = dev(x), dev(w), dev(g)
+    G = 1024
+    outs = []
+    for shape in (layer.shapes()[2], layer.shapes()[0], layer.shapes()[1]):
+        numel = int(np.prod(shape))
+        buf = torch.full((numel + 2 * G,), float("nan"), dtype=torch.float32, device="cuda")
+        outs.append((buf, buf[G:G + numel].view(shape)))
+    # accGrad first, then bprop, then fprop: every pass finds a different set of cached spectra
+    dw = plan.accgrad(gd, xd, outs[2][1])
+    dx = plan.bprop(gd, wd, outs[1][1])
+    y = plan.fprop(xd, wd, outs[0][1])
+    torch.cuda.synchronize()
+    assert plan.valid_slots() == fc.SPEC_X | fc.SPEC_W | fc.SPEC_G | fc.SPEC_G2
+    for buf, _ in outs:
+        assert torch.isnan(buf[:G]).all() and torch.isnan(buf[-G:]).all(), "stray write outside an output tensor"
+    check(y.cpu().numpy(), direct.fprop(x, w), f"{layer.name} fprop")
+    check(dx.cpu().numpy(), direct.bprop(g, w, layer.n), f"{layer.name} bprop")
+    check(dw.cpu().numpy(), direct.accgrad(g, x, layer.k), f"{layer.name} accgrad")
+    # invalidating dL/dy drops both of its transforms; the memory-efficient plan gives the same results
+    plan.invalidate(fc.SPEC_G)
+    assert plan.valid_slots() == fc.SPEC_X | fc.SPEC_W
+    lean = fc.Plan(layer.S, layer.f, layer.fo, layer.n, layer.k, flags=fc.RECOMPUTE)
+    dx2 = lean.bprop(gd, wd)
+    dw2 = lean.accgrad(gd, xd)
+    y2 = lean.fprop(xd, wd)
+    dx3 = lean.bprop(gd, wd)
+    torch.cuda.synchronize()
+    assert torch.equal(y2, y) and torch.equal(dx2, dx) and torch.equal(dw2, dw) and torch.equal(dx3, dx)
+    assert lean.valid_slots() == 0
+
+
+def test_sampled_parity_tiled_full_size(fc):
+    """A first-layer-like tiled layer at a realistic size (S=32, 3 -> 64 maps, 128 x 128, k = 7), oracle on a sample."""
+    layer = wl.Layer("tiled_first", 32, 3, 64, 128, 7, 0.05, 99)
+    print(f"\ncase {layer}", flush=True)
+    sampled_check_tiled = sampled_check
+    sampled_check_tiled(fc, layer, (24, 24, 96))
 
 
 EDGE_LAYERS = [
