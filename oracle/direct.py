@@ -49,7 +49,7 @@ def _load():
         for name in ("oracle_fprop", "oracle_bprop", "oracle_accgrad"):
             fn = getattr(lib, name)
             fn.restype = None
-            fn.argtypes = [dp, dp, dp] + [ctypes.c_int] * 5 + [lp, ctypes.c_long]
+            fn.argtypes = [dp, dp, dp] + [ctypes.c_int] * 7 + [lp, ctypes.c_long]
         lib.oracle_num_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -75,58 +75,68 @@ def _units(units):
     return u, u.ctypes.data_as(ctypes.POINTER(ctypes.c_long)), int(u.size)
 
 
+def _pair(v):
+    """An int (square) or a (height, width) pair."""
+    if isinstance(v, (tuple, list)):
+        h, w = v
+        return int(h), int(w)
+    return int(v), int(v)
+
+
 def _dims(x_shape, w_shape):
-    S, f, n, n2 = x_shape
-    fo, f2, k, k2 = w_shape
-    if n != n2 or k != k2 or f != f2 or k > n or min(S, f, fo, n, k) < 1:
+    S, f, nh, nw = x_shape
+    fo, f2, kh, kw = w_shape
+    if f != f2 or kh > nh or kw > nw or min(S, f, fo, nh, nw, kh, kw) < 1:
         raise ValueError(f"inconsistent shapes x{tuple(x_shape)} w{tuple(w_shape)}")
-    return S, f, fo, n, k
+    return S, f, fo, nh, nw, kh, kw
 
 
 def fprop(x, w, units=None):
-    """Eq. (1): y[s,j] = sum_i x[s,i] (star) w[j,i], valid window, shape [S,fo,no,no].
+    """Eq. (1): y[s,j] = sum_i x[s,i] (star) w[j,i], valid window, shape [S,fo,noh,now].
 
     ``units`` (optional) lists output maps s*fo+j; the result is then
-    [len(units), no, no] in list order.
+    [len(units), noh, now] in list order.
     """
     x, w = _f64(x), _f64(w)
-    S, f, fo, n, k = _dims(x.shape, w.shape)
-    no = n - k + 1
+    S, f, fo, nh, nw, kh, kw = _dims(x.shape, w.shape)
+    noh, now = nh - kh + 1, nw - kw + 1
     u, up, nu = _units(units)
-    out = np.empty((nu, no, no) if u is not None else (S, fo, no, no), dtype=np.float64)
-    _load().oracle_fprop(_dp(x), _dp(w), _dp(out), S, f, fo, n, k, up, nu)
+    out = np.empty((nu, noh, now) if u is not None else (S, fo, noh, now), dtype=np.float64)
+    _load().oracle_fprop(_dp(x), _dp(w), _dp(out), S, f, fo, nh, nw, kh, kw, up, nu)
     return out
 
 
 def bprop(g, w, n, units=None):
-    """Eq. (2): dx[s,i] = sum_j g[s,j] (star) w[j,i] rotated, full window, shape [S,f,n,n].
+    """Eq. (2): dx[s,i] = sum_j g[s,j] (star) w[j,i] rotated, full window, shape [S,f,nh,nw].
 
-    ``units`` lists input maps s*f+i.
+    ``n`` is the input size: an int for square maps or (nh, nw).  ``units`` lists input maps s*f+i.
     """
     g, w = _f64(g), _f64(w)
-    fo, f, k, _ = w.shape
+    fo, f, kh, kw = w.shape
+    nh, nw = _pair(n)
     S = g.shape[0]
-    no = n - k + 1
-    if g.shape != (S, fo, no, no):
+    noh, now = nh - kh + 1, nw - kw + 1
+    if g.shape != (S, fo, noh, now):
         raise ValueError(f"g{g.shape} does not match w{w.shape} and n={n}")
     u, up, nu = _units(units)
-    out = np.empty((nu, n, n) if u is not None else (S, f, n, n), dtype=np.float64)
-    _load().oracle_bprop(_dp(g), _dp(w), _dp(out), S, f, fo, n, k, up, nu)
+    out = np.empty((nu, nh, nw) if u is not None else (S, f, nh, nw), dtype=np.float64)
+    _load().oracle_bprop(_dp(g), _dp(w), _dp(out), S, f, fo, nh, nw, kh, kw, up, nu)
     return out
 
 
 def accgrad(g, x, k, units=None):
-    """Eq. (3): dw[j,i] = sum_s g[s,j] (star) x[s,i], k x k window, shape [fo,f,k,k].
+    """Eq. (3): dw[j,i] = sum_s g[s,j] (star) x[s,i], kh x kw window, shape [fo,f,kh,kw].
 
-    ``units`` lists kernels j*f+i.
+    ``k`` is the kernel size: an int for square kernels or (kh, kw).  ``units`` lists kernels j*f+i.
     """
     g, x = _f64(g), _f64(x)
-    S, f, n, _ = x.shape
+    S, f, nh, nw = x.shape
+    kh, kw = _pair(k)
     fo = g.shape[1]
-    no = n - k + 1
-    if g.shape != (S, fo, no, no):
+    noh, now = nh - kh + 1, nw - kw + 1
+    if g.shape != (S, fo, noh, now):
         raise ValueError(f"g{g.shape} does not match x{x.shape} and k={k}")
     u, up, nu = _units(units)
-    out = np.empty((nu, k, k) if u is not None else (fo, f, k, k), dtype=np.float64)
-    _load().oracle_accgrad(_dp(g), _dp(x), _dp(out), S, f, fo, n, k, up, nu)
+    out = np.empty((nu, kh, kw) if u is not None else (fo, f, kh, kw), dtype=np.float64)
+    _load().oracle_accgrad(_dp(g), _dp(x), _dp(out), S, f, fo, nh, nw, kh, kw, up, nu)
     return out

@@ -8,14 +8,17 @@
  * oracle is those sums written out.
  *
  * Notation (paper Sec. 2.1): S minibatch size, f input maps, fo (= f') output
- * maps, n input width, k kernel width, no = n - k + 1 output width.  The paper's
+ * maps, n input width, k kernel width, no = n - k + 1 output width.  The paper
+ * writes square maps and kernels only to keep its notation short; the sums below
+ * carry a height and a width (nh x nw inputs, kh x kw kernels,
+ * noh = nh - kh + 1, now = nw - kw + 1), which is the same definition per axis.  The paper's
  * "*" is read as the cross-correlation used by neural-network layers (stride 1,
  * no spatial padding); bprop is then the adjoint of fprop with respect to x and
  * accGrad the adjoint with respect to w.
  *
  * Layouts (row-major, contiguous, double):
- *   x [S][f ][n ][n ]     w [fo][f][k][k]
- *   y [S][fo][no][no]     g = dL/dy like y,  dx like x,  dw like w
+ *   x [S][f ][nh ][nw ]     w [fo][f][kh][kw]
+ *   y [S][fo][noh][now]     g = dL/dy like y,  dx like x,  dw like w
  *
  * Every routine can be restricted to a list of independent output units
  * (whole output maps) so that large layers can be spot-checked; units == NULL
@@ -43,27 +46,27 @@ int oracle_num_threads(void)
 #endif
 }
 
-/* Eq. (1):  y[s,j,p,q] = sum_i sum_{a,b<k} x[s,i,p+a,q+b] * w[j,i,a,b],  0 <= p,q < no. */
+/* Eq. (1):  y[s,j,p,q] = sum_i sum_{a<kh,b<kw} x[s,i,p+a,q+b] * w[j,i,a,b],  0 <= p < noh, 0 <= q < now. */
 void oracle_fprop(const double *x, const double *w, double *out,
-                  int S, int f, int fo, int n, int k,
+                  int S, int f, int fo, int nh, int nw, int kh, int kw,
                   const long *units, long nunits)
 {
-    const int no = n - k + 1;
+    const int noh = nh - kh + 1, now = nw - kw + 1;
     const long total = units ? nunits : (long)S * fo;
 #pragma omp parallel for schedule(dynamic, 1)
     for (long u = 0; u < total; ++u) {
         const long unit = units ? units[u] : u;
         const int s = (int)(unit / fo), j = (int)(unit % fo);
-        double *ymap = out + (size_t)u * no * no;
-        memset(ymap, 0, sizeof(double) * (size_t)no * no);
+        double *ymap = out + (size_t)u * noh * now;
+        memset(ymap, 0, sizeof(double) * (size_t)noh * now);
         for (int i = 0; i < f; ++i)
-            for (int a = 0; a < k; ++a)
-                for (int b = 0; b < k; ++b) {
-                    const double wv = w[IDX4(j, fo, i, f, a, k, b, k)];
-                    for (int p = 0; p < no; ++p) {
-                        const double *xrow = x + IDX4(s, S, i, f, p + a, n, b, n);
-                        double *yrow = ymap + (size_t)p * no;
-                        for (int q = 0; q < no; ++q)
+            for (int a = 0; a < kh; ++a)
+                for (int b = 0; b < kw; ++b) {
+                    const double wv = w[IDX4(j, fo, i, f, a, kh, b, kw)];
+                    for (int p = 0; p < noh; ++p) {
+                        const double *xrow = x + IDX4(s, S, i, f, p + a, nh, b, nw);
+                        double *yrow = ymap + (size_t)p * now;
+                        for (int q = 0; q < now; ++q)
                             yrow[q] += xrow[q] * wv;
                     }
                 }
@@ -71,29 +74,29 @@ void oracle_fprop(const double *x, const double *w, double *out,
 }
 
 /* Eq. (2) with the sum over output maps written out:
- *   dx[s,i,p,q] = sum_j sum_{a,b<k} g[s,j,p-a,q-b] * w[j,i,a,b],  0 <= p,q < n,
- * where g is taken as zero outside [0,no)^2. */
+ *   dx[s,i,p,q] = sum_j sum_{a<kh,b<kw} g[s,j,p-a,q-b] * w[j,i,a,b],  0 <= p < nh, 0 <= q < nw,
+ * where g is taken as zero outside [0,noh) x [0,now). */
 void oracle_bprop(const double *g, const double *w, double *out,
-                  int S, int f, int fo, int n, int k,
+                  int S, int f, int fo, int nh, int nw, int kh, int kw,
                   const long *units, long nunits)
 {
-    const int no = n - k + 1;
+    const int noh = nh - kh + 1, now = nw - kw + 1;
     const long total = units ? nunits : (long)S * f;
 #pragma omp parallel for schedule(dynamic, 1)
     for (long u = 0; u < total; ++u) {
         const long unit = units ? units[u] : u;
         const int s = (int)(unit / f), i = (int)(unit % f);
-        double *dmap = out + (size_t)u * n * n;
-        memset(dmap, 0, sizeof(double) * (size_t)n * n);
+        double *dmap = out + (size_t)u * nh * nw;
+        memset(dmap, 0, sizeof(double) * (size_t)nh * nw);
         for (int j = 0; j < fo; ++j)
-            for (int a = 0; a < k; ++a)
-                for (int b = 0; b < k; ++b) {
-                    const double wv = w[IDX4(j, fo, i, f, a, k, b, k)];
-                    /* p - a in [0,no)  <=>  p in [a, a+no) */
-                    for (int p = a; p < a + no; ++p) {
-                        const double *grow = g + IDX4(s, S, j, fo, p - a, no, 0, no);
-                        double *drow = dmap + (size_t)p * n + b;
-                        for (int q = 0; q < no; ++q)      /* q here is (q_out - b) */
+            for (int a = 0; a < kh; ++a)
+                for (int b = 0; b < kw; ++b) {
+                    const double wv = w[IDX4(j, fo, i, f, a, kh, b, kw)];
+                    /* p - a in [0,noh)  <=>  p in [a, a+noh) */
+                    for (int p = a; p < a + noh; ++p) {
+                        const double *grow = g + IDX4(s, S, j, fo, p - a, noh, 0, now);
+                        double *drow = dmap + (size_t)p * nw + b;
+                        for (int q = 0; q < now; ++q)      /* q here is (q_out - b) */
                             drow[q] += grow[q] * wv;
                     }
                 }
@@ -101,29 +104,29 @@ void oracle_bprop(const double *g, const double *w, double *out,
 }
 
 /* Eq. (3) with the sums over the minibatch and over positions written out:
- *   dw[j,i,a,b] = sum_s sum_{p,q<no} g[s,j,p,q] * x[s,i,p+a,q+b],  0 <= a,b < k. */
+ *   dw[j,i,a,b] = sum_s sum_{p<noh,q<now} g[s,j,p,q] * x[s,i,p+a,q+b],  0 <= a < kh, 0 <= b < kw. */
 void oracle_accgrad(const double *g, const double *x, double *out,
-                    int S, int f, int fo, int n, int k,
+                    int S, int f, int fo, int nh, int nw, int kh, int kw,
                     const long *units, long nunits)
 {
-    const int no = n - k + 1;
+    const int noh = nh - kh + 1, now = nw - kw + 1;
     const long total = units ? nunits : (long)fo * f;
 #pragma omp parallel for schedule(dynamic, 1)
     for (long u = 0; u < total; ++u) {
         const long unit = units ? units[u] : u;
         const int j = (int)(unit / f), i = (int)(unit % f);
-        double *kmap = out + (size_t)u * k * k;
-        for (int a = 0; a < k; ++a)
-            for (int b = 0; b < k; ++b) {
+        double *kmap = out + (size_t)u * kh * kw;
+        for (int a = 0; a < kh; ++a)
+            for (int b = 0; b < kw; ++b) {
                 double acc = 0.0;
                 for (int s = 0; s < S; ++s)
-                    for (int p = 0; p < no; ++p) {
-                        const double *grow = g + IDX4(s, S, j, fo, p, no, 0, no);
-                        const double *xrow = x + IDX4(s, S, i, f, p + a, n, b, n);
-                        for (int q = 0; q < no; ++q)
+                    for (int p = 0; p < noh; ++p) {
+                        const double *grow = g + IDX4(s, S, j, fo, p, noh, 0, now);
+                        const double *xrow = x + IDX4(s, S, i, f, p + a, nh, b, nw);
+                        for (int q = 0; q < now; ++q)
                             acc += grow[q] * xrow[q];
                     }
-                kmap[a * k + b] = acc;
+                kmap[a * kw + b] = acc;
             }
     }
 }

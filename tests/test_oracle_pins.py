@@ -241,3 +241,61 @@ def test_shape_errors():
         direct.fprop(np.zeros((1, 2, 4, 4)), np.zeros((1, 2, 5, 5)))
     with pytest.raises(ValueError):
         direct.bprop(np.zeros((1, 2, 3, 3)), np.zeros((2, 2, 2, 2)), 5)
+
+
+# ---------------------------------------------------------------- rectangular maps and kernels
+# (Sec. 2.1 writes square maps only to keep the notation short; a wrong axis, a transposed
+# kernel or swapped height / width in any of the three loops fails at least one of these.)
+
+def rand_rect(seed, S, f, fo, nh, nw, kh, kw):
+    r = rng(seed)
+    return (r.uniform(-1, 1, (S, f, nh, nw)), r.standard_normal((fo, f, kh, kw)),
+            r.standard_normal((S, fo, nh - kh + 1, nw - kw + 1)))
+
+
+RECT = [(2, 3, 2, 7, 11, 3, 2), (1, 2, 3, 12, 5, 1, 4), (2, 2, 2, 6, 9, 6, 2), (3, 1, 2, 5, 8, 2, 8)]
+
+
+@pytest.mark.parametrize("dims", RECT)
+def test_rectangular_single_pairs_match_scipy(dims):
+    S, f, fo, nh, nw, kh, kw = dims
+    x, w, g = rand_rect(21, 1, 1, 1, nh, nw, kh, kw)
+    np.testing.assert_allclose(direct.fprop(x, w)[0, 0], sps.correlate2d(x[0, 0], w[0, 0], "valid"), rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(direct.bprop(g, w, (nh, nw))[0, 0], sps.convolve2d(g[0, 0], w[0, 0], "full"), rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(direct.accgrad(g, x, (kh, kw))[0, 0], sps.correlate2d(x[0, 0], g[0, 0], "valid"), rtol=1e-12, atol=1e-13)
+
+
+@pytest.mark.parametrize("dims", RECT)
+def test_rectangular_layer_matches_torch_and_adjoint_identity(dims):
+    S, f, fo, nh, nw, kh, kw = dims
+    x, w, g = rand_rect(22, *dims)
+    xt = torch.tensor(x, dtype=torch.float64, requires_grad=True)
+    wt = torch.tensor(w, dtype=torch.float64, requires_grad=True)
+    yt = torch.nn.functional.conv2d(xt, wt)
+    yt.backward(torch.tensor(g, dtype=torch.float64))
+    y, dx, dw = direct.fprop(x, w), direct.bprop(g, w, (nh, nw)), direct.accgrad(g, x, (kh, kw))
+    assert y.shape == g.shape and dx.shape == x.shape and dw.shape == w.shape
+    np.testing.assert_allclose(y, yt.detach().numpy(), rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(dx, xt.grad.numpy(), rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(dw, wt.grad.numpy(), rtol=1e-11, atol=1e-12)
+    a, b, c = np.vdot(y, g), np.vdot(x, dx), np.vdot(w, dw)
+    assert abs(a - b) <= 1e-12 * abs(a) + 1e-12 and abs(a - c) <= 1e-12 * abs(a) + 1e-12
+
+
+def test_rectangular_brute_force_and_delta_kernel():
+    S, f, fo, nh, nw, kh, kw = 2, 2, 2, 4, 3, 2, 3
+    x, w, g = rand_rect(23, S, f, fo, nh, nw, kh, kw)
+    noh, now = nh - kh + 1, nw - kw + 1
+    y = np.zeros((S, fo, noh, now)); dx = np.zeros_like(x); dw = np.zeros_like(w)
+    for s, j, i, p, q, a, b in itertools.product(range(S), range(fo), range(f), range(noh), range(now), range(kh), range(kw)):
+        y[s, j, p, q] += x[s, i, p + a, q + b] * w[j, i, a, b]
+        dx[s, i, p + a, q + b] += g[s, j, p, q] * w[j, i, a, b]
+        dw[j, i, a, b] += g[s, j, p, q] * x[s, i, p + a, q + b]
+    np.testing.assert_allclose(direct.fprop(x, w), y, rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(direct.bprop(g, w, (nh, nw)), dx, rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(direct.accgrad(g, x, (kh, kw)), dw, rtol=1e-13, atol=1e-13)
+    # delta kernel at (a0, b0) of a 2 x 4 kernel selects the window shifted by (a0, b0)
+    x = rng(24).uniform(-1, 1, (1, 1, 6, 9))
+    for a0, b0 in ((0, 0), (1, 3), (0, 2)):
+        wd = np.zeros((1, 1, 2, 4)); wd[0, 0, a0, b0] = 1.0
+        assert np.array_equal(direct.fprop(x, wd)[0, 0], x[0, 0, a0:a0 + 5, b0:b0 + 6])
