@@ -232,7 +232,7 @@ def measure(layer, args, inputs=None):
                              "frac": gbs / PEAK_HBM_GBS, "mfma_TFLOPs": achieved})
     # HBM-side view of the transform stages: algorithmic bytes = unpadded real map + stored half spectrum
     # (images, image extent, transforms): a layer with n > 64 runs one transform per tile
-    L, nt, nt2 = plan.tiling
+    (L, _), (nt, _), (nt2, _) = plan.tiling   # bench layers are square
     T, T2 = nt * nt, nt2 * nt2
     ext = {"fft_x": (layer.S * layer.f, layer.n, layer.S * layer.f * T),
            "fft_w": (layer.fo * layer.f, layer.k, layer.fo * layer.f),

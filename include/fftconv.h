@@ -44,6 +44,15 @@ typedef struct {
     unsigned flags; /* 0 or FFTCONV_RECOMPUTE */
 } fftconv_desc;
 
+/* The same layer with a height and a width for maps and kernels (the paper writes square
+ * ones only to keep its notation short, Sec. 2.1): x [S][f][nh][nw], w [fo][f][kh][kw],
+ * y and dL/dy [S][fo][nh-kh+1][nw-kw+1].  The transform stays square: N covers
+ * max(nh, nw). */
+typedef struct {
+    int S, f, fo, nh, nw, kh, kw;
+    unsigned flags; /* 0 or FFTCONV_RECOMPUTE */
+} fftconv_desc2d;
+
 /* Plan flag: the memory-efficient mode all of the paper's own timings assume (Sec. 2.3).
  * No spectrum is reused: every pass transforms both of its operands again, and the
  * workspace shrinks to the three slots x, w, g (8*B*(S*f + fo*f + S*fo) bytes, the
@@ -85,6 +94,7 @@ enum {
  * n > 64, for slots of more than 2^31 transforms, or for unknown flag bits.  *out is
  * written only on success. */
 int fftconv_plan(fftconv_plan_t *out, const fftconv_desc *d);
+int fftconv_plan2d(fftconv_plan_t *out, const fftconv_desc2d *d);   /* same, rectangular maps / kernels */
 int fftconv_plan_destroy(fftconv_plan_t p);
 
 /* Transform size N (2^m or 3 * 2^m, >= n) and number of stored bins B = N*N/2 + 2:
@@ -93,7 +103,7 @@ int fftconv_plan_destroy(fftconv_plan_t p);
 int fftconv_fft_size(fftconv_plan_t p);
 int fftconv_num_bins(fftconv_plan_t p);
 
-/* Layers with n > 64 are cut into tiles (the paper instead pads the whole map to the next
+/* Layers with a map side above 64 are cut into tiles (the paper instead pads the whole map to the next
  * power of two, Sec. 4).  With L = N - k + 1: y and dL/dy are cut into ceil(no / L)^2 blocks
  * of L x L, dx into ceil(n / L)^2.  fprop transforms the N x N window of x under each
  * block of y, multiplies and keeps rows / columns [0, L) of the inverse transform; accGrad
@@ -101,9 +111,11 @@ int fftconv_num_bins(fftconv_plan_t p);
  * sums over samples and tiles; bprop transforms, for each block of dx, the N x N window of
  * dL/dy that starts k - 1 rows and columns before it and keeps rows / columns [k-1, N) of
  * the inverse transform (the part of a circular result that no wrap-around touches).  The
- * tiles of a sample act as extra samples for the contraction.
- * *tile = L (0: not tiled), *tiles_y and *tiles_dx = blocks per dimension (1 if not tiled). */
-int fftconv_tiling(fftconv_plan_t p, int *tile, int *tiles_y, int *tiles_dx);
+ * tiles of a sample act as extra samples for the contraction.  (Rectangular layers: L, the
+ * block counts, the window offsets and the kept rows / columns are per axis, with kh and kw.)
+ * Each array is (rows, columns): tile = (Ly, Lx), (0, 0) if not tiled; tiles_y and tiles_dx =
+ * blocks per axis of y and of dx, (1, 1) if not tiled. */
+int fftconv_tiling(fftconv_plan_t p, int tile[2], int tiles_y[2], int tiles_dx[2]);
 
 /* Bytes of device workspace the passes need: the x, w and g spectra (8*B bytes
  * per map for S*f + fo*f + S*fo maps, the count of Sec. 2.3) plus one result

@@ -81,11 +81,11 @@ int replay_fft_size(int n) { return fft_size_for(n); }
 int replay_extent_class(int N, int ext) { return extent_class(N, ext); }
 int replay_maps_per_block(int N) { return maps_per_block(N); }
 
-// src: [M][ext][ext] floats; spec: [B][M] complex (2 floats each), B = N*N/2 + 2.
-int replay_fft2d_r2c(int N, const float *src, float *spec, int M, int ext)
+// src: [M][ext_y][ext_x] floats; spec: [B][M] complex (2 floats each), B = N*N/2 + 2.
+int replay_fft2d_r2c(int N, const float *src, float *spec, int M, int ext_y, int ext_x)
 {
-    FwdArgs a{src, reinterpret_cast<cf *>(spec), M, ext};
-    const int T = maps_per_block(N), NX = extent_class(N, ext);
+    FwdArgs a{src, reinterpret_cast<cf *>(spec), M, ext_y, ext_x};
+    const int T = maps_per_block(N), NX = extent_class(N, ext_y > ext_x ? ext_y : ext_x);
 #define X(n_, t_, nx_) \
     if (N == n_ && T == t_ && NX == nx_) { replay_forward<TileGeom<n_, t_, nx_, rounds_for(n_)>>(a); return 0; }
     FFTCONV_FOR_EACH_GEOM(X)
@@ -93,10 +93,10 @@ int replay_fft2d_r2c(int N, const float *src, float *spec, int M, int ext)
     return 1;
 }
 
-int replay_ifft2d_c2r_crop(int N, const float *spec, float *dst, int M, int crop, int accumulate)
+int replay_ifft2d_c2r_crop(int N, const float *spec, float *dst, int M, int crop_y, int crop_x, int accumulate)
 {
-    InvArgs a{reinterpret_cast<const cf *>(spec), dst, M, crop, 1.0f / (float)(N * N)};
-    const int T = maps_per_block(N), NX = extent_class(N, crop);
+    InvArgs a{reinterpret_cast<const cf *>(spec), dst, M, crop_y, crop_x, 1.0f / (float)(N * N)};
+    const int T = maps_per_block(N), NX = extent_class(N, crop_y > crop_x ? crop_y : crop_x);
 #define X(n_, t_, nx_) \
     if (N == n_ && T == t_ && NX == nx_) { replay_inverse<TileGeom<n_, t_, nx_, rounds_for(n_)>>(a, accumulate != 0); return 0; }
     FFTCONV_FOR_EACH_GEOM(X)
@@ -106,10 +106,10 @@ int replay_ifft2d_c2r_crop(int N, const float *spec, float *dst, int M, int crop
 
 // Tiled variants: src / dst are [S][C][H][W] images, M = S * tiles * C transforms of size N
 // (the full-extent geometry of N), tile t of an image at (ty * step + org, tx * step + org).
-int replay_fft2d_r2c_tiled(int N, const float *src, float *spec, int M, int ext, int H, int W, int C, int tiles_x,
-                           int tiles, int step, int org)
+int replay_fft2d_r2c_tiled(int N, const float *src, float *spec, int M, int ext_y, int ext_x, int H, int W, int C,
+                           int tiles_x, int tiles, int step_y, int step_x, int org_y, int org_x)
 {
-    FwdArgs a{src, reinterpret_cast<cf *>(spec), M, ext, {H, W, C, tiles_x, tiles, step, org}};
+    FwdArgs a{src, reinterpret_cast<cf *>(spec), M, ext_y, ext_x, {H, W, C, tiles_x, tiles, step_y, step_x, org_y, org_x}};
     const int T = maps_per_block(N);
 #define X(n_, t_, nx_) \
     if (N == n_ && T == t_ && n_ == nx_) { replay_forward<TileGeom<n_, t_, nx_, rounds_for(n_)>, true>(a); return 0; }
@@ -118,10 +118,11 @@ int replay_fft2d_r2c_tiled(int N, const float *src, float *spec, int M, int ext,
     return 1;
 }
 
-int replay_ifft2d_c2r_tiled(int N, const float *spec, float *dst, int M, int crop, int c0, int H, int W, int C,
-                            int tiles_x, int tiles, int step)
+int replay_ifft2d_c2r_tiled(int N, const float *spec, float *dst, int M, int crop_y, int crop_x, int c0_y, int c0_x,
+                            int H, int W, int C, int tiles_x, int tiles, int step_y, int step_x)
 {
-    InvArgs a{reinterpret_cast<const cf *>(spec), dst, M, crop, 1.0f / (float)(N * N), c0, {H, W, C, tiles_x, tiles, step, 0}};
+    InvArgs a{reinterpret_cast<const cf *>(spec), dst, M, crop_y, crop_x, 1.0f / (float)(N * N), c0_y, c0_x,
+              {H, W, C, tiles_x, tiles, step_y, step_x, 0, 0}};
     const int T = maps_per_block(N);
 #define X(n_, t_, nx_) \
     if constexpr (n_ == nx_) { if (N == n_ && T == t_) { replay_inverse<TileGeom<n_, t_, nx_, rounds_for(n_)>, true>(a, false); return 0; } }

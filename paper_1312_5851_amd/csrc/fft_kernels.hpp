@@ -49,31 +49,32 @@ namespace fftconv {
 // kernels below).  Transform m of a tiled tensor [S][C][H][W] is tile t of image s * C + c with
 //     m = (s * tiles + t) * C + c,   t = ty * tiles_x + tx,
 // i.e. the tiles of a sample are extra samples for the contraction.  A tile's window starts
-// at (ty * step + org, tx * step + org) of its image.
+// at (ty * step_y + org_y, tx * step_x + org_x) of its image.
 struct Tiling {
-    int H, W;           // image size
-    int C;              // images per sample (f or f')
-    int tiles_x, tiles; // tiles per image row, tiles per image
-    int step;           // distance between neighbouring tile origins
-    int org;            // offset of the first origin (0, or -(k-1) for the windows of bprop)
+    int H, W;             // image size
+    int C;                // images per sample (f or f')
+    int tiles_x, tiles;   // tiles per image row, tiles per image
+    int step_y, step_x;   // distance between neighbouring tile origins
+    int org_y, org_x;     // offset of the first origin (0, or -(k-1) for the windows of bprop)
 };
 
 struct FwdArgs {
-    const float *src;   // [M][ext][ext] real maps (tiled kernels: [S][C][H][W] images)
-    cf *spec;           // [B][M] bin-major spectrum, B = N*N/2 + 2 stored bins
-    int M;              // number of transforms
-    int ext;            // spatial extent of a map or window; everything beyond is zero padding
-    Tiling t;           // read by the tiled kernels only
+    const float *src;     // [M][ext_y][ext_x] real maps (tiled kernels: [S][C][H][W] images)
+    cf *spec;             // [B][M] bin-major spectrum, B = N*N/2 + 2 stored bins
+    int M;                // number of transforms
+    int ext_y, ext_x;     // spatial extent of a map or window; everything beyond is zero padding
+    Tiling t;             // read by the tiled kernels only
 };
 
 struct InvArgs {
-    const cf *spec;     // [B][M]
-    float *dst;         // [M][crop][crop] (tiled kernels: [S][C][H][W] images)
+    const cf *spec;       // [B][M]
+    float *dst;           // [M][crop_y][crop_x] (tiled kernels: [S][C][H][W] images)
     int M;
-    int crop;           // stored window [0,crop)^2 (tiled kernels: [c0, c0 + crop)^2, stored at the tile origin)
-    float scale;        // 1 / N^2
-    int c0;             // tiled kernels: first stored row / column of the transform's output
-    Tiling t;           // read by the tiled kernels only
+    int crop_y, crop_x;   // stored window [0,crop_y) x [0,crop_x)
+                          // (tiled kernels: [c0_y, c0_y + crop_y) x [c0_x, c0_x + crop_x), stored at the tile origin)
+    float scale;          // 1 / N^2
+    int c0_y, c0_x;       // tiled kernels: first stored row / column of the transform's output
+    Tiling t;             // read by the tiled kernels only
 };
 
 struct TileOrigin {
@@ -86,8 +87,8 @@ FC_HD TileOrigin tile_origin(int m, const Tiling &t)
     const int s = sp / t.tiles, tile = sp % t.tiles;
     TileOrigin o;
     o.image = s * t.C + c;
-    o.oy = (tile / t.tiles_x) * t.step + t.org;
-    o.ox = (tile % t.tiles_x) * t.step + t.org;
+    o.oy = (tile / t.tiles_x) * t.step_y + t.org_y;
+    o.ox = (tile % t.tiles_x) * t.step_x + t.org_x;
     return o;
 }
 
@@ -132,17 +133,17 @@ FC_HD bool fwd_y_compute(int tid, int blk, const FwdArgs &a, cf (&z)[G::N])
     // Loads are unconditional from clamped (always valid) addresses and masked
     // afterwards, so that they issue back to back; rows beyond the extent are
     // skipped by a wave-uniform branch.
-    const bool va = (ma < a.M) && (x < a.ext), vb = (mb < a.M) && (x < a.ext);
-    const int xc = x < a.ext ? x : a.ext - 1;
+    const bool va = (ma < a.M) && (x < a.ext_x), vb = (mb < a.M) && (x < a.ext_x);
+    const int xc = x < a.ext_x ? x : a.ext_x - 1;
     const int mac = ma < a.M ? ma : a.M - 1, mbc = mb < a.M ? mb : a.M - 1;
-    const float *pa = a.src + ((size_t)mac * a.ext) * a.ext + xc;
-    const float *pb = a.src + ((size_t)mbc * a.ext) * a.ext + xc;
+    const float *pa = a.src + ((size_t)mac * a.ext_y) * a.ext_x + xc;
+    const float *pb = a.src + ((size_t)mbc * a.ext_y) * a.ext_x + xc;
     float fa[NX], fb[NX];
     static_for<0, NX>([&](auto yi) {
         constexpr int y = decltype(yi)::value;
-        if (y < a.ext) {
-            fa[y] = pa[y * a.ext];
-            fb[y] = pb[y * a.ext];
+        if (y < a.ext_y) {
+            fa[y] = pa[y * a.ext_x];
+            fb[y] = pb[y * a.ext_x];
         } else {
             fa[y] = 0.0f;
             fb[y] = 0.0f;
@@ -172,11 +173,11 @@ FC_HD bool fwd_y_compute_tiled(int tid, int blk, const FwdArgs &a, cf (&z)[G::N]
         const int m = blk * G::T + 2 * p + which;
         const TileOrigin o = tile_origin(m < a.M ? m : a.M - 1, a.t);
         const int xg = o.ox + x;
-        const bool vx = (m < a.M) && (x < a.ext) && xg >= 0 && xg < a.t.W;
+        const bool vx = (m < a.M) && (x < a.ext_x) && xg >= 0 && xg < a.t.W;
         const int xc = xg < 0 ? 0 : (xg < a.t.W ? xg : a.t.W - 1);
         // valid window rows [ylo, yhi)
         const int ylo = o.oy < 0 ? -o.oy : 0;
-        const int yhi = a.ext < a.t.H - o.oy ? a.ext : a.t.H - o.oy;
+        const int yhi = a.ext_y < a.t.H - o.oy ? a.ext_y : a.t.H - o.oy;
         const float *col = a.src + (size_t)o.image * a.t.H * a.t.W + xc;
         static_for<0, NX>([&](auto yi) {
             constexpr int y = decltype(yi)::value;
@@ -349,14 +350,14 @@ FC_HD void store_column(float *col, bool valid, const InvArgs &a, Get &&get)
     if constexpr (ACC) {
         static_for<0, G::NX>([&](auto yi) {
             constexpr int y = decltype(yi)::value;
-            old[y] = (y < a.crop) ? col[y * a.crop] : 0.0f;
+            old[y] = (y < a.crop_y) ? col[y * a.crop_x] : 0.0f;
         });
     }
     static_for<0, G::NX>([&](auto yi) {
         constexpr int y = decltype(yi)::value;
-        if (y < a.crop) {
-            if constexpr (ACC) col[y * a.crop] = old[y] + get(yi) * a.scale;
-            else col[y * a.crop] = get(yi) * a.scale;
+        if (y < a.crop_y) {
+            if constexpr (ACC) col[y * a.crop_x] = old[y] + get(yi) * a.scale;
+            else col[y * a.crop_x] = get(yi) * a.scale;
         }
     });
 }
@@ -370,11 +371,11 @@ FC_HD void inv_y_finish(int tid, int blk, const InvArgs &a, cf (&z)[G::N])
     const int p = tid / NX, x = tid % NX;
     const int ma = blk * G::T + 2 * p, mb = ma + 1;
     fft_dif<N, true, 0, first_outputs_mask<N>(NX)>(z);
-    if (x >= a.crop) return;
-    store_column<G, ACC>(a.dst + ((size_t)ma * a.crop) * a.crop + x, ma < a.M, a, [&](auto yi) {
+    if (x >= a.crop_x) return;
+    store_column<G, ACC>(a.dst + ((size_t)ma * a.crop_y) * a.crop_x + x, ma < a.M, a, [&](auto yi) {
         return z[brev<N>(decltype(yi)::value)].x;
     });
-    store_column<G, ACC>(a.dst + ((size_t)mb * a.crop) * a.crop + x, mb < a.M, a, [&](auto yi) {
+    store_column<G, ACC>(a.dst + ((size_t)mb * a.crop_y) * a.crop_x + x, mb < a.M, a, [&](auto yi) {
         return z[brev<N>(decltype(yi)::value)].y;
     });
 }
@@ -389,19 +390,19 @@ FC_HD void inv_y_finish_tiled(int tid, int blk, const InvArgs &a, cf (&z)[G::N])
     if (tid >= G::YITEMS) return;
     const int p = tid / NX, x = tid % NX;
     fft_dif<N, true>(z);
-    const int xs = x - a.c0;
-    if (xs < 0 || xs >= a.crop) return;
+    const int xs = x - a.c0_x;
+    if (xs < 0 || xs >= a.crop_x) return;
     static_for<0, 2>([&](auto wi) {
         constexpr int which = decltype(wi)::value;
         const int m = blk * G::T + 2 * p + which;
         if (m >= a.M) return;
         const TileOrigin o = tile_origin(m, a.t);
         if (o.ox + xs >= a.t.W) return;
-        const int rows = a.crop < a.t.H - o.oy ? a.crop : a.t.H - o.oy;
+        const int rows = a.crop_y < a.t.H - o.oy ? a.crop_y : a.t.H - o.oy;
         float *col = a.dst + ((size_t)o.image * a.t.H + o.oy) * a.t.W + o.ox + xs;
         static_for<0, N>([&](auto yi) {
             constexpr int y = decltype(yi)::value;
-            const int ys = y - a.c0;
+            const int ys = y - a.c0_y;
             if (ys >= 0 && ys < rows) {
                 const cf v = z[brev<N>(y)];
                 col[(size_t)ys * a.t.W] = (which == 0 ? v.x : v.y) * a.scale;

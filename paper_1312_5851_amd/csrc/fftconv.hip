@@ -135,12 +135,12 @@ int choose_gemm_tile(int Md, int Nd, int /*Kd*/, int /*bins*/)
 }  // namespace
 
 struct fftconv_plan_s {
-    fftconv_desc d;
-    int no, N, B;
-    // Tiling (n > 64 only; otherwise L = 0 and one "tile" per image): tiles are L x L output
-    // blocks, nt per dimension for y (and for the blocks of dL/dy and windows of x), nt2 per
-    // dimension for dx (and for the windows of dL/dy that bprop reads).
-    int L, nt, nt2;
+    fftconv_desc2d d;
+    int noh, now, N, B;
+    // Tiling (maps larger than 64 only; otherwise Ly = Lx = 0 and one "tile" per image): tiles
+    // are Ly x Lx output blocks, nty x ntx of them for y (and for the blocks of dL/dy and the
+    // windows of x), nty2 x ntx2 for dx (and for the windows of dL/dy that bprop reads).
+    int Ly, Lx, nty, ntx, nty2, ntx2;
     long maps_x, maps_w, maps_g, maps_g2, maps_out;   // transforms per slot
     size_t off_x, off_w, off_g, off_g2, off_out, ws_bytes;
     unsigned valid;
@@ -234,38 +234,39 @@ cf *slot_ptr(fftconv_plan_t p, void *ws, int slot)
     return reinterpret_cast<cf *>(static_cast<unsigned char *>(ws) + off);
 }
 
-bool tiled(fftconv_plan_t p) { return p->L > 0; }
+bool tiled(fftconv_plan_t p) { return p->Ly > 0; }
 
 int launch_forward(fftconv_plan_t p, int slot, const float *src, void *ws, hipStream_t stream)
 {
     long M;
-    int ext, stage;
+    int ext_y, ext_x, stage;
     Tiling t{};
+    const fftconv_desc2d &d = p->d;
     switch (slot) {
         case FFTCONV_SPEC_X:   // dense N x N windows of x, one per output tile
-            M = p->maps_x; ext = tiled(p) ? p->N : p->d.n; stage = FFTCONV_STAGE_FFT_X;
-            t = Tiling{p->d.n, p->d.n, p->d.f, p->nt, p->nt * p->nt, p->L, 0};
+            M = p->maps_x; ext_y = tiled(p) ? p->N : d.nh; ext_x = tiled(p) ? p->N : d.nw; stage = FFTCONV_STAGE_FFT_X;
+            t = Tiling{d.nh, d.nw, d.f, p->ntx, p->nty * p->ntx, p->Ly, p->Lx, 0, 0};
             break;
         case FFTCONV_SPEC_W:   // kernels are never tiled
-            M = p->maps_w; ext = p->d.k; stage = FFTCONV_STAGE_FFT_W;
+            M = p->maps_w; ext_y = d.kh; ext_x = d.kw; stage = FFTCONV_STAGE_FFT_W;
             break;
-        case FFTCONV_SPEC_G:   // L x L blocks of dL/dy
-            M = p->maps_g; ext = tiled(p) ? p->L : p->no; stage = FFTCONV_STAGE_FFT_G;
-            t = Tiling{p->no, p->no, p->d.fo, p->nt, p->nt * p->nt, p->L, 0};
+        case FFTCONV_SPEC_G:   // Ly x Lx blocks of dL/dy
+            M = p->maps_g; ext_y = tiled(p) ? p->Ly : p->noh; ext_x = tiled(p) ? p->Lx : p->now; stage = FFTCONV_STAGE_FFT_G;
+            t = Tiling{p->noh, p->now, d.fo, p->ntx, p->nty * p->ntx, p->Ly, p->Lx, 0, 0};
             break;
-        case FFTCONV_SPEC_G2:  // N x N windows of dL/dy starting k-1 before each tile of dx
+        case FFTCONV_SPEC_G2:  // N x N windows of dL/dy starting (kh-1, kw-1) before each tile of dx
             if (!tiled(p)) return FFTCONV_EINVAL;
-            M = p->maps_g2; ext = p->N; stage = FFTCONV_STAGE_FFT_G;
-            t = Tiling{p->no, p->no, p->d.fo, p->nt2, p->nt2 * p->nt2, p->L, -(p->d.k - 1)};
+            M = p->maps_g2; ext_y = ext_x = p->N; stage = FFTCONV_STAGE_FFT_G;
+            t = Tiling{p->noh, p->now, d.fo, p->ntx2, p->nty2 * p->ntx2, p->Ly, p->Lx, -(d.kh - 1), -(d.kw - 1)};
             break;
         default: return FFTCONV_EINVAL;
     }
     const bool use_tiles = tiled(p) && slot != FFTCONV_SPEC_W;
-    const FftEntry *e = find_fft(p->N, use_tiles ? p->N : ext);
+    const FftEntry *e = find_fft(p->N, use_tiles ? p->N : (ext_y > ext_x ? ext_y : ext_x));
     if (!e || (use_tiles && !e->fwd_tiled)) return FFTCONV_EUNSUPPORTED;
     FwdKernel kernel = use_tiles ? e->fwd_tiled : e->fwd;
     if (int rc = allow_lds(kernel, e->lds_bytes)) return rc;
-    FwdArgs a{src, slot_ptr(p, ws, slot), (int)M, ext, t};
+    FwdArgs a{src, slot_ptr(p, ws, slot), (int)M, ext_y, ext_x, t};
     const unsigned blocks = (unsigned)((M + e->T - 1) / e->T);
     StageTimer timer(p, stage, stream);
     hipLaunchKernelGGL(kernel, dim3(blocks), dim3(e->threads), e->lds_bytes, stream, a);
@@ -280,8 +281,8 @@ int launch_forward(fftconv_plan_t p, int slot, const float *src, void *ws, hipSt
 
 void pass_dims(fftconv_plan_t p, int pass, int &Md, int &Nd, int &Kd, int &slot_a, int &slot_b)
 {
-    // the tiles of a sample act as extra samples: S * nt^2 (fprop, accGrad) or S * nt2^2 (bprop)
-    const int St = p->d.S * p->nt * p->nt, St2 = p->d.S * p->nt2 * p->nt2;
+    // the tiles of a sample act as extra samples: S * nty * ntx (fprop, accGrad) or S * nty2 * ntx2 (bprop)
+    const int St = p->d.S * p->nty * p->ntx, St2 = p->d.S * p->nty2 * p->ntx2;
     switch (pass) {
         case FFTCONV_FPROP: Md = St; Nd = p->d.fo; Kd = p->d.f; slot_a = FFTCONV_SPEC_X; slot_b = FFTCONV_SPEC_W; break;
         case FFTCONV_BPROP: Md = St2; Nd = p->d.f; Kd = p->d.fo; slot_a = tiled(p) ? FFTCONV_SPEC_G2 : FFTCONV_SPEC_G; slot_b = FFTCONV_SPEC_W; break;
@@ -321,32 +322,31 @@ int launch_contract(fftconv_plan_t p, int pass, void *ws, hipStream_t stream)
 int launch_inverse(fftconv_plan_t p, int pass, float *dst, void *ws, hipStream_t stream, int accumulate)
 {
     long M;
-    int crop;
     InvArgs a{};
+    const fftconv_desc2d &d = p->d;
     switch (pass) {
-        case FFTCONV_FPROP:   // tiles of y: output rows / columns [0, L) of each transform
-            M = p->maps_g; crop = tiled(p) ? p->L : p->no;
-            a.t = Tiling{p->no, p->no, p->d.fo, p->nt, p->nt * p->nt, p->L, 0};
-            a.c0 = 0;
+        case FFTCONV_FPROP:   // tiles of y: output rows [0, Ly) and columns [0, Lx) of each transform
+            M = p->maps_g; a.crop_y = tiled(p) ? p->Ly : p->noh; a.crop_x = tiled(p) ? p->Lx : p->now;
+            a.t = Tiling{p->noh, p->now, d.fo, p->ntx, p->nty * p->ntx, p->Ly, p->Lx, 0, 0};
             break;
-        case FFTCONV_BPROP:   // tiles of dx: rows / columns [k-1, N), the part of the circular result free of wrap-around
-            M = tiled(p) ? (long)p->d.S * p->nt2 * p->nt2 * p->d.f : p->maps_x; crop = tiled(p) ? p->L : p->d.n;
-            a.t = Tiling{p->d.n, p->d.n, p->d.f, p->nt2, p->nt2 * p->nt2, p->L, 0};
-            a.c0 = p->d.k - 1;
+        case FFTCONV_BPROP:   // tiles of dx: rows [kh-1, N), columns [kw-1, N), the part of the circular result free of wrap-around
+            M = tiled(p) ? (long)d.S * p->nty2 * p->ntx2 * d.f : p->maps_x;
+            a.crop_y = tiled(p) ? p->Ly : d.nh; a.crop_x = tiled(p) ? p->Lx : d.nw;
+            a.t = Tiling{d.nh, d.nw, d.f, p->ntx2, p->nty2 * p->ntx2, p->Ly, p->Lx, 0, 0};
+            a.c0_y = d.kh - 1; a.c0_x = d.kw - 1;
             break;
         default:              // dw is never tiled
-            M = p->maps_w; crop = p->d.k;
+            M = p->maps_w; a.crop_y = d.kh; a.crop_x = d.kw;
             break;
     }
     const bool use_tiles = tiled(p) && pass != FFTCONV_ACCGRAD;
-    const FftEntry *e = find_fft(p->N, use_tiles ? p->N : crop);
+    const FftEntry *e = find_fft(p->N, use_tiles ? p->N : (a.crop_y > a.crop_x ? a.crop_y : a.crop_x));
     if (!e || (use_tiles && !e->inv_tiled)) return FFTCONV_EUNSUPPORTED;
     InvKernel kernel = use_tiles ? e->inv_tiled : (accumulate ? e->inv_acc : e->inv);
     if (int rc = allow_lds(kernel, e->lds_bytes)) return rc;
     a.spec = slot_ptr(p, ws, result_slot(p, pass));
     a.dst = dst;
     a.M = (int)M;
-    a.crop = crop;
     a.scale = 1.0f / ((float)p->N * (float)p->N);
     const unsigned blocks = (unsigned)((M + e->T - 1) / e->T);
     StageTimer timer(p, FFTCONV_STAGE_IFFT_Y + pass, stream);
@@ -381,26 +381,40 @@ extern "C" {
 int fftconv_plan(fftconv_plan_t *out, const fftconv_desc *d)
 {
     if (!out || !d) return FFTCONV_EINVAL;
-    if (d->S < 1 || d->f < 1 || d->fo < 1 || d->n < 1 || d->k < 1 || d->k > d->n) return FFTCONV_EINVAL;
+    const fftconv_desc2d d2{d->S, d->f, d->fo, d->n, d->n, d->k, d->k, d->flags};
+    return fftconv_plan2d(out, &d2);
+}
+
+int fftconv_plan2d(fftconv_plan_t *out, const fftconv_desc2d *d)
+{
+    if (!out || !d) return FFTCONV_EINVAL;
+    if (d->S < 1 || d->f < 1 || d->fo < 1 || d->nh < 1 || d->nw < 1 || d->kh < 1 || d->kw < 1 || d->kh > d->nh ||
+        d->kw > d->nw)
+        return FFTCONV_EINVAL;
     if ((d->flags & ~(unsigned)FFTCONV_RECOMPUTE) != 0) return FFTCONV_EUNSUPPORTED;
-    const int no = d->n - d->k + 1;
-    int N = fft_size_for(d->n), L = 0, nt = 1, nt2 = 1;
+    const int noh = d->nh - d->kh + 1, now = d->nw - d->kw + 1;
+    int N = fft_size_for(d->nh > d->nw ? d->nh : d->nw), Ly = 0, Lx = 0, nty = 1, ntx = 1, nty2 = 1, ntx2 = 1;
     if (N < 0) {
-        // Larger than the largest transform: cut into tiles of L = N - k + 1 outputs per side
+        // Larger than the largest transform: cut into tiles of (N - kh + 1) x (N - kw + 1) outputs
         // (overlap-save).  Pick the tile transform that needs the fewest transformed points over
         // the tiles of y and of dx together.
         static const int sizes[] = {16, 24, 32, 48, 64};
         double best = -1.0;
         for (int cand : sizes) {
-            const int l = cand - d->k + 1;
-            if (l < 1) continue;
-            const long a = (no + l - 1) / l, b = (d->n + l - 1) / l;
-            const double cost = (double)(a * a + b * b) * cand * cand;
-            if (best < 0.0 || cost < best) { best = cost; N = cand; L = l; nt = (int)a; nt2 = (int)b; }
+            const int ly = cand - d->kh + 1, lx = cand - d->kw + 1;
+            if (ly < 1 || lx < 1) continue;
+            const long ay = (noh + ly - 1) / ly, ax = (now + lx - 1) / lx;
+            const long by = (d->nh + ly - 1) / ly, bx = (d->nw + lx - 1) / lx;
+            const double cost = (double)(ay * ax + by * bx) * cand * cand;
+            if (best < 0.0 || cost < best) {
+                best = cost; N = cand; Ly = ly; Lx = lx;
+                nty = (int)ay; ntx = (int)ax; nty2 = (int)by; ntx2 = (int)bx;
+            }
         }
-        if (N < 0) return FFTCONV_EUNSUPPORTED;   // k > 64
+        if (N < 0) return FFTCONV_EUNSUPPORTED;   // a kernel side above 64
     }
-    const long T = (long)nt * nt, T2 = (long)nt2 * nt2;
+    const long T = (long)nty * ntx, T2 = (long)nty2 * ntx2;
+    const int L = Ly;   // non-zero iff tiled
     const bool lean = (d->flags & FFTCONV_RECOMPUTE) != 0;
     // transforms per slot; in the three-slot workspace the x and g slots also take the results
     // dX and Y and the windows of bprop, whose tile counts can differ
@@ -414,12 +428,16 @@ int fftconv_plan(fftconv_plan_t *out, const fftconv_desc *d)
     fftconv_plan_s *p = new (std::nothrow) fftconv_plan_s();
     if (!p) return FFTCONV_EINVAL;
     p->d = *d;
-    p->no = no;
+    p->noh = noh;
+    p->now = now;
     p->N = N;
     p->B = N * N / 2 + 2;
-    p->L = L;
-    p->nt = nt;
-    p->nt2 = nt2;
+    p->Ly = Ly;
+    p->Lx = Lx;
+    p->nty = nty;
+    p->ntx = ntx;
+    p->nty2 = nty2;
+    p->ntx2 = ntx2;
     p->maps_x = (long)d->S * d->f * T;
     p->maps_w = maps_w;
     p->maps_g = (long)d->S * d->fo * T;
@@ -588,16 +606,16 @@ size_t fftconv_paper_ram_bytes(int S, int n, int f, int fo)
 double fftconv_contraction_flops(fftconv_plan_t p)
 {
     if (!p) return 0.0;
-    const double tiles = (2.0 * p->nt * p->nt + (double)p->nt2 * p->nt2) / 3.0;   // mean over the three passes
+    const double tiles = (2.0 * p->nty * p->ntx + (double)p->nty2 * p->ntx2) / 3.0;   // mean over the three passes
     return 6.0 * p->d.S * p->d.f * p->d.fo * p->B * tiles;
 }
 
-int fftconv_tiling(fftconv_plan_t p, int *tile, int *tiles_y, int *tiles_dx)
+int fftconv_tiling(fftconv_plan_t p, int tile[2], int tiles_y[2], int tiles_dx[2])
 {
     if (!p || !tile || !tiles_y || !tiles_dx) return FFTCONV_EINVAL;
-    *tile = p->L;
-    *tiles_y = p->nt;
-    *tiles_dx = p->nt2;
+    tile[0] = p->Ly; tile[1] = p->Lx;
+    tiles_y[0] = p->nty; tiles_y[1] = p->ntx;
+    tiles_dx[0] = p->nty2; tiles_dx[1] = p->ntx2;
     return FFTCONV_OK;
 }
 

@@ -25,7 +25,7 @@ STAGE_NAMES = ("fft_x", "fft_w", "fft_g", "cgemm_fprop", "cgemm_bprop", "cgemm_a
                "ifft_y", "ifft_dx", "ifft_dw")
 
 EXPORTS = (
-    "fftconv_plan", "fftconv_plan_destroy", "fftconv_fft_size", "fftconv_num_bins",
+    "fftconv_plan", "fftconv_plan2d", "fftconv_plan_destroy", "fftconv_fft_size", "fftconv_num_bins",
     "fftconv_workspace_bytes", "fftconv_slot_offset", "fftconv_slot_maps", "fftconv_invalidate",
     "fftconv_valid_slots", "fftconv_fprop", "fftconv_bprop", "fftconv_accgrad",
     "fftconv_forward_transform", "fftconv_contract", "fftconv_inverse_transform",
@@ -37,6 +37,12 @@ EXPORTS = (
 class Desc(ctypes.Structure):
     _fields_ = [("S", ctypes.c_int), ("f", ctypes.c_int), ("fo", ctypes.c_int),
                 ("n", ctypes.c_int), ("k", ctypes.c_int), ("flags", ctypes.c_uint)]
+
+
+class Desc2d(ctypes.Structure):
+    _fields_ = [("S", ctypes.c_int), ("f", ctypes.c_int), ("fo", ctypes.c_int),
+                ("nh", ctypes.c_int), ("nw", ctypes.c_int), ("kh", ctypes.c_int), ("kw", ctypes.c_int),
+                ("flags", ctypes.c_uint)]
 
 
 class FftconvError(RuntimeError):
@@ -53,6 +59,7 @@ def _load() -> ctypes.CDLL:
     vp, ip, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
     sig = {
         "fftconv_plan": (ip, [ctypes.POINTER(vp), ctypes.POINTER(Desc)]),
+        "fftconv_plan2d": (ip, [ctypes.POINTER(vp), ctypes.POINTER(Desc2d)]),
         "fftconv_plan_destroy": (ip, [vp]),
         "fftconv_fft_size": (ip, [vp]),
         "fftconv_num_bins": (ip, [vp]),
@@ -72,7 +79,7 @@ def _load() -> ctypes.CDLL:
         "fftconv_strerror": (ctypes.c_char_p, [ip]),
         "fftconv_paper_ram_bytes": (sz, [ip, ip, ip, ip]),
         "fftconv_contraction_flops": (ctypes.c_double, [vp]),
-        "fftconv_tiling": (ip, [vp, ctypes.POINTER(ip), ctypes.POINTER(ip), ctypes.POINTER(ip)]),
+        "fftconv_tiling": (ip, [vp, ctypes.POINTER(ip * 2), ctypes.POINTER(ip * 2), ctypes.POINTER(ip * 2)]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -114,12 +121,23 @@ class Plan:
     contiguous fp32 device tensors of the shapes in include/fftconv.h.
     """
 
-    def __init__(self, S: int, f: int, fo: int, n: int, k: int, flags: int = 0):
+    def __init__(self, S: int, f: int, fo: int, n, k, flags: int = 0):
+        """n, k: ints (square maps / kernels, the paper's notation) or (height, width) pairs."""
         self._h = ctypes.c_void_p()
-        d = Desc(S, f, fo, n, k, flags)
-        _check(_lib.fftconv_plan(ctypes.byref(self._h), ctypes.byref(d)), "fftconv_plan")
+        if isinstance(n, (tuple, list)) or isinstance(k, (tuple, list)):
+            nh, nw = n if isinstance(n, (tuple, list)) else (n, n)
+            kh, kw = k if isinstance(k, (tuple, list)) else (k, k)
+            d = Desc2d(S, f, fo, nh, nw, kh, kw, flags)
+            _check(_lib.fftconv_plan2d(ctypes.byref(self._h), ctypes.byref(d)), "fftconv_plan2d")
+        else:
+            nh = nw = n
+            kh = kw = k
+            d = Desc(S, f, fo, n, k, flags)
+            _check(_lib.fftconv_plan(ctypes.byref(self._h), ctypes.byref(d)), "fftconv_plan")
         self.S, self.f, self.fo, self.n, self.k = S, f, fo, n, k
-        self.no = n - k + 1
+        self.nh, self.nw, self.kh, self.kw = nh, nw, kh, kw
+        self.noh, self.now = nh - kh + 1, nw - kw + 1
+        self.no = self.noh
         self.ws = None
 
     def close(self):
@@ -148,10 +166,10 @@ class Plan:
 
     @property
     def tiling(self):
-        """(L, tiles per dimension of y, tiles per dimension of dx); L = 0 if the layer is not tiled."""
-        a, b, c = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+        """((Ly, Lx), tiles of y per axis, tiles of dx per axis); (0, 0) first if the layer is not tiled."""
+        a, b, c = (ctypes.c_int * 2)(), (ctypes.c_int * 2)(), (ctypes.c_int * 2)()
         _check(_lib.fftconv_tiling(self._h, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)), "fftconv_tiling")
-        return a.value, b.value, c.value
+        return tuple(a), tuple(b), tuple(c)
 
     def slot_offset(self, slot: int) -> int:
         return int(_lib.fftconv_slot_offset(self._h, slot))
@@ -187,14 +205,14 @@ class Plan:
     # -- passes ------------------------------------------------------------
     def fprop(self, x, w, y=None):
         if y is None:
-            y = torch.empty((self.S, self.fo, self.no, self.no), dtype=torch.float32, device=x.device)
+            y = torch.empty((self.S, self.fo, self.noh, self.now), dtype=torch.float32, device=x.device)
         _check(_lib.fftconv_fprop(self._h, _ptr(x, "x"), _ptr(w, "w"), _ptr(y, "y"), self._ws_ptr(), _stream()),
                "fftconv_fprop")
         return y
 
     def bprop(self, g, w, dx=None):
         if dx is None:
-            dx = torch.empty((self.S, self.f, self.n, self.n), dtype=torch.float32, device=g.device)
+            dx = torch.empty((self.S, self.f, self.nh, self.nw), dtype=torch.float32, device=g.device)
         _check(_lib.fftconv_bprop(self._h, _ptr(g, "g"), _ptr(w, "w"), _ptr(dx, "dx"), self._ws_ptr(), _stream()),
                "fftconv_bprop")
         return dx
@@ -203,7 +221,7 @@ class Plan:
         if dw is None:
             if accumulate:
                 raise ValueError("accumulate needs an existing dw")
-            dw = torch.empty((self.fo, self.f, self.k, self.k), dtype=torch.float32, device=g.device)
+            dw = torch.empty((self.fo, self.f, self.kh, self.kw), dtype=torch.float32, device=g.device)
         _check(_lib.fftconv_accgrad(self._h, _ptr(g, "g"), _ptr(x, "x"), _ptr(dw, "dw"), self._ws_ptr(), _stream(),
                                     1 if accumulate else 0), "fftconv_accgrad")
         return dw

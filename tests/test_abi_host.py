@@ -21,7 +21,7 @@ def fc(fftconv_lib_path):
 def declared_functions():
     text = open(os.path.join(ROOT, "include", "fftconv.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(fftconv_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(fftconv_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_header_and_binding_agree_and_every_symbol_is_exported(fc, fftconv_lib_path):
@@ -111,7 +111,8 @@ def test_large_maps_are_tiled(fc, n, k):
     transformed points; slots hold one transform per tile; an extra slot for bprop's windows."""
     S, f, fo = 2, 3, 4
     p = fc.Plan(S, f, fo, n, k)
-    N, (L, nt, nt2) = p.fft_size, p.tiling
+    N, ((L, Lx), (nt, ntx), (nt2, ntx2)) = p.fft_size, p.tiling
+    assert (L, nt, nt2) == (Lx, ntx, ntx2)
     no = n - k + 1
     assert N in (16, 24, 32, 48, 64) and L == N - k + 1 >= 1
     assert nt == ceil_div(no, L) and nt2 == ceil_div(n, L)
@@ -135,9 +136,32 @@ def test_large_maps_are_tiled(fc, n, k):
     assert lean.slot_offset(fc.SPEC_G2) == lean.slot_offset(fc.SPEC_G) == sizes[0] + sizes[1]
 
 
+def test_rectangular_plans(fc):
+    """Height and width of maps and kernels per axis; the transform stays square and covers the longer side."""
+    p = fc.Plan(2, 3, 4, (20, 45), (3, 7))
+    assert p.fft_size == 48 and p.num_bins == 48 * 48 // 2 + 2 and p.tiling == ((0, 0), (1, 1), (1, 1))
+    assert p.slot_maps(fc.SPEC_X) == 6 and p.slot_maps(fc.SPEC_G) == 8 and p.slot_maps(fc.SPEC_W) == 12
+    sq, rect = fc.Plan(2, 3, 4, 20, 3), fc.Plan(2, 3, 4, (20, 20), (3, 3))
+    assert sq.fft_size == rect.fft_size and sq.workspace_bytes == rect.workspace_bytes
+    # tiled, different block sizes and counts per axis
+    p = fc.Plan(2, 3, 4, (70, 200), (3, 9))
+    N, ((Ly, Lx), (ty, tx), (ty2, tx2)) = p.fft_size, p.tiling
+    assert (Ly, Lx) == (N - 2, N - 8)
+    assert (ty, tx) == (ceil_div(68, Ly), ceil_div(192, Lx)) and (ty2, tx2) == (ceil_div(70, Ly), ceil_div(200, Lx))
+    assert p.slot_maps(fc.SPEC_X) == 2 * 3 * ty * tx and p.slot_maps(fc.SPEC_G2) == 2 * 4 * ty2 * tx2
+    for bad in (((8, 8), (9, 3)), ((8, 8), (3, 9)), ((0, 8), (1, 1)), ((8, 8), (0, 1))):
+        with pytest.raises(fc.FftconvError) as ei:
+            fc.Plan(1, 1, 1, *bad)
+        assert ei.value.status == 1
+    with pytest.raises(fc.FftconvError) as ei:
+        fc.Plan(1, 1, 1, (100, 100), (3, 65))
+    assert ei.value.status == 2
+    assert fc._lib.fftconv_plan2d(None, None) == 1
+
+
 def test_small_maps_are_not_tiled(fc):
     p = fc.Plan(2, 3, 4, 64, 3)
-    assert p.tiling == (0, 1, 1) and p.slot_maps(fc.SPEC_G2) == -1 and p.slot_offset(fc.SPEC_G2) == 2 ** 64 - 1
+    assert p.tiling == ((0, 0), (1, 1), (1, 1)) and p.slot_maps(fc.SPEC_G2) == -1 and p.slot_offset(fc.SPEC_G2) == 2 ** 64 - 1
     assert fc._lib.fftconv_forward_transform(p._h, fc.SPEC_G2, ctypes.c_void_p(256), ctypes.c_void_p(256), None) == 1
     assert fc._lib.fftconv_tiling(p._h, None, None, None) == 1
 

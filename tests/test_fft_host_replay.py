@@ -23,18 +23,20 @@ FP = ctypes.POINTER(ctypes.c_float)
 
 
 def forward(lib, src, N):
-    M, ext, _ = src.shape
+    M, ext_y, ext_x = src.shape
     B = N * N // 2 + 2
     spec = np.full((B, M, 2), np.nan, np.float32)
-    assert lib.replay_fft2d_r2c(N, src.ctypes.data_as(FP), spec.ctypes.data_as(FP), M, ext) == 0
+    assert lib.replay_fft2d_r2c(N, src.ctypes.data_as(FP), spec.ctypes.data_as(FP), M, ext_y, ext_x) == 0
     return spec[..., 0].astype(np.float64) + 1j * spec[..., 1]
 
 
 def inverse(lib, spec, N, crop, into=None):
+    """crop: an int (square window) or (rows, columns)."""
+    cy, cx = crop if isinstance(crop, tuple) else (crop, crop)
     s = np.ascontiguousarray(np.stack([spec.real, spec.imag], -1).astype(np.float32))
     M = spec.shape[1]
-    dst = np.full((M, crop, crop), np.nan, np.float32) if into is None else into.copy()
-    assert lib.replay_ifft2d_c2r_crop(N, s.ctypes.data_as(FP), dst.ctypes.data_as(FP), M, crop, 0 if into is None else 1) == 0
+    dst = np.full((M, cy, cx), np.nan, np.float32) if into is None else into.copy()
+    assert lib.replay_ifft2d_c2r_crop(N, s.ctypes.data_as(FP), dst.ctypes.data_as(FP), M, cy, cx, 0 if into is None else 1) == 0
     return dst
 
 
@@ -108,15 +110,18 @@ def test_impulse_constant_and_round_trip(replay, N):
 
 def tile_windows(img, N, tiles_x, tiles, step, org, ext):
     """[S, C, H, W] images -> zero-filled windows [S * tiles * C, N, N] in transform order
-    m = (s * tiles + t) * C + c, window origin (ty * step + org, tx * step + org), extent ext."""
+    m = (s * tiles + t) * C + c, window origin (ty * step_y + org_y, tx * step_x + org_x), extent
+    ext_y x ext_x (step, org, ext: ints or (y, x) pairs)."""
+    pair = lambda v: v if isinstance(v, tuple) else (v, v)
+    (sy, sx), (gy, gx), (ey, ex) = pair(step), pair(org), pair(ext)
     S, C, H, W = img.shape
     out = np.zeros((S * tiles * C, N, N))
     for s in range(S):
         for t in range(tiles):
-            oy, ox = (t // tiles_x) * step + org, (t % tiles_x) * step + org
+            oy, ox = (t // tiles_x) * sy + gy, (t % tiles_x) * sx + gx
             for c in range(C):
-                for y in range(ext):
-                    for x in range(ext):
+                for y in range(ey):
+                    for x in range(ex):
                         if 0 <= oy + y < H and 0 <= ox + x < W:
                             out[(s * tiles + t) * C + c, y, x] = img[s, c, oy + y, ox + x]
     return out
@@ -137,8 +142,8 @@ def test_tiled_forward_windows(replay, N, H, k):
         img = rng.uniform(-1, 1, (S, C, size, size)).astype(np.float32)
         M = S * tx * tx * C
         spec = np.full((B, M, 2), np.nan, np.float32)
-        rc = replay.replay_fft2d_r2c_tiled(N, img.ctypes.data_as(FP), spec.ctypes.data_as(FP), M, ext, size, size, C,
-                                           tx, tx * tx, L, org)
+        rc = replay.replay_fft2d_r2c_tiled(N, img.ctypes.data_as(FP), spec.ctypes.data_as(FP), M, ext, ext, size, size, C,
+                                           tx, tx * tx, L, L, org, org)
         assert rc == 0
         got = spec[..., 0].astype(np.float64) + 1j * spec[..., 1]
         ref = reference_spectrum(tile_windows(img, N, tx, tx * tx, L, org, ext), N)
@@ -161,7 +166,8 @@ def test_tiled_inverse_scatters_each_tile_once(replay, N, H, k, c0):
     guard = np.full(64, np.nan, np.float32)
     buf = np.concatenate([guard, dst.ravel(), guard])
     view = buf[64:64 + dst.size]
-    rc = replay.replay_ifft2d_c2r_tiled(N, sp.ctypes.data_as(FP), view.ctypes.data_as(FP), M, L, c0, H, H, C, tx, tx * tx, L)
+    rc = replay.replay_ifft2d_c2r_tiled(N, sp.ctypes.data_as(FP), view.ctypes.data_as(FP), M, L, L, c0, c0, H, H, C,
+                                        tx, tx * tx, L, L)
     assert rc == 0
     assert np.all(np.isnan(buf[:64])) and np.all(np.isnan(buf[-64:]))
     got = view.reshape(S, C, H, H)
@@ -173,3 +179,63 @@ def test_tiled_inverse_scatters_each_tile_once(replay, N, H, k, c0):
                 h, w = min(L, H - oy), min(L, H - ox)
                 ref = patches[(s * tx * tx + t) * C + c, c0:c0 + h, c0:c0 + w]
                 assert np.abs(got[s, c, oy:oy + h, ox:ox + w] - ref).max() < 3e-6
+
+
+# ---------------------------------------------------------------- rectangular extents
+
+@pytest.mark.parametrize("N", [8, 12, 16, 24, 32, 48, 64])
+def test_rectangular_maps_forward_and_inverse(replay, N):
+    """Maps and windows with different height and width inside a square transform."""
+    rng = np.random.default_rng(300 + N)
+    T = replay.replay_maps_per_block(N)
+    for ey, ex in ((1, N), (N, 1), (N // 2, N - 1), (N - 1, N // 4 + 1), (3, 2), (N // 4, N // 2 + 1)):
+        M = T + 1
+        src = rng.uniform(-1, 1, (M, ey, ex)).astype(np.float32)
+        pad = np.zeros((M, N, N)); pad[:, :ey, :ex] = src
+        ky, kx = stored_bins(N)
+        ref = np.fft.fft2(pad)[:, ky, kx].T
+        got = forward(replay, src, N)
+        assert np.abs(got - ref).max() <= 3e-6 * max(np.abs(ref).max(), 1), (N, ey, ex)
+        full = rng.uniform(-1, 1, (M, N, N))
+        back = inverse(replay, reference_spectrum(full, N), N, (ey, ex))
+        assert back.shape == (M, ey, ex) and np.abs(back - full[:, :ey, :ex]).max() < 3e-6, (N, ey, ex)
+
+
+def test_tiled_rectangular_windows_and_scatter(replay):
+    """Tiles of a 70 x 41 image with a 3 x 6 kernel at N = 32: different steps, origins,
+    extents and stored windows per axis."""
+    rng = np.random.default_rng(77)
+    N, H, W, kh, kw, S, C = 32, 70, 41, 3, 6, 2, 3
+    Ly, Lx = N - kh + 1, N - kw + 1
+    noh, now = H - kh + 1, W - kw + 1
+    B = N * N // 2 + 2
+    cases = [("x windows", (H, W), (-(-noh // Ly), -(-now // Lx)), (0, 0), (N, N)),
+             ("g blocks", (noh, now), (-(-noh // Ly), -(-now // Lx)), (0, 0), (Ly, Lx)),
+             ("g windows", (noh, now), (-(-H // Ly), -(-W // Lx)), (-(kh - 1), -(kw - 1)), (N, N))]
+    for what, (h, w), (ty, tx), org, ext in cases:
+        img = rng.uniform(-1, 1, (S, C, h, w)).astype(np.float32)
+        M = S * ty * tx * C
+        spec = np.full((B, M, 2), np.nan, np.float32)
+        rc = replay.replay_fft2d_r2c_tiled(N, img.ctypes.data_as(FP), spec.ctypes.data_as(FP), M, ext[0], ext[1], h, w, C,
+                                           tx, ty * tx, Ly, Lx, org[0], org[1])
+        assert rc == 0
+        got = spec[..., 0].astype(np.float64) + 1j * spec[..., 1]
+        ref = reference_spectrum(tile_windows(img, N, tx, ty * tx, (Ly, Lx), org, ext), N)
+        assert np.abs(got - ref).max() <= 3e-6 * max(np.abs(ref).max(), 1), what
+    # scatter of dx tiles: rows [kh-1, N), columns [kw-1, N) of each transform
+    ty, tx = -(-H // Ly), -(-W // Lx)
+    M = S * ty * tx * C
+    patches = rng.uniform(-1, 1, (M, N, N))
+    spec = reference_spectrum(patches, N)
+    sp = np.ascontiguousarray(np.stack([spec.real, spec.imag], -1).astype(np.float32))
+    dst = np.full((S, C, H, W), np.nan, np.float32)
+    rc = replay.replay_ifft2d_c2r_tiled(N, sp.ctypes.data_as(FP), dst.ctypes.data_as(FP), M, Ly, Lx, kh - 1, kw - 1, H, W, C,
+                                        tx, ty * tx, Ly, Lx)
+    assert rc == 0 and not np.isnan(dst).any()
+    for s in range(S):
+        for t in range(ty * tx):
+            oy, ox = (t // tx) * Ly, (t % tx) * Lx
+            for c in range(C):
+                h, w = min(Ly, H - oy), min(Lx, W - ox)
+                ref = patches[(s * ty * tx + t) * C + c, kh - 1:kh - 1 + h, kw - 1:kw - 1 + w]
+                assert np.abs(dst[s, c, oy:oy + h, ox:ox + w] - ref).max() < 3e-6

@@ -50,7 +50,7 @@ def run_three(fc, layer, x, w, g):
     dx = plan.bprop(gd, wd)
     dw = plan.accgrad(gd, xd)
     torch.cuda.synchronize()
-    expect = fc.SPEC_X | fc.SPEC_W | fc.SPEC_G | (fc.SPEC_G2 if plan.tiling[0] else 0)
+    expect = fc.SPEC_X | fc.SPEC_W | fc.SPEC_G | (fc.SPEC_G2 if plan.tiling[0][0] else 0)
     assert plan.valid_slots() == expect
     return plan, y.cpu().numpy(), dx.cpu().numpy(), dw.cpu().numpy()
 
@@ -210,7 +210,7 @@ def test_full_parity_tiled_layers(fc, layer):
     print(f"\ncase {layer}", flush=True)
     x, w, g = wl.make_inputs(layer)
     plan = fc.Plan(layer.S, layer.f, layer.fo, layer.n, layer.k)
-    L, nt, nt2 = plan.tiling
+    (L, _), (nt, _), (nt2, _) = plan.tiling
     print(f"N={plan.fft_size} L={L} tiles {nt}x{nt} (y), {nt2}x{nt2} (dx)", flush=True)
     assert L > 0
     xd, wd, gd = dev(x), dev(w), dev(g)
@@ -250,6 +250,64 @@ def test_sampled_parity_tiled_full_size(fc):
     print(f"\ncase {layer}", flush=True)
     sampled_check_tiled = sampled_check
     sampled_check_tiled(fc, layer, (24, 24, 96))
+
+
+def rect_inputs(seed, S, f, fo, nh, nw, kh, kw):
+    rng = np.random.Generator(np.random.Philox(key=seed))
+    x = rng.uniform(-1, 1, (S, f, nh, nw)).astype(np.float32)
+    w = (rng.standard_normal((fo, f, kh, kw)) * 0.1).astype(np.float32)
+    g = rng.standard_normal((S, fo, nh - kh + 1, nw - kw + 1)).astype(np.float32)
+    return x, w, g
+
+
+RECT_LAYERS = [
+    (2, 3, 4, 20, 31, 3, 5),      # N = 32 from the width
+    (3, 2, 2, 45, 12, 7, 2),      # tall maps, N = 48
+    (2, 3, 2, 16, 64, 16, 1),     # kh = nh: one output row; kw = 1
+    (5, 3, 4, 7, 8, 2, 8),        # one output column, N = 8
+    (2, 2, 3, 64, 9, 5, 3),       # N = 64, narrow
+    (1, 2, 2, 1, 24, 1, 4),       # a single row: 1-D correlation
+    (2, 3, 2, 70, 41, 3, 6),      # tiled along both axes with different blocks
+    (1, 2, 3, 30, 150, 4, 11),    # tiled because of the width only
+    (2, 2, 2, 200, 10, 9, 2),     # tiled because of the height only
+]
+
+
+@pytest.mark.parametrize("dims", RECT_LAYERS, ids=lambda d: "x".join(map(str, d)))
+def test_full_parity_rectangular(fc, dims):
+    """Maps and kernels with different height and width (Sec. 2.1 writes square ones only to keep the
+    notation short), through fftconv_plan2d, against the oracle."""
+    S, f, fo, nh, nw, kh, kw = dims
+    print(f"\ncase rect {dims}", flush=True)
+    x, w, g = rect_inputs(500 + nh + nw, *dims)
+    xd, wd, gd = dev(x), dev(w), dev(g)
+    for flags in (0, fc.RECOMPUTE):
+        plan = fc.Plan(S, f, fo, (nh, nw), (kh, kw), flags=flags)
+        print(f"N={plan.fft_size} tiling {plan.tiling} flags {flags}", flush=True)
+        dw = plan.accgrad(gd, xd)
+        y = plan.fprop(xd, wd)
+        dx = plan.bprop(gd, wd)
+        torch.cuda.synchronize()
+        assert y.shape == g.shape and dx.shape == x.shape and dw.shape == w.shape
+        check(y.cpu().numpy(), direct.fprop(x, w), f"rect fprop flags={flags}")
+        check(dx.cpu().numpy(), direct.bprop(g, w, (nh, nw)), f"rect bprop flags={flags}")
+        check(dw.cpu().numpy(), direct.accgrad(g, x, (kh, kw)), f"rect accgrad flags={flags}")
+
+
+def test_transposed_layer_gives_transposed_results(fc):
+    """Swapping height and width of every tensor swaps them in every result (bitwise is not
+    expected: the two axes are transformed in different phases)."""
+    S, f, fo, nh, nw, kh, kw = 2, 3, 2, 18, 40, 3, 6
+    x, w, g = rect_inputs(77, S, f, fo, nh, nw, kh, kw)
+    a = fc.Plan(S, f, fo, (nh, nw), (kh, kw))
+    b = fc.Plan(S, f, fo, (nw, nh), (kw, kh))
+    tr = lambda t: np.ascontiguousarray(np.swapaxes(t, 2, 3))
+    ya = a.fprop(dev(x), dev(w)).cpu().numpy()
+    yb = b.fprop(dev(tr(x)), dev(tr(w))).cpu().numpy()
+    check(tr(yb), ya.astype(np.float64), "transposed fprop")
+    da = a.accgrad(dev(g), dev(x)).cpu().numpy()
+    db = b.accgrad(dev(tr(g)), dev(tr(x))).cpu().numpy()
+    check(tr(db), da.astype(np.float64), "transposed accgrad")
 
 
 EDGE_LAYERS = [
