@@ -17,8 +17,10 @@
 //     re = k1 - k3,          im = k1 + k2
 // Each is accumulated over K by v_mfma_f32_32x32x2_f32 in its own fp32 tile, so a
 // bin costs 6*M*N*K matrix-core flops instead of the 8*M*N*K of the four-product
-// form; the operand sums are three VALU adds per fragment, and re/im are formed
-// once in the epilogue.  Conjugation is applied while a tile is written to LDS.
+// form; the operand sums are three VALU operations per fragment, and re/im are
+// formed once in the epilogue.  A conjugated operand costs nothing: its sign goes
+// into those sums (conj b: bi - br -> -bi - br, br + bi -> br - bi; conj a:
+// ar + ai -> ar - ai and k3 enters the real part with the opposite sign).
 //
 // Data flow.  A workgroup of WM x WN waves owns an MT x NT tile of one bin and
 // walks K in chunks of kKT.  Operand chunks go global -> registers -> LDS, laid
@@ -28,6 +30,13 @@
 // (its global loads were issued one chunk earlier) and chunk c+2's loads are
 // issued; one barrier per chunk.  Fragments are double-buffered in registers so
 // the LDS latency of step ks+1 hides behind the MFMAs of step ks.
+//
+// Vector-ALU instructions and MFMAs of the waves on a SIMD do not overlap (counters:
+// no co-execution cycles; a chunk's 24 MFMAs take 1536 cycles, every other vector
+// instruction four more), so the K loop carries as few of them as possible.  A tile
+// that lies fully inside the matrices with K a multiple of the chunk takes the
+// full-tile path: no masks, and every load address is a uniform (scalar) base plus one
+// per-thread offset that never changes.  Edge tiles and K tails take the general path.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -45,6 +54,7 @@ struct GemmArgs {
     int bins;
     int tiles_m, tiles_n;
     int xcd_remap;   // 1: renumber workgroups so that each XCD gets contiguous work
+    int full_tiles_ok;   // 1: both operand matrices of a bin are below 2 GB, so 32-bit byte offsets suffice
 };
 
 constexpr int kXcds = 8;   // accelerator complex dies on MI355X; workgroups are dealt to them round-robin
@@ -56,7 +66,7 @@ constexpr int kKT = 16;    // complex K elements per chunk (one 128-byte line of
 // LDS layout Ps[kk * SP + r].  SP is odd: the 16 lanes that an LDS store of 8-byte
 // elements serves together then hit 16 different bank pairs whether they run along r
 // (stride 1) or along kk (stride SP).
-template <int ROWS, int THREADS, bool KIN, bool CONJ>
+template <int ROWS, int THREADS, bool KIN>
 struct TileLoader {
     static constexpr int ELEMS = ROWS * kKT;
     static constexpr int PER_THREAD = (ELEMS + THREADS - 1) / THREADS;
@@ -74,7 +84,7 @@ struct TileLoader {
 
     // Issues the loads only.  Nothing here consumes the loaded values, so the loads stay
     // in flight while the caller goes on issuing MFMAs; masking of out-of-range elements
-    // and conjugation happen in store(), when the values are needed.
+    // happens in store(), when the values are needed.
     __device__ __forceinline__ void load(const cf *base, int ld, int r0, int rmax, int k0, int kmax, int tid)
     {
         static_assert(PER_THREAD <= 32, "okmask holds one bit per element");
@@ -100,9 +110,59 @@ struct TileLoader {
             coords(tid, p, r, kk);
             cf v = regs[p];
             if (!((okmask >> p) & 1u)) v = mk(0.0f, 0.0f);
-            if (CONJ) v.y = -v.y;
             if (ELEMS % THREADS == 0 || p * THREADS + tid < ELEMS) Ps[kk * SP + r] = v;
         }
+    }
+};
+
+// The same for a tile that lies fully inside the matrix, K a multiple of kKT.  Element p of a
+// thread is p * PSTEP rows (KIN) or K indices (not KIN) after its element 0, so its address is
+// a uniform part (tile origin + chunk + p * PSTEP * ld) plus one per-thread offset that never
+// changes.  The loads are buffer loads: the uniform part travels in a scalar register and the
+// per-thread offset in one vector register, so a load costs no vector-ALU instruction.  Its LDS
+// address is the thread's first one plus a compile-time constant.
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+constexpr int kBufferWord3 = 0x00020000;   // raw buffer of 32-bit data on gfx9 (DATA_FORMAT = 32)
+
+template <int ROWS, int THREADS, bool KIN>
+struct FullTileLoader {
+    static constexpr int ELEMS = ROWS * kKT;
+    static constexpr int PER_THREAD = (ELEMS + THREADS - 1) / THREADS;
+    static constexpr int SP = ROWS + 1;
+    static constexpr int PSTEP = KIN ? THREADS / kKT : THREADS / ROWS;
+    static constexpr int LDS_PSTEP = KIN ? PSTEP : PSTEP * SP;
+    static_assert(KIN ? THREADS % kKT == 0 : THREADS % ROWS == 0, "elements of a thread differ by whole rows / K indices");
+
+    cf regs[PER_THREAD];
+    __amdgpu_buffer_rsrc_t rsrc;   // one bin's operand matrix
+    unsigned voff;                 // byte offset of element 0 from the chunk's first element
+    int lds_off;                   // LDS element index of element 0
+
+    // `matrix`: the bin's operand matrix of `bytes` bytes (below 2 GB), leading dimension ld.
+    __device__ __forceinline__ void init(const cf *matrix, unsigned bytes, int ld, int tid)
+    {
+        rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<cf *>(matrix), 0, (int)bytes, kBufferWord3);
+        const int kk = KIN ? tid % kKT : tid / ROWS, r = KIN ? tid / kKT : tid % ROWS;
+        voff = (unsigned)((KIN ? r * ld + kk : kk * ld + r) * 8);
+        lds_off = kk * SP + r;
+    }
+
+    // `origin`: byte offset (uniform) of the tile's first element of this K chunk inside the matrix.
+    __device__ __forceinline__ void load(int origin, int ld, int tid)
+    {
+#pragma unroll
+        for (int p = 0; p < PER_THREAD; ++p)
+            if (ELEMS % THREADS == 0 || p * THREADS + tid < ELEMS) {
+                const floatx2 v = __builtin_amdgcn_raw_buffer_load_b64(rsrc, (int)voff, origin + p * PSTEP * ld * 8, 0);
+                regs[p] = mk(v.x, v.y);
+            }
+    }
+
+    __device__ __forceinline__ void store(cf *Ps, int tid) const
+    {
+#pragma unroll
+        for (int p = 0; p < PER_THREAD; ++p)
+            if (ELEMS % THREADS == 0 || p * THREADS + tid < ELEMS) Ps[lds_off + p * LDS_PSTEP] = regs[p];
     }
 };
 
@@ -120,11 +180,103 @@ struct GemmTile {
     static constexpr int WAVES_PER_SIMD = ACC_REGS <= 48 ? (WM * WN >= 4 ? 4 : 3) : (ACC_REGS <= 96 ? 2 : 1);
 };
 
+// The K loop of one tile.  LA / LB are the two operands' loaders (general or full-tile);
+// loadA(k0) / loadB(k0) issue the loads of the chunk starting at K index k0.
+template <class G, bool CONJ_A, bool CONJ_B, class LA, class LB, class LoadA, class LoadB>
+__device__ __forceinline__ void contract_tile(cf *lds, int tid, int lane, int wm, int wn, int nchunks, LA &la, LB &lb,
+                                              LoadA &&loadA, LoadB &&loadB, floatx16 (&k1)[G::IT][G::JT],
+                                              floatx16 (&k2)[G::IT][G::JT], floatx16 (&k3)[G::IT][G::JT])
+{
+    constexpr int IT = G::IT, JT = G::JT, KS = kKT / 2;
+    loadA(0);
+    loadB(0);
+    la.store(lds, tid);
+    lb.store(lds + kKT * G::SA, tid);
+    if (nchunks > 1) {
+        loadA(kKT);
+        loadB(kKT);
+    }
+    __syncthreads();
+
+    const int lrow = lane & 31, lk = lane >> 5;
+    const int a_off = lk * G::SA + wm * (IT * 32) + lrow;
+    const int b_off = kKT * G::SA + lk * G::SB + wn * (JT * 32) + lrow;
+
+    // operand sums of the three-product form, with the sign of a conjugated operand folded in
+    auto sum_a = [](cf a) { return CONJ_A ? a.x - a.y : a.x + a.y; };       // ar + ai'
+    auto dif_b = [](cf b) { return CONJ_B ? -b.y - b.x : b.y - b.x; };      // bi' - br
+    auto sum_b = [](cf b) { return CONJ_B ? b.x - b.y : b.x + b.y; };       // br + bi'
+
+    for (int c = 0; c < nchunks; ++c) {
+        const cf *Af = lds + (c & 1) * G::STAGE + a_off;
+        const cf *Bf = lds + (c & 1) * G::STAGE + b_off;
+        cf af[2][IT], bf[2][JT];
+        float as[2][IT], bd[2][JT], bs[2][JT];
+#pragma unroll
+        for (int a = 0; a < IT; ++a) {
+            af[0][a] = Af[a * 32];
+            as[0][a] = sum_a(af[0][a]);
+        }
+#pragma unroll
+        for (int b = 0; b < JT; ++b) {
+            bf[0][b] = Bf[b * 32];
+            bd[0][b] = dif_b(bf[0][b]);
+            bs[0][b] = sum_b(bf[0][b]);
+        }
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int cur = ks & 1, nxt = cur ^ 1;
+            if (ks + 1 < KS) {   // fragments of the next step: their LDS latency hides behind this step's MFMAs
+#pragma unroll
+                for (int a = 0; a < IT; ++a) af[nxt][a] = Af[(2 * (ks + 1)) * G::SA + a * 32];
+#pragma unroll
+                for (int b = 0; b < JT; ++b) bf[nxt][b] = Bf[(2 * (ks + 1)) * G::SB + b * 32];
+            }
+            if (ks == KS / 2) {   // mid-chunk: hand the next chunk to LDS, start fetching the one after
+                cf *stage = lds + ((c + 1) & 1) * G::STAGE;
+                if (c + 1 < nchunks) {
+                    la.store(stage, tid);
+                    lb.store(stage + kKT * G::SA, tid);
+                }
+                if (c + 2 < nchunks) {
+                    loadA((c + 2) * kKT);
+                    loadB((c + 2) * kKT);
+                }
+            }
+            // Order within a step: fragment reads (and staging) first, then this step's MFMAs,
+            // then the operand sums of the NEXT step.  Left alone, the scheduler sinks the reads to
+            // just before their use (LDS latency back on the critical path), and a sum computed right
+            // before the MFMA that consumes it holds up the matrix pipe.
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int a = 0; a < IT; ++a)
+#pragma unroll
+                for (int b = 0; b < JT; ++b) {
+                    k1[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(as[cur][a], bf[cur][b].x, k1[a][b], 0, 0, 0);
+                    k2[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cur][a].x, bd[cur][b], k2[a][b], 0, 0, 0);
+                    k3[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cur][a].y, bs[cur][b], k3[a][b], 0, 0, 0);
+                }
+            __builtin_amdgcn_sched_barrier(0);
+            if (ks + 1 < KS) {
+#pragma unroll
+                for (int a = 0; a < IT; ++a) as[nxt][a] = sum_a(af[nxt][a]);
+#pragma unroll
+                for (int b = 0; b < JT; ++b) {
+                    bd[nxt][b] = dif_b(bf[nxt][b]);
+                    bs[nxt][b] = sum_b(bf[nxt][b]);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        __syncthreads();
+    }
+}
+
 // Launch: grid = bins * tiles_m * tiles_n blocks of G::THREADS threads, G::LDS_BYTES dynamic LDS.
 template <class G, bool A_KIN, bool B_KIN, bool CONJ_A, bool CONJ_B>
 __global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void bin_cgemm_kernel(GemmArgs g)
 {
-    constexpr int IT = G::IT, JT = G::JT, KS = kKT / 2;
+    constexpr int IT = G::IT, JT = G::JT;
     extern __shared__ __align__(16) unsigned char lds_raw[];
     cf *lds = reinterpret_cast<cf *>(lds_raw);
 
@@ -153,9 +305,6 @@ __global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void bin_cgemm_kerne
     const cf *Bb = g.B + (size_t)bin * g.Nd * g.Kd;
     cf *Cb = g.C + (size_t)bin * g.Md * g.Nd;
 
-    TileLoader<G::MT, G::THREADS, A_KIN, CONJ_A> la;
-    TileLoader<G::NT, G::THREADS, B_KIN, CONJ_B> lb;
-
     floatx16 k1[IT][JT], k2[IT][JT], k3[IT][JT];
 #pragma unroll
     for (int a = 0; a < IT; ++a)
@@ -165,85 +314,29 @@ __global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void bin_cgemm_kerne
             for (int v = 0; v < 16; ++v) { k1[a][b][v] = 0.0f; k2[a][b][v] = 0.0f; k3[a][b][v] = 0.0f; }
 
     const int nchunks = (g.Kd + kKT - 1) / kKT;
-    la.load(Ab, lda, i0, g.Md, 0, g.Kd, tid);
-    lb.load(Bb, ldb, j0, g.Nd, 0, g.Kd, tid);
-    la.store(lds, tid);
-    lb.store(lds + kKT * G::SA, tid);
-    if (nchunks > 1) {
-        la.load(Ab, lda, i0, g.Md, kKT, g.Kd, tid);
-        lb.load(Bb, ldb, j0, g.Nd, kKT, g.Kd, tid);
+    // uniform across the workgroup: the tile lies inside both matrices and K has no tail
+    const bool full = g.full_tiles_ok && i0 + G::MT <= g.Md && j0 + G::NT <= g.Nd && g.Kd % kKT == 0;
+    if (full) {
+        FullTileLoader<G::MT, G::THREADS, A_KIN> la;
+        FullTileLoader<G::NT, G::THREADS, B_KIN> lb;
+        la.init(Ab, (unsigned)g.Md * (unsigned)g.Kd * 8u, lda, tid);
+        lb.init(Bb, (unsigned)g.Nd * (unsigned)g.Kd * 8u, ldb, tid);
+        contract_tile<G, CONJ_A, CONJ_B>(
+            lds, tid, lane, wm, wn, nchunks, la, lb,
+            [&](int k0) { la.load((A_KIN ? i0 * lda + k0 : k0 * lda + i0) * 8, lda, tid); },
+            [&](int k0) { lb.load((B_KIN ? j0 * ldb + k0 : k0 * ldb + j0) * 8, ldb, tid); }, k1, k2, k3);
+    } else {
+        TileLoader<G::MT, G::THREADS, A_KIN> la;
+        TileLoader<G::NT, G::THREADS, B_KIN> lb;
+        contract_tile<G, CONJ_A, CONJ_B>(
+            lds, tid, lane, wm, wn, nchunks, la, lb,
+            [&](int k0) { la.load(Ab, lda, i0, g.Md, k0, g.Kd, tid); },
+            [&](int k0) { lb.load(Bb, ldb, j0, g.Nd, k0, g.Kd, tid); }, k1, k2, k3);
     }
-    __syncthreads();
 
+    // 32x32 accumulator layout: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32.
+    // k3 was accumulated with the plain imaginary part of a; for conj(a) it changes sign.
     const int lrow = lane & 31, lk = lane >> 5;
-    const int a_off = lk * G::SA + wm * (IT * 32) + lrow;
-    const int b_off = kKT * G::SA + lk * G::SB + wn * (JT * 32) + lrow;
-
-    for (int c = 0; c < nchunks; ++c) {
-        const cf *Af = lds + (c & 1) * G::STAGE + a_off;
-        const cf *Bf = lds + (c & 1) * G::STAGE + b_off;
-        cf af[2][IT], bf[2][JT];
-        float as[2][IT], bd[2][JT], bs[2][JT];   // ar + ai, bi - br, br + bi
-#pragma unroll
-        for (int a = 0; a < IT; ++a) {
-            af[0][a] = Af[a * 32];
-            as[0][a] = af[0][a].x + af[0][a].y;
-        }
-#pragma unroll
-        for (int b = 0; b < JT; ++b) {
-            bf[0][b] = Bf[b * 32];
-            bd[0][b] = bf[0][b].y - bf[0][b].x;
-            bs[0][b] = bf[0][b].x + bf[0][b].y;
-        }
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const int cur = ks & 1, nxt = cur ^ 1;
-            if (ks + 1 < KS) {   // fragments of the next step: their LDS latency hides behind this step's MFMAs
-#pragma unroll
-                for (int a = 0; a < IT; ++a) af[nxt][a] = Af[(2 * (ks + 1)) * G::SA + a * 32];
-#pragma unroll
-                for (int b = 0; b < JT; ++b) bf[nxt][b] = Bf[(2 * (ks + 1)) * G::SB + b * 32];
-            }
-            if (ks == KS / 2) {   // mid-chunk: hand the next chunk to LDS, start fetching the one after
-                cf *stage = lds + ((c + 1) & 1) * G::STAGE;
-                if (c + 1 < nchunks) {
-                    la.store(stage, tid);
-                    lb.store(stage + kKT * G::SA, tid);
-                }
-                if (c + 2 < nchunks) {
-                    la.load(Ab, lda, i0, g.Md, (c + 2) * kKT, g.Kd, tid);
-                    lb.load(Bb, ldb, j0, g.Nd, (c + 2) * kKT, g.Kd, tid);
-                }
-            }
-            // Order within a step: fragment reads (and staging) first, then this step's MFMAs,
-            // then the operand sums of the NEXT step.  Left alone, the scheduler sinks the reads to
-            // just before their use (LDS latency back on the critical path), and a sum computed right
-            // before the MFMA that consumes it holds up the matrix pipe.
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int a = 0; a < IT; ++a)
-#pragma unroll
-                for (int b = 0; b < JT; ++b) {
-                    k1[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(as[cur][a], bf[cur][b].x, k1[a][b], 0, 0, 0);
-                    k2[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cur][a].x, bd[cur][b], k2[a][b], 0, 0, 0);
-                    k3[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cur][a].y, bs[cur][b], k3[a][b], 0, 0, 0);
-                }
-            __builtin_amdgcn_sched_barrier(0);
-            if (ks + 1 < KS) {
-#pragma unroll
-                for (int a = 0; a < IT; ++a) as[nxt][a] = af[nxt][a].x + af[nxt][a].y;
-#pragma unroll
-                for (int b = 0; b < JT; ++b) {
-                    bd[nxt][b] = bf[nxt][b].y - bf[nxt][b].x;
-                    bs[nxt][b] = bf[nxt][b].x + bf[nxt][b].y;
-                }
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        __syncthreads();
-    }
-
-    // 32x32 accumulator layout: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32
 #pragma unroll
     for (int a = 0; a < IT; ++a)
 #pragma unroll
@@ -252,8 +345,10 @@ __global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void bin_cgemm_kerne
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int row = i0 + wm * (IT * 32) + a * 32 + 8 * (v / 4) + 4 * lk + (v % 4);
-                if (row < g.Md && col < g.Nd)
-                    Cb[(size_t)row * g.Nd + col] = mk(k1[a][b][v] - k3[a][b][v], k1[a][b][v] + k2[a][b][v]);
+                if (row < g.Md && col < g.Nd) {
+                    const float re = CONJ_A ? k1[a][b][v] + k3[a][b][v] : k1[a][b][v] - k3[a][b][v];
+                    Cb[(size_t)row * g.Nd + col] = mk(re, k1[a][b][v] + k2[a][b][v]);
+                }
             }
         }
 }

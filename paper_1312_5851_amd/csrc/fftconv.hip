@@ -90,41 +90,30 @@ struct GemmEntry {
       bin_cgemm_kernel<GemmTile<it, jt, wm, wn>, true, false, false, false>,                     \
       bin_cgemm_kernel<GemmTile<it, jt, wm, wn>, false, false, true, false>}}
 // (32x32 tiles per wave along M and N, waves along M and N, resident waves per SIMD)
+// One 32x32 tile per wave throughout.  Measured inside the full step on MI355X (operands
+// coming from HBM, not from a cache warmed by the previous launch), these shapes win over
+// larger wave tiles (64x32, 64x64 per wave) and over 8-, 12- and 16-wave workgroups at the K
+// of these layers: more independent workgroups per CU hide the per-tile prologue, epilogue
+// and barrier waits.
 const GemmEntry kGemmTable[] = {
-    GEMM_ENTRY(2, 1, 2, 2, 3),   //  0: 128 x  64
-    GEMM_ENTRY(1, 2, 2, 2, 3),   //  1:  64 x 128
-    GEMM_ENTRY(1, 1, 2, 2, 4),   //  2:  64 x  64
-    GEMM_ENTRY(2, 1, 1, 3, 3),   //  3:  64 x  96
-    GEMM_ENTRY(2, 1, 2, 3, 3),   //  4: 128 x  96
-    GEMM_ENTRY(1, 1, 2, 3, 4),   //  5:  64 x  96 (32 x 32 per wave)
-    GEMM_ENTRY(1, 1, 1, 1, 4),   //  6:  32 x  32
-    GEMM_ENTRY(1, 1, 4, 1, 4),   //  7: 128 x  32
-    GEMM_ENTRY(2, 1, 2, 1, 3),   //  8: 128 x  32 (64 x 32 per wave)
-    GEMM_ENTRY(2, 2, 2, 2, 1),   //  9: 128 x 128
-    GEMM_ENTRY(1, 3, 2, 1, 2),   // 10:  64 x  96 (32 x 96 per wave)
-    GEMM_ENTRY(1, 1, 4, 2, 4),   // 11: 128 x  64, 8 waves
-    GEMM_ENTRY(1, 1, 2, 4, 4),   // 12:  64 x 128, 8 waves
-    GEMM_ENTRY(1, 1, 4, 4, 4),   // 13: 128 x 128, 16 waves
-    GEMM_ENTRY(1, 1, 4, 3, 4),   // 14: 128 x  96, 12 waves
+    GEMM_ENTRY(1, 1, 2, 2, 4),   // 0:  64 x 64
+    GEMM_ENTRY(1, 1, 4, 1, 4),   // 1: 128 x 32
+    GEMM_ENTRY(1, 1, 2, 3, 4),   // 2:  64 x 96
+    GEMM_ENTRY(1, 1, 1, 1, 4),   // 3:  32 x 32
 };
 #undef GEMM_ENTRY
 constexpr int kNumGemm = sizeof(kGemmTable) / sizeof(kGemmTable[0]);
 
-// Picks the tile shape.  Measured inside the full step on MI355X (operands coming from HBM,
-// not from a cache warmed by the previous launch), the 4-wave shapes with one 32x32 tile per
-// wave win over larger wave tiles and over 8- or 16-wave workgroups at these K: more
-// independent workgroups per CU hide the per-tile prologue, epilogue and barrier waits.
-// So the choice is among those: least padded work first, then the preference order.
+// Picks the tile shape: least padded work first, then the order of the table.
 int choose_gemm_tile(int Md, int Nd, int /*Kd*/, int /*bins*/)
 {
     if (const char *env = std::getenv("FFTCONV_GEMM_TILE")) {
         const int v = std::atoi(env);
         if (v >= 0 && v < kNumGemm) return v;
     }
-    static const int preference[] = {2, 7, 5, 6};   // 64x64, 128x32, 64x96, 32x32
-    int best = preference[0];
+    int best = 0;
     long best_area = -1;
-    for (int i : preference) {
+    for (int i = 0; i < kNumGemm; ++i) {
         const GemmEntry &e = kGemmTable[i];
         const long area = (long)((Md + e.MT - 1) / e.MT) * e.MT * ((Nd + e.NT - 1) / e.NT) * e.NT;
         if (best_area < 0 || area < best_area) { best_area = area; best = i; }
@@ -306,6 +295,8 @@ int launch_contract(fftconv_plan_t p, int pass, void *ws, hipStream_t stream)
     g.tiles_m = (Md + e.MT - 1) / e.MT;
     g.tiles_n = (Nd + e.NT - 1) / e.NT;
     g.xcd_remap = std::getenv("FFTCONV_NO_XCD_REMAP") ? 0 : 1;
+    const long lim = 1L << 28;   // complex elements in 2 GB
+    g.full_tiles_ok = ((long)Md * Kd < lim && (long)Nd * Kd < lim && !std::getenv("FFTCONV_NO_FULL_TILES")) ? 1 : 0;
     const long blocks = (long)g.bins * g.tiles_m * g.tiles_n;
     if (blocks <= 0 || blocks > 0x7fffffffL) return FFTCONV_EUNSUPPORTED;
     if (int rc = allow_lds(e.pass[pass], e.lds_bytes)) return rc;
