@@ -92,9 +92,9 @@ struct GemmEntry {
 // (32x32 tiles per wave along M and N, waves along M and N, resident waves per SIMD)
 // One 32x32 tile per wave throughout.  Measured inside the full step on MI355X (operands
 // coming from HBM, not from a cache warmed by the previous launch), these shapes win over
-// larger wave tiles (64x32, 64x64 per wave) and over 8-, 12- and 16-wave workgroups at the K
-// of these layers: more independent workgroups per CU hide the per-tile prologue, epilogue
-// and barrier waits.
+// larger wave tiles (64x32, 64x64 per wave), over 8-, 12- and 16-wave workgroups and over 1-
+// and 2-wave workgroups of the same wave tile at the K of these layers: four resident
+// workgroups per CU hide the per-tile prologue, epilogue and barrier waits best.
 const GemmEntry kGemmTable[] = {
     GEMM_ENTRY(1, 1, 2, 2, 4),   // 0:  64 x 64
     GEMM_ENTRY(1, 1, 4, 1, 4),   // 1: 128 x 32
