@@ -54,7 +54,7 @@ struct GemmArgs {
     int bins;
     int tiles_m, tiles_n;
     int xcd_remap;   // 1: renumber workgroups so that each XCD gets contiguous work
-    int full_tiles_ok;   // 1: both operand matrices of a bin are below 2 GB, so 32-bit byte offsets suffice
+    int full_tiles_ok;   // 1: the operand and result matrices of a bin are below 2 GB, so 32-bit byte offsets suffice
 };
 
 constexpr int kXcds = 8;   // accelerator complex dies on MI355X; workgroups are dealt to them round-robin
@@ -207,7 +207,10 @@ __device__ __forceinline__ void contract_tile(cf *lds, int tid, int lane, int wm
     auto dif_b = [](cf b) { return CONJ_B ? -b.y - b.x : b.y - b.x; };      // bi' - br
     auto sum_b = [](cf b) { return CONJ_B ? b.x - b.y : b.x + b.y; };       // br + bi'
 
-    for (int c = 0; c < nchunks; ++c) {
+    // One K chunk.  In the first chunk the accumulators start from zero: its first MFMAs take the
+    // constant 0 as their addend, which saves clearing 48 registers per tile beforehand.
+    auto chunk = [&](auto first_tag, int c) {
+        constexpr bool FIRST = decltype(first_tag)::value;
         const cf *Af = lds + (c & 1) * G::STAGE + a_off;
         const cf *Bf = lds + (c & 1) * G::STAGE + b_off;
         cf af[2][IT], bf[2][JT];
@@ -252,9 +255,11 @@ __device__ __forceinline__ void contract_tile(cf *lds, int tid, int lane, int wm
             for (int a = 0; a < IT; ++a)
 #pragma unroll
                 for (int b = 0; b < JT; ++b) {
-                    k1[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(as[cur][a], bf[cur][b].x, k1[a][b], 0, 0, 0);
-                    k2[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cur][a].x, bd[cur][b], k2[a][b], 0, 0, 0);
-                    k3[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cur][a].y, bs[cur][b], k3[a][b], 0, 0, 0);
+                    const floatx16 zero = {};
+                    const bool start = FIRST && ks == 0;
+                    k1[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(as[cur][a], bf[cur][b].x, start ? zero : k1[a][b], 0, 0, 0);
+                    k2[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cur][a].x, bd[cur][b], start ? zero : k2[a][b], 0, 0, 0);
+                    k3[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cur][a].y, bs[cur][b], start ? zero : k3[a][b], 0, 0, 0);
                 }
             __builtin_amdgcn_sched_barrier(0);
             if (ks + 1 < KS) {
@@ -269,7 +274,9 @@ __device__ __forceinline__ void contract_tile(cf *lds, int tid, int lane, int wm
             __builtin_amdgcn_sched_barrier(0);
         }
         __syncthreads();
-    }
+    };
+    chunk(std::true_type{}, 0);
+    for (int c = 1; c < nchunks; ++c) chunk(std::false_type{}, c);
 }
 
 // Launch: grid = bins * tiles_m * tiles_n blocks of G::THREADS threads, G::LDS_BYTES dynamic LDS.
@@ -305,13 +312,7 @@ __global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void bin_cgemm_kerne
     const cf *Bb = g.B + (size_t)bin * g.Nd * g.Kd;
     cf *Cb = g.C + (size_t)bin * g.Md * g.Nd;
 
-    floatx16 k1[IT][JT], k2[IT][JT], k3[IT][JT];
-#pragma unroll
-    for (int a = 0; a < IT; ++a)
-#pragma unroll
-        for (int b = 0; b < JT; ++b)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) { k1[a][b][v] = 0.0f; k2[a][b][v] = 0.0f; k3[a][b][v] = 0.0f; }
+    floatx16 k1[IT][JT], k2[IT][JT], k3[IT][JT];   // written first by the MFMAs of the first K chunk
 
     const int nchunks = (g.Kd + kKT - 1) / kKT;
     // uniform across the workgroup: the tile lies inside both matrices and K has no tail
@@ -337,6 +338,25 @@ __global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void bin_cgemm_kerne
     // 32x32 accumulator layout: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32.
     // k3 was accumulated with the plain imaginary part of a; for conj(a) it changes sign.
     const int lrow = lane & 31, lk = lane >> 5;
+    if (full) {
+        // buffer stores: the per-lane part of the address is one register, the rest is uniform
+        const __amdgpu_buffer_rsrc_t rsrc =
+            __builtin_amdgcn_make_buffer_rsrc(Cb, 0, (int)((unsigned)g.Md * (unsigned)g.Nd * 8u), kBufferWord3);
+        const int voff = ((wm * (IT * 32) + 4 * lk) * g.Nd + wn * (JT * 32) + lrow) * 8;
+#pragma unroll
+        for (int a = 0; a < IT; ++a)
+#pragma unroll
+            for (int b = 0; b < JT; ++b)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int soff = ((i0 + a * 32 + 8 * (v / 4) + (v % 4)) * g.Nd + j0 + b * 32) * 8;
+                    floatx2 out;
+                    out.x = CONJ_A ? k1[a][b][v] + k3[a][b][v] : k1[a][b][v] - k3[a][b][v];
+                    out.y = k1[a][b][v] + k2[a][b][v];
+                    __builtin_amdgcn_raw_buffer_store_b64(out, rsrc, voff, soff, 0);
+                }
+        return;
+    }
 #pragma unroll
     for (int a = 0; a < IT; ++a)
 #pragma unroll

@@ -296,7 +296,8 @@ int launch_contract(fftconv_plan_t p, int pass, void *ws, hipStream_t stream)
     g.tiles_n = (Nd + e.NT - 1) / e.NT;
     g.xcd_remap = std::getenv("FFTCONV_NO_XCD_REMAP") ? 0 : 1;
     const long lim = 1L << 28;   // complex elements in 2 GB
-    g.full_tiles_ok = ((long)Md * Kd < lim && (long)Nd * Kd < lim && !std::getenv("FFTCONV_NO_FULL_TILES")) ? 1 : 0;
+    g.full_tiles_ok =
+        ((long)Md * Kd < lim && (long)Nd * Kd < lim && (long)Md * Nd < lim && !std::getenv("FFTCONV_NO_FULL_TILES")) ? 1 : 0;
     const long blocks = (long)g.bins * g.tiles_m * g.tiles_n;
     if (blocks <= 0 || blocks > 0x7fffffffL) return FFTCONV_EUNSUPPORTED;
     if (int rc = allow_lds(e.pass[pass], e.lds_bytes)) return rc;
