@@ -12,15 +12,14 @@
 // bin-major, complex interleaved, row-major inside a bin.
 //
 // Arithmetic.  A complex product needs three real products when sums of the
-// operands are formed first (Gauss):
-//     k1 = (ar + ai) * br,   k2 = ar * (bi - br),   k3 = ai * (br + bi)
-//     re = k1 - k3,          im = k1 + k2
+// operands are formed first (Karatsuba):
+//     k1 = ar * br,   k2 = ai * bi,   k3 = (ar + ai) * (br + bi)
+//     re = k1 - k2,   im = k3 - k1 - k2
 // Each is accumulated over K by v_mfma_f32_32x32x2_f32 in its own fp32 tile, so a
 // bin costs 6*M*N*K matrix-core flops instead of the 8*M*N*K of the four-product
-// form; the operand sums are three VALU operations per fragment, and re/im are
+// form; the operand sums are two VALU operations per fragment pair, and re/im are
 // formed once in the epilogue.  A conjugated operand costs nothing: its sign goes
-// into those sums (conj b: bi - br -> -bi - br, br + bi -> br - bi; conj a:
-// ar + ai -> ar - ai and k3 enters the real part with the opposite sign).
+// into its sum (ar - ai or br - bi) and into the sign of k2 in the epilogue.
 //
 // Data flow.  A workgroup of WM x WN waves owns an MT x NT tile of one bin and
 // walks K in chunks of kKT.  Operand chunks go global -> registers -> LDS, laid
@@ -204,7 +203,6 @@ __device__ __forceinline__ void contract_tile(cf *lds, int tid, int lane, int wm
 
     // operand sums of the three-product form, with the sign of a conjugated operand folded in
     auto sum_a = [](cf a) { return CONJ_A ? a.x - a.y : a.x + a.y; };       // ar + ai'
-    auto dif_b = [](cf b) { return CONJ_B ? -b.y - b.x : b.y - b.x; };      // bi' - br
     auto sum_b = [](cf b) { return CONJ_B ? b.x - b.y : b.x + b.y; };       // br + bi'
 
     // One K chunk.  In the first chunk the accumulators start from zero: its first MFMAs take the
@@ -214,7 +212,7 @@ __device__ __forceinline__ void contract_tile(cf *lds, int tid, int lane, int wm
         const cf *Af = lds + (c & 1) * G::STAGE + a_off;
         const cf *Bf = lds + (c & 1) * G::STAGE + b_off;
         cf af[2][IT], bf[2][JT];
-        float as[2][IT], bd[2][JT], bs[2][JT];
+        float as[2][IT], bs[2][JT];
 #pragma unroll
         for (int a = 0; a < IT; ++a) {
             af[0][a] = Af[a * 32];
@@ -223,7 +221,6 @@ __device__ __forceinline__ void contract_tile(cf *lds, int tid, int lane, int wm
 #pragma unroll
         for (int b = 0; b < JT; ++b) {
             bf[0][b] = Bf[b * 32];
-            bd[0][b] = dif_b(bf[0][b]);
             bs[0][b] = sum_b(bf[0][b]);
         }
 #pragma unroll
@@ -257,19 +254,16 @@ __device__ __forceinline__ void contract_tile(cf *lds, int tid, int lane, int wm
                 for (int b = 0; b < JT; ++b) {
                     const floatx16 zero = {};
                     const bool start = FIRST && ks == 0;
-                    k1[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(as[cur][a], bf[cur][b].x, start ? zero : k1[a][b], 0, 0, 0);
-                    k2[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cur][a].x, bd[cur][b], start ? zero : k2[a][b], 0, 0, 0);
-                    k3[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cur][a].y, bs[cur][b], start ? zero : k3[a][b], 0, 0, 0);
+                    k1[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cur][a].x, bf[cur][b].x, start ? zero : k1[a][b], 0, 0, 0);
+                    k2[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cur][a].y, bf[cur][b].y, start ? zero : k2[a][b], 0, 0, 0);
+                    k3[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(as[cur][a], bs[cur][b], start ? zero : k3[a][b], 0, 0, 0);
                 }
             __builtin_amdgcn_sched_barrier(0);
             if (ks + 1 < KS) {
 #pragma unroll
                 for (int a = 0; a < IT; ++a) as[nxt][a] = sum_a(af[nxt][a]);
 #pragma unroll
-                for (int b = 0; b < JT; ++b) {
-                    bd[nxt][b] = dif_b(bf[nxt][b]);
-                    bs[nxt][b] = sum_b(bf[nxt][b]);
-                }
+                for (int b = 0; b < JT; ++b) bs[nxt][b] = sum_b(bf[nxt][b]);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -336,7 +330,9 @@ __global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void bin_cgemm_kerne
     }
 
     // 32x32 accumulator layout: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32.
-    // k3 was accumulated with the plain imaginary part of a; for conj(a) it changes sign.
+    // k1 = sum ar br, k2 = sum ai bi (plain imaginary parts), k3 = sum (ar + ai')(br + bi'):
+    //   re = k1 - s k2,  im = k3 - k1 - s k2,  s = -1 if exactly one operand is conjugated, else +1.
+    constexpr bool ONE_CONJ = CONJ_A != CONJ_B;
     const int lrow = lane & 31, lk = lane >> 5;
     if (full) {
         // buffer stores: the per-lane part of the address is one register, the rest is uniform
@@ -351,8 +347,8 @@ __global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void bin_cgemm_kerne
                 for (int v = 0; v < 16; ++v) {
                     const int soff = ((i0 + a * 32 + 8 * (v / 4) + (v % 4)) * g.Nd + j0 + b * 32) * 8;
                     floatx2 out;
-                    out.x = CONJ_A ? k1[a][b][v] + k3[a][b][v] : k1[a][b][v] - k3[a][b][v];
-                    out.y = k1[a][b][v] + k2[a][b][v];
+                    out.x = ONE_CONJ ? k1[a][b][v] + k2[a][b][v] : k1[a][b][v] - k2[a][b][v];
+                    out.y = ONE_CONJ ? (k3[a][b][v] - k1[a][b][v]) + k2[a][b][v] : (k3[a][b][v] - k1[a][b][v]) - k2[a][b][v];
                     __builtin_amdgcn_raw_buffer_store_b64(out, rsrc, voff, soff, 0);
                 }
         return;
@@ -366,8 +362,9 @@ __global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void bin_cgemm_kerne
             for (int v = 0; v < 16; ++v) {
                 const int row = i0 + wm * (IT * 32) + a * 32 + 8 * (v / 4) + 4 * lk + (v % 4);
                 if (row < g.Md && col < g.Nd) {
-                    const float re = CONJ_A ? k1[a][b][v] + k3[a][b][v] : k1[a][b][v] - k3[a][b][v];
-                    Cb[(size_t)row * g.Nd + col] = mk(re, k1[a][b][v] + k2[a][b][v]);
+                    const float re = ONE_CONJ ? k1[a][b][v] + k2[a][b][v] : k1[a][b][v] - k2[a][b][v];
+                    const float im = ONE_CONJ ? (k3[a][b][v] - k1[a][b][v]) + k2[a][b][v] : (k3[a][b][v] - k1[a][b][v]) - k2[a][b][v];
+                    Cb[(size_t)row * g.Nd + col] = mk(re, im);
                 }
             }
         }

@@ -294,6 +294,43 @@ def test_full_parity_rectangular(fc, dims):
         check(dw.cpu().numpy(), direct.accgrad(g, x, (kh, kw)), f"rect accgrad flags={flags}")
 
 
+def random_dims(rng):
+    """A small random layer; sizes chosen so that every transform size, both tiling regimes,
+    rectangular shapes, k = 1, k = n and ragged map counts all turn up over a few dozen draws."""
+    nh = int(rng.choice([rng.integers(1, 13), rng.integers(13, 65), rng.integers(65, 110)]))
+    nw = nh if rng.random() < 0.4 else int(rng.choice([rng.integers(1, 13), rng.integers(13, 65), rng.integers(65, 110)]))
+    # (a tiled layer, n > 64, supports kernel sides up to 64)
+    pick_k = lambda n: int(min(n, 64 if n > 64 else n, rng.choice([1, n, rng.integers(1, 8), rng.integers(1, 20)])))
+    return (int(rng.integers(1, 5)), int(rng.integers(1, 6)), int(rng.integers(1, 6)), nh, nw, pick_k(nh), pick_k(nw))
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_random_layers_parity(fc, seed):
+    """Twelve random layers per seed (square and rectangular, tiled and not, both plan modes)."""
+    rng = np.random.default_rng(9000 + seed)
+    for case in range(12):
+        dims = random_dims(rng)
+        S, f, fo, nh, nw, kh, kw = dims
+        flags = fc.RECOMPUTE if case % 3 == 2 else 0
+        print(f"\ncase seed={seed} #{case} dims={dims} flags={flags}", flush=True)
+        x, w, g = rect_inputs(10000 + 100 * seed + case, *dims)
+        plan = fc.Plan(S, f, fo, (nh, nw), (kh, kw), flags=flags)
+        xd, wd, gd = dev(x), dev(w), dev(g)
+        order = rng.permutation(3)
+        out = {}
+        for p in order:
+            if p == 0:
+                out["y"] = plan.fprop(xd, wd)
+            elif p == 1:
+                out["dx"] = plan.bprop(gd, wd)
+            else:
+                out["dw"] = plan.accgrad(gd, xd)
+        torch.cuda.synchronize()
+        check(out["y"].cpu().numpy(), direct.fprop(x, w), f"random fprop {dims}")
+        check(out["dx"].cpu().numpy(), direct.bprop(g, w, (nh, nw)), f"random bprop {dims}")
+        check(out["dw"].cpu().numpy(), direct.accgrad(g, x, (kh, kw)), f"random accgrad {dims}")
+
+
 def test_transposed_layer_gives_transposed_results(fc):
     """Swapping height and width of every tensor swaps them in every result (bitwise is not
     expected: the two axes are transformed in different phases)."""
