@@ -197,7 +197,7 @@ const char *fftconv_strerror(int status);
 size_t fftconv_paper_ram_bytes(int S, int n, int f, int fo);
 
 /* Matrix-core floating-point operations the contraction of one pass issues:
- * 6 * S * f * fo * B (three real multiply-adds per complex product, Gauss's
+ * 6 * S * f * fo * B (three real multiply-adds per complex product, Karatsuba's
  * form, over the B stored bins), padding of matrix tiles not counted.  For a tiled
  * layer S counts the tiles too, and the value is the mean over the three passes. */
 double fftconv_contraction_flops(fftconv_plan_t p);

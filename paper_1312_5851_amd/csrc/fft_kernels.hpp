@@ -419,6 +419,19 @@ FC_HD void inv_y_finish_tiled(int tid, int blk, const InvArgs &a, cf (&z)[G::N])
 //   inverse: x_compute | per round r: (barrier,) team r: x_write, barrier, y_gather<r> | y_finish
 
 #if defined(__HIPCC__)
+// Workgroups are dealt round-robin to the 8 XCDs of an MI355X (each with its own L2).  Renumber
+// them so that every XCD walks a contiguous range of map groups: neighbouring groups, whose
+// bin runs are neighbours in memory, then go through the same L2 (measured at N = 64 on 32768
+// maps in isolation: forward 243 -> 229 us, inverse 276 -> 264 us; 2-5 % inside a full step).
+__device__ __forceinline__ int xcd_contiguous_block()
+{
+    constexpr int kXcdCount = 8;
+    const int total = (int)gridDim.x, id = (int)blockIdx.x;
+    const int xcd = id % kXcdCount, slot = id / kXcdCount;
+    const int per = total / kXcdCount, rem = total % kXcdCount;
+    return xcd * per + (xcd < rem ? xcd : rem) + slot;
+}
+
 // Device kernels.  Launch with G::THREADS threads, ceil(M / G::T) blocks and G::LDS_BYTES
 // of dynamic LDS.
 // (the second launch bound is the number of waves per SIMD the register budget must allow)
@@ -427,7 +440,7 @@ __global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void fft2d_r2c_kerne
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     cf *lds = reinterpret_cast<cf *>(lds_raw);
-    const int tid = (int)threadIdx.x, blk = (int)blockIdx.x;
+    const int tid = (int)threadIdx.x, blk = xcd_contiguous_block();
     const int team = tid / G::XTHREADS, xt = tid % G::XTHREADS;
     cf z[G::N], v[G::N];
     const bool has = TILED ? fwd_y_compute_tiled<G>(tid, blk, a, z) : fwd_y_compute<G>(tid, blk, a, z);
@@ -446,7 +459,7 @@ __global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void ifft2d_c2r_crop
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     cf *lds = reinterpret_cast<cf *>(lds_raw);
-    const int tid = (int)threadIdx.x, blk = (int)blockIdx.x;
+    const int tid = (int)threadIdx.x, blk = xcd_contiguous_block();
     const int team = tid / G::XTHREADS, xt = tid % G::XTHREADS;
     cf z[G::N], v[G::N];
     inv_x_compute<G>(xt, blk, team, a, v);
@@ -466,7 +479,7 @@ __global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void ifft2d_c2r_tile
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     cf *lds = reinterpret_cast<cf *>(lds_raw);
-    const int tid = (int)threadIdx.x, blk = (int)blockIdx.x;
+    const int tid = (int)threadIdx.x, blk = xcd_contiguous_block();
     const int team = tid / G::XTHREADS, xt = tid % G::XTHREADS;
     cf z[G::N], v[G::N];
     inv_x_compute<G>(xt, blk, team, a, v);
