@@ -312,7 +312,7 @@ def main():
     ap.add_argument("--workload", default="mid", help="layer name from paper_1312_5851_amd.workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stage-events", action="store_true", help="do not bracket kernels with HIP events")
-    ap.add_argument("--report", metavar="PATH", help="also measure BASELINE's four layers, the n x k sweep, the "
+    ap.add_argument("--report", metavar="PATH", help="also measure the four headline layers, the n x k sweep, the "
                     "paper's table columns and its figure's three axes (fewer steps each) and write PATH.json and PATH.md")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 256 MiB device copy three times (reference for HBM byte counters)")

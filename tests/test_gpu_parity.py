@@ -83,7 +83,7 @@ def test_full_parity_small(fc, layer):
 
 @pytest.mark.parametrize("name", ["mid", "first", "deep"])
 def test_sampled_parity_full_size(fc, name):
-    """BASELINE layer shapes at full size in the launch configuration bench.py times;
+    """The headline layer shapes at full size in the launch configuration bench.py times;
     the oracle evaluates a seeded sample of whole output maps / kernels."""
     layer = wl.CONFIGS[name]
     print(f"\ncase {layer}", flush=True)
