@@ -165,10 +165,13 @@ struct FullTileLoader {
     }
 };
 
-// IT x JT 32x32 MFMA tiles per wave, WM x WN waves per workgroup.
-template <int IT_, int JT_, int WM_, int WN_>
+// IT x JT 32x32 MFMA tiles per wave, WM x WN waves per workgroup.  SETS register sets hold
+// operand chunks on their way from global memory: a chunk reaches LDS SETS chunks after its
+// loads were issued.  One set is enough when the matrix cores are the limit; products with
+// little arithmetic per byte (f = 3) are bound by HBM latency instead and run with two.
+template <int IT_, int JT_, int WM_, int WN_, int SETS_ = 1>
 struct GemmTile {
-    static constexpr int IT = IT_, JT = JT_, WM = WM_, WN = WN_;
+    static constexpr int IT = IT_, JT = JT_, WM = WM_, WN = WN_, SETS = SETS_;
     static constexpr int MT = 32 * IT * WM, NT = 32 * JT * WN;
     static constexpr int THREADS = 64 * WM * WN;
     static constexpr int SA = MT + 1, SB = NT + 1;
@@ -176,24 +179,33 @@ struct GemmTile {
     static constexpr int LDS_BYTES = 2 * STAGE * 8;     // two chunks
     static constexpr int ACC_REGS = 3 * IT * JT * 16;
     // waves per SIMD the register allocation must allow (the accumulators alone take ACC_REGS of 512)
-    static constexpr int WAVES_PER_SIMD = ACC_REGS <= 48 ? (WM * WN >= 4 ? 4 : 3) : (ACC_REGS <= 96 ? 2 : 1);
+    static constexpr int WAVES_PER_SIMD =
+        SETS > 1 ? 3 : (ACC_REGS <= 48 ? (WM * WN >= 4 ? 4 : 3) : (ACC_REGS <= 96 ? 2 : 1));
 };
 
-// The K loop of one tile.  LA / LB are the two operands' loaders (general or full-tile);
-// loadA(k0) / loadB(k0) issue the loads of the chunk starting at K index k0.
+// The K loop of one tile.  la / lb are the two operands' loaders (general or full-tile), one per
+// register set; chunk j travels through set j % SETS.  loadA(set, k0) / loadB(set, k0) issue the
+// loads of the chunk starting at K index k0 into that set.
 template <class G, bool CONJ_A, bool CONJ_B, class LA, class LB, class LoadA, class LoadB>
-__device__ __forceinline__ void contract_tile(cf *lds, int tid, int lane, int wm, int wn, int nchunks, LA &la, LB &lb,
-                                              LoadA &&loadA, LoadB &&loadB, floatx16 (&k1)[G::IT][G::JT],
-                                              floatx16 (&k2)[G::IT][G::JT], floatx16 (&k3)[G::IT][G::JT])
+__device__ __forceinline__ void contract_tile(cf *lds, int tid, int lane, int wm, int wn, int nchunks,
+                                              LA (&la)[G::SETS], LB (&lb)[G::SETS], LoadA &&loadA, LoadB &&loadB,
+                                              floatx16 (&k1)[G::IT][G::JT], floatx16 (&k2)[G::IT][G::JT],
+                                              floatx16 (&k3)[G::IT][G::JT])
 {
-    constexpr int IT = G::IT, JT = G::JT, KS = kKT / 2;
-    loadA(0);
-    loadB(0);
-    la.store(lds, tid);
-    lb.store(lds + kKT * G::SA, tid);
-    if (nchunks > 1) {
-        loadA(kKT);
-        loadB(kKT);
+    constexpr int IT = G::IT, JT = G::JT, KS = kKT / 2, SETS = G::SETS;
+    // Prologue: request the first SETS chunks, hand chunk 0 to LDS, refill its set with chunk SETS.
+    static_for<0, SETS>([&](auto si) {
+        constexpr int set = decltype(si)::value;
+        if (set == 0 || set < nchunks) {
+            loadA(si, set * kKT);
+            loadB(si, set * kKT);
+        }
+    });
+    la[0].store(lds, tid);
+    lb[0].store(lds + kKT * G::SA, tid);
+    if (SETS < nchunks) {
+        loadA(std::integral_constant<int, 0>{}, SETS * kKT);
+        loadB(std::integral_constant<int, 0>{}, SETS * kKT);
     }
     __syncthreads();
 
@@ -205,10 +217,13 @@ __device__ __forceinline__ void contract_tile(cf *lds, int tid, int lane, int wm
     auto sum_a = [](cf a) { return CONJ_A ? a.x - a.y : a.x + a.y; };       // ar + ai'
     auto sum_b = [](cf b) { return CONJ_B ? b.x - b.y : b.x + b.y; };       // br + bi'
 
-    // One K chunk.  In the first chunk the accumulators start from zero: its first MFMAs take the
-    // constant 0 as their addend, which saves clearing 48 registers per tile beforehand.
-    auto chunk = [&](auto first_tag, int c) {
+    // One K chunk; P = c % SETS is a compile-time value so that the set handed to LDS in this chunk
+    // is a fixed group of registers.  In the first chunk the accumulators start from zero: its first
+    // MFMAs take the constant 0 as their addend, which saves clearing 48 registers per tile beforehand.
+    auto chunk = [&](auto first_tag, auto set_tag, int c) {
         constexpr bool FIRST = decltype(first_tag)::value;
+        constexpr int Q = (decltype(set_tag)::value + 1) % SETS;   // set of chunk c + 1
+        const std::integral_constant<int, Q> q_tag{};
         const cf *Af = lds + (c & 1) * G::STAGE + a_off;
         const cf *Bf = lds + (c & 1) * G::STAGE + b_off;
         cf af[2][IT], bf[2][JT];
@@ -232,15 +247,15 @@ __device__ __forceinline__ void contract_tile(cf *lds, int tid, int lane, int wm
 #pragma unroll
                 for (int b = 0; b < JT; ++b) bf[nxt][b] = Bf[(2 * (ks + 1)) * G::SB + b * 32];
             }
-            if (ks == KS / 2) {   // mid-chunk: hand the next chunk to LDS, start fetching the one after
+            if (ks == KS / 2) {   // mid-chunk: hand the next chunk to LDS, refill its set with chunk c + 1 + SETS
                 cf *stage = lds + ((c + 1) & 1) * G::STAGE;
                 if (c + 1 < nchunks) {
-                    la.store(stage, tid);
-                    lb.store(stage + kKT * G::SA, tid);
+                    la[Q].store(stage, tid);
+                    lb[Q].store(stage + kKT * G::SA, tid);
                 }
-                if (c + 2 < nchunks) {
-                    loadA((c + 2) * kKT);
-                    loadB((c + 2) * kKT);
+                if (c + 1 + SETS < nchunks) {
+                    loadA(q_tag, (c + 1 + SETS) * kKT);
+                    loadB(q_tag, (c + 1 + SETS) * kKT);
                 }
             }
             // Order within a step: fragment reads (and staging) first, then this step's MFMAs,
@@ -269,8 +284,12 @@ __device__ __forceinline__ void contract_tile(cf *lds, int tid, int lane, int wm
         }
         __syncthreads();
     };
-    chunk(std::true_type{}, 0);
-    for (int c = 1; c < nchunks; ++c) chunk(std::false_type{}, c);
+    chunk(std::true_type{}, std::integral_constant<int, 0>{}, 0);
+    for (int c = 1; c < nchunks; c += SETS)
+        static_for<0, SETS>([&](auto pi) {
+            constexpr int p = decltype(pi)::value;
+            if (c + p < nchunks) chunk(std::false_type{}, std::integral_constant<int, (1 + p) % SETS>{}, c + p);
+        });
 }
 
 // Launch: grid = bins * tiles_m * tiles_n blocks of G::THREADS threads, G::LDS_BYTES dynamic LDS.
@@ -312,21 +331,24 @@ __global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void bin_cgemm_kerne
     // uniform across the workgroup: the tile lies inside both matrices and K has no tail
     const bool full = g.full_tiles_ok && i0 + G::MT <= g.Md && j0 + G::NT <= g.Nd && g.Kd % kKT == 0;
     if (full) {
-        FullTileLoader<G::MT, G::THREADS, A_KIN> la;
-        FullTileLoader<G::NT, G::THREADS, B_KIN> lb;
-        la.init(Ab, (unsigned)g.Md * (unsigned)g.Kd * 8u, lda, tid);
-        lb.init(Bb, (unsigned)g.Nd * (unsigned)g.Kd * 8u, ldb, tid);
+        FullTileLoader<G::MT, G::THREADS, A_KIN> la[G::SETS];
+        FullTileLoader<G::NT, G::THREADS, B_KIN> lb[G::SETS];
+        static_for<0, G::SETS>([&](auto si) {
+            la[decltype(si)::value].init(Ab, (unsigned)g.Md * (unsigned)g.Kd * 8u, lda, tid);
+            lb[decltype(si)::value].init(Bb, (unsigned)g.Nd * (unsigned)g.Kd * 8u, ldb, tid);
+        });
         contract_tile<G, CONJ_A, CONJ_B>(
             lds, tid, lane, wm, wn, nchunks, la, lb,
-            [&](int k0) { la.load((A_KIN ? i0 * lda + k0 : k0 * lda + i0) * 8, lda, tid); },
-            [&](int k0) { lb.load((B_KIN ? j0 * ldb + k0 : k0 * ldb + j0) * 8, ldb, tid); }, k1, k2, k3);
+            [&](auto si, int k0) { la[decltype(si)::value].load((A_KIN ? i0 * lda + k0 : k0 * lda + i0) * 8, lda, tid); },
+            [&](auto si, int k0) { lb[decltype(si)::value].load((B_KIN ? j0 * ldb + k0 : k0 * ldb + j0) * 8, ldb, tid); },
+            k1, k2, k3);
     } else {
-        TileLoader<G::MT, G::THREADS, A_KIN> la;
-        TileLoader<G::NT, G::THREADS, B_KIN> lb;
+        TileLoader<G::MT, G::THREADS, A_KIN> la[G::SETS];
+        TileLoader<G::NT, G::THREADS, B_KIN> lb[G::SETS];
         contract_tile<G, CONJ_A, CONJ_B>(
             lds, tid, lane, wm, wn, nchunks, la, lb,
-            [&](int k0) { la.load(Ab, lda, i0, g.Md, k0, g.Kd, tid); },
-            [&](int k0) { lb.load(Bb, ldb, j0, g.Nd, k0, g.Kd, tid); }, k1, k2, k3);
+            [&](auto si, int k0) { la[decltype(si)::value].load(Ab, lda, i0, g.Md, k0, g.Kd, tid); },
+            [&](auto si, int k0) { lb[decltype(si)::value].load(Bb, ldb, j0, g.Nd, k0, g.Kd, tid); }, k1, k2, k3);
     }
 
     // 32x32 accumulator layout: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32.

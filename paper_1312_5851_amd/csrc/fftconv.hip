@@ -13,6 +13,7 @@
 #include "../../include/fftconv.h"
 #include "contract_kernels.hpp"
 #include "fft_dispatch.hpp"
+#include "skinny_kernels.hpp"
 
 using namespace fftconv;
 
@@ -83,12 +84,13 @@ struct GemmEntry {
 //   fprop   A = Xh [S][f]  K contiguous,  B = Wh [fo][f] K contiguous, conj B
 //   bprop   A = Gh [S][fo] K contiguous,  B = Wh [fo][f] K outer
 //   accGrad A = Gh [S][fo] K outer, conj A,  B = Xh [S][f] K outer
-#define GEMM_ENTRY(it, jt, wm, wn, occ)                                                       \
-    {GemmTile<it, jt, wm, wn>::MT, GemmTile<it, jt, wm, wn>::NT, it * jt, wm * wn, occ,          \
-     GemmTile<it, jt, wm, wn>::THREADS, GemmTile<it, jt, wm, wn>::LDS_BYTES,                     \
-     {bin_cgemm_kernel<GemmTile<it, jt, wm, wn>, true, true, false, true>,                       \
-      bin_cgemm_kernel<GemmTile<it, jt, wm, wn>, true, false, false, false>,                     \
-      bin_cgemm_kernel<GemmTile<it, jt, wm, wn>, false, false, true, false>}}
+#define GEMM_ENTRY(it, jt, wm, wn, occ) GEMM_ENTRY_SETS(it, jt, wm, wn, occ, 1)
+#define GEMM_ENTRY_SETS(it, jt, wm, wn, occ, sets)                                             \
+    {GemmTile<it, jt, wm, wn, sets>::MT, GemmTile<it, jt, wm, wn, sets>::NT, it * jt, wm * wn, occ, \
+     GemmTile<it, jt, wm, wn, sets>::THREADS, GemmTile<it, jt, wm, wn, sets>::LDS_BYTES,         \
+     {bin_cgemm_kernel<GemmTile<it, jt, wm, wn, sets>, true, true, false, true>,                 \
+      bin_cgemm_kernel<GemmTile<it, jt, wm, wn, sets>, true, false, false, false>,               \
+      bin_cgemm_kernel<GemmTile<it, jt, wm, wn, sets>, false, false, true, false>}}
 // (32x32 tiles per wave along M and N, waves along M and N, resident waves per SIMD)
 // One 32x32 tile per wave throughout.  Measured inside the full step on MI355X (operands
 // coming from HBM, not from a cache warmed by the previous launch), these shapes win over
@@ -100,8 +102,15 @@ const GemmEntry kGemmTable[] = {
     GEMM_ENTRY(1, 1, 4, 1, 4),   // 1: 128 x 32
     GEMM_ENTRY(1, 1, 2, 3, 4),   // 2:  64 x 96
     GEMM_ENTRY(1, 1, 1, 1, 4),   // 3:  32 x 32
+    // the same shapes with two register sets of operand chunks in flight, for HBM-bound products
+    GEMM_ENTRY_SETS(1, 1, 2, 2, 3, 2),   // 4:  64 x 64
+    GEMM_ENTRY_SETS(1, 1, 4, 1, 3, 2),   // 5: 128 x 32
+    GEMM_ENTRY_SETS(1, 1, 2, 3, 3, 2),   // 6:  64 x 96
+    GEMM_ENTRY_SETS(1, 1, 1, 1, 3, 2),   // 7:  32 x 32
 };
 #undef GEMM_ENTRY
+#undef GEMM_ENTRY_SETS
+constexpr int kNumShapes = 4;   // entries i and i + kNumShapes have the same shape
 constexpr int kNumGemm = sizeof(kGemmTable) / sizeof(kGemmTable[0]);
 
 // Picks the tile shape: least padded work first, then the order of the table.
@@ -113,7 +122,7 @@ int choose_gemm_tile(int Md, int Nd, int /*Kd*/, int /*bins*/)
     }
     int best = 0;
     long best_area = -1;
-    for (int i = 0; i < kNumGemm; ++i) {
+    for (int i = 0; i < kNumShapes; ++i) {
         const GemmEntry &e = kGemmTable[i];
         const long area = (long)((Md + e.MT - 1) / e.MT) * e.MT * ((Nd + e.NT - 1) / e.NT) * e.NT;
         if (best_area < 0 || area < best_area) { best_area = area; best = i; }
@@ -279,11 +288,39 @@ void pass_dims(fftconv_plan_t p, int pass, int &Md, int &Nd, int &Kd, int &slot_
     }
 }
 
+typedef void (*SkinnyKernel)(SkinnyArgs);
+const SkinnyKernel kSkinnyAccgrad[4] = {skinny_accgrad_kernel<1>, skinny_accgrad_kernel<2>, skinny_accgrad_kernel<3>,
+                                        skinny_accgrad_kernel<4>};
+
+// accGrad of a layer with at most four input maps: a streaming kernel on the vector ALU instead
+// of matrix-core tiles that would be nine tenths padding.
+int launch_skinny_accgrad(fftconv_plan_t p, void *ws, hipStream_t stream)
+{
+    SkinnyArgs a{};
+    a.X = slot_ptr(p, ws, FFTCONV_SPEC_X);
+    a.G = slot_ptr(p, ws, FFTCONV_SPEC_G);
+    const int sc = result_slot(p, FFTCONV_ACCGRAD);
+    a.C = slot_ptr(p, ws, sc);
+    a.M = p->d.S * p->nty * p->ntx;
+    a.N = p->d.fo;
+    a.bins = p->B;
+    a.jblocks = (p->d.fo + 63) / 64;
+    const long blocks = (long)a.bins * a.jblocks;
+    if (blocks <= 0 || blocks > 0x7fffffffL) return FFTCONV_EUNSUPPORTED;
+    StageTimer timer(p, FFTCONV_STAGE_CGEMM_ACCGRAD, stream);
+    hipLaunchKernelGGL(kSkinnyAccgrad[p->d.f - 1], dim3((unsigned)blocks), dim3(kSkinnyThreads), 0, stream, a);
+    if (int rc = check_launch()) return rc;
+    if (sc != FFTCONV_SPEC_OUT) p->valid &= ~(unsigned)sc;   // the w slot now holds the result spectrum
+    return timer.finish();
+}
+
 int launch_contract(fftconv_plan_t p, int pass, void *ws, hipStream_t stream)
 {
     int Md, Nd, Kd, sa, sb;
     pass_dims(p, pass, Md, Nd, Kd, sa, sb);
     if ((p->valid & (unsigned)sa) == 0 || (p->valid & (unsigned)sb) == 0) return FFTCONV_ENOTREADY;
+    if (p->d.f <= 4 && pass == FFTCONV_ACCGRAD && !std::getenv("FFTCONV_NO_SKINNY"))
+        return launch_skinny_accgrad(p, ws, stream);
     const GemmEntry &e = kGemmTable[p->gemm_tile[pass]];
     GemmArgs g;
     g.A = slot_ptr(p, ws, sa);

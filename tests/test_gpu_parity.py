@@ -301,7 +301,8 @@ def random_dims(rng):
     nw = nh if rng.random() < 0.4 else int(rng.choice([rng.integers(1, 13), rng.integers(13, 65), rng.integers(65, 110)]))
     # (a tiled layer, n > 64, supports kernel sides up to 64)
     pick_k = lambda n: int(min(n, 64 if n > 64 else n, rng.choice([1, n, rng.integers(1, 8), rng.integers(1, 20)])))
-    return (int(rng.integers(1, 5)), int(rng.integers(1, 6)), int(rng.integers(1, 6)), nh, nw, pick_k(nh), pick_k(nw))
+    # f up to 9: layers with f <= 4 take the streaming contraction kernel in accGrad, the others the matrix-core one
+    return (int(rng.integers(1, 5)), int(rng.integers(1, 10)), int(rng.integers(1, 6)), nh, nw, pick_k(nh), pick_k(nw))
 
 
 @pytest.mark.parametrize("seed", range(4))
@@ -329,6 +330,25 @@ def test_random_layers_parity(fc, seed):
         check(out["y"].cpu().numpy(), direct.fprop(x, w), f"random fprop {dims}")
         check(out["dx"].cpu().numpy(), direct.bprop(g, w, (nh, nw)), f"random bprop {dims}")
         check(out["dw"].cpu().numpy(), direct.accgrad(g, x, (kh, kw)), f"random accgrad {dims}")
+
+
+@pytest.mark.parametrize("layer", [SMALL_LAYERS[2], SMALL_LAYERS[7], wl.Layer("f3_wide", 5, 3, 70, 20, 5, 0.1, 82),
+                                   wl.Layer("f4_tiled", 2, 4, 33, 70, 7, 0.1, 83), wl.Layer("f1", 3, 1, 40, 16, 3, 0.1, 84)],
+                         ids=lambda l: l.name)
+def test_few_input_maps_both_contraction_paths(fc, layer, monkeypatch):
+    """Layers with f <= 4 run the contraction of accGrad through a streaming kernel on the vector
+    ALU; the matrix-core kernel must give the same results (to rounding) on the same layers."""
+    print(f"\ncase {layer}", flush=True)
+    x, w, g = wl.make_inputs(layer)
+    ref = (direct.fprop(x, w), direct.bprop(g, w, layer.n), direct.accgrad(g, x, layer.k))
+    for env in (None, "1"):
+        if env:
+            monkeypatch.setenv("FFTCONV_NO_SKINNY", env)
+        plan, y, dx, dw = run_three(fc, layer, x, w, g)
+        tag = "matrix cores" if env else "streaming"
+        check(y, ref[0], f"{layer.name} fprop ({tag})")
+        check(dx, ref[1], f"{layer.name} bprop ({tag})")
+        check(dw, ref[2], f"{layer.name} accgrad ({tag})")
 
 
 def test_transposed_layer_gives_transposed_results(fc):
