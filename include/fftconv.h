@@ -5,7 +5,8 @@
  *
  * Notation (paper Sec. 2.1): S minibatch size, f input maps, fo (= f') output
  * maps, n x n inputs, k x k kernels, no = n - k + 1 (valid output, stride 1).
- * "*" is read as the cross-correlation of neural-network layers.
+ * "*" is read as the cross-correlation of neural-network layers (plan flag
+ * FFTCONV_TRUE_CONV: as the true convolution).
  *
  * Every pass follows Sec. 2.2: each 2-D map is Fourier-transformed once (zero
  * padded to N x N, N = the smallest of 8, 12, 16, 24, 32, 48, 64 that is >= n;
@@ -41,7 +42,7 @@ typedef struct fftconv_plan_s *fftconv_plan_t;
 
 typedef struct {
     int S, f, fo, n, k;
-    unsigned flags; /* 0 or FFTCONV_RECOMPUTE */
+    unsigned flags; /* bitwise OR of FFTCONV_RECOMPUTE, FFTCONV_TRUE_CONV */
 } fftconv_desc;
 
 /* The same layer with a height and a width for maps and kernels (the paper writes square
@@ -50,7 +51,7 @@ typedef struct {
  * max(nh, nw). */
 typedef struct {
     int S, f, fo, nh, nw, kh, kw;
-    unsigned flags; /* 0 or FFTCONV_RECOMPUTE */
+    unsigned flags; /* bitwise OR of FFTCONV_RECOMPUTE, FFTCONV_TRUE_CONV */
 } fftconv_desc2d;
 
 /* Plan flag: the memory-efficient mode all of the paper's own timings assume (Sec. 2.3).
@@ -61,6 +62,13 @@ typedef struct {
  * of a network in turn, sized for the largest.  fftconv_valid_slots is 0 after a pass,
  * and FFTCONV_SPEC_OUT has no offset of its own. */
 enum { FFTCONV_RECOMPUTE = 1 };
+
+/* Plan flag: read "*" in Eqs. (1)-(3) as the true convolution, i.e. with the kernel
+ * index reversed, y[s,j,p,q] = sum_i sum_ab x[s,i,p+a,q+b] w[j,i,kh-1-a,kw-1-b], instead
+ * of the cross-correlation of neural-network layers (the default).  bprop and accGrad
+ * stay the adjoints of that fprop.  Costs nothing: the kernels are read, and their
+ * gradient is stored, rotated by 180 degrees. */
+enum { FFTCONV_TRUE_CONV = 2 };
 
 enum {
     FFTCONV_OK = 0,

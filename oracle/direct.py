@@ -91,12 +91,21 @@ def _dims(x_shape, w_shape):
     return S, f, fo, nh, nw, kh, kw
 
 
-def fprop(x, w, units=None):
+def _rot180(w):
+    """Kernels with both spatial indices reversed: the true convolution with w is the
+    cross-correlation with this (the other reading of the paper's "*")."""
+    return np.ascontiguousarray(np.asarray(w)[..., ::-1, ::-1])
+
+
+def fprop(x, w, units=None, true_conv=False):
     """Eq. (1): y[s,j] = sum_i x[s,i] (star) w[j,i], valid window, shape [S,fo,noh,now].
 
     ``units`` (optional) lists output maps s*fo+j; the result is then
-    [len(units), noh, now] in list order.
+    [len(units), noh, now] in list order.  ``true_conv``: read (star) as the true
+    convolution (kernel index reversed) instead of the cross-correlation.
     """
+    if true_conv:
+        w = _rot180(w)
     x, w = _f64(x), _f64(w)
     S, f, fo, nh, nw, kh, kw = _dims(x.shape, w.shape)
     noh, now = nh - kh + 1, nw - kw + 1
@@ -106,11 +115,13 @@ def fprop(x, w, units=None):
     return out
 
 
-def bprop(g, w, n, units=None):
+def bprop(g, w, n, units=None, true_conv=False):
     """Eq. (2): dx[s,i] = sum_j g[s,j] (star) w[j,i] rotated, full window, shape [S,f,nh,nw].
 
     ``n`` is the input size: an int for square maps or (nh, nw).  ``units`` lists input maps s*f+i.
     """
+    if true_conv:
+        w = _rot180(w)
     g, w = _f64(g), _f64(w)
     fo, f, kh, kw = w.shape
     nh, nw = _pair(n)
@@ -124,11 +135,15 @@ def bprop(g, w, n, units=None):
     return out
 
 
-def accgrad(g, x, k, units=None):
+def accgrad(g, x, k, units=None, true_conv=False):
     """Eq. (3): dw[j,i] = sum_s g[s,j] (star) x[s,i], kh x kw window, shape [fo,f,kh,kw].
 
     ``k`` is the kernel size: an int for square kernels or (kh, kw).  ``units`` lists kernels j*f+i.
+    ``true_conv``: the gradient with respect to the kernels of a true convolution, i.e. the same
+    sums stored with both kernel indices reversed.
     """
+    if true_conv:
+        return _rot180(accgrad(g, x, k, units))
     g, x = _f64(g), _f64(x)
     S, f, nh, nw = x.shape
     kh, kw = _pair(k)

@@ -82,9 +82,10 @@ int replay_extent_class(int N, int ext) { return extent_class(N, ext); }
 int replay_maps_per_block(int N) { return maps_per_block(N); }
 
 // src: [M][ext_y][ext_x] floats; spec: [B][M] complex (2 floats each), B = N*N/2 + 2.
-int replay_fft2d_r2c(int N, const float *src, float *spec, int M, int ext_y, int ext_x)
+int replay_fft2d_r2c(int N, const float *src, float *spec, int M, int ext_y, int ext_x, int flip)
 {
     FwdArgs a{src, reinterpret_cast<cf *>(spec), M, ext_y, ext_x};
+    a.flip = flip;
     const int T = maps_per_block(N), NX = extent_class(N, ext_y > ext_x ? ext_y : ext_x);
 #define X(n_, t_, nx_) \
     if (N == n_ && T == t_ && NX == nx_) { replay_forward<TileGeom<n_, t_, nx_, rounds_for(n_)>>(a); return 0; }
@@ -93,9 +94,10 @@ int replay_fft2d_r2c(int N, const float *src, float *spec, int M, int ext_y, int
     return 1;
 }
 
-int replay_ifft2d_c2r_crop(int N, const float *spec, float *dst, int M, int crop_y, int crop_x, int accumulate)
+int replay_ifft2d_c2r_crop(int N, const float *spec, float *dst, int M, int crop_y, int crop_x, int accumulate, int flip)
 {
     InvArgs a{reinterpret_cast<const cf *>(spec), dst, M, crop_y, crop_x, 1.0f / (float)(N * N)};
+    a.flip = flip;
     const int T = maps_per_block(N), NX = extent_class(N, crop_y > crop_x ? crop_y : crop_x);
 #define X(n_, t_, nx_) \
     if (N == n_ && T == t_ && NX == nx_) { replay_inverse<TileGeom<n_, t_, nx_, rounds_for(n_)>>(a, accumulate != 0); return 0; }

@@ -64,6 +64,7 @@ struct FwdArgs {
     int M;                // number of transforms
     int ext_y, ext_x;     // spatial extent of a map or window; everything beyond is zero padding
     Tiling t;             // read by the tiled kernels only
+    int flip;             // untiled kernels: read every map rotated by 180 degrees (kernels of a true convolution)
 };
 
 struct InvArgs {
@@ -75,6 +76,7 @@ struct InvArgs {
     float scale;          // 1 / N^2
     int c0_y, c0_x;       // tiled kernels: first stored row / column of the transform's output
     Tiling t;             // read by the tiled kernels only
+    int flip;             // untiled kernels: store every window rotated by 180 degrees
 };
 
 struct TileOrigin {
@@ -136,14 +138,17 @@ FC_HD bool fwd_y_compute(int tid, int blk, const FwdArgs &a, cf (&z)[G::N])
     const bool va = (ma < a.M) && (x < a.ext_x), vb = (mb < a.M) && (x < a.ext_x);
     const int xc = x < a.ext_x ? x : a.ext_x - 1;
     const int mac = ma < a.M ? ma : a.M - 1, mbc = mb < a.M ? mb : a.M - 1;
-    const float *pa = a.src + ((size_t)mac * a.ext_y) * a.ext_x + xc;
-    const float *pb = a.src + ((size_t)mbc * a.ext_y) * a.ext_x + xc;
+    // element (y, x) of the transform's input is map element (y, x), or (ext_y-1-y, ext_x-1-x) if flipped
+    const int first = a.flip ? (a.ext_y - 1) * a.ext_x + (a.ext_x - 1 - xc) : xc;
+    const int rstep = a.flip ? -a.ext_x : a.ext_x;
+    const float *pa = a.src + ((size_t)mac * a.ext_y) * a.ext_x + first;
+    const float *pb = a.src + ((size_t)mbc * a.ext_y) * a.ext_x + first;
     float fa[NX], fb[NX];
     static_for<0, NX>([&](auto yi) {
         constexpr int y = decltype(yi)::value;
         if (y < a.ext_y) {
-            fa[y] = pa[y * a.ext_x];
-            fb[y] = pb[y * a.ext_x];
+            fa[y] = pa[y * rstep];
+            fb[y] = pb[y * rstep];
         } else {
             fa[y] = 0.0f;
             fb[y] = 0.0f;
@@ -343,21 +348,21 @@ FC_HD void inv_y_gather(int tid, const cf *lds, cf (&z)[G::N])
 // Stores one cropped output column (rows y < crop of one map at one x), scaled;
 // with ACC the old values are all loaded first, then added, then stored.
 template <class G, bool ACC, class Get>
-FC_HD void store_column(float *col, bool valid, const InvArgs &a, Get &&get)
+FC_HD void store_column(float *col, int rstep, bool valid, const InvArgs &a, Get &&get)
 {
     if (!valid) return;
     float old[G::NX];
     if constexpr (ACC) {
         static_for<0, G::NX>([&](auto yi) {
             constexpr int y = decltype(yi)::value;
-            old[y] = (y < a.crop_y) ? col[y * a.crop_x] : 0.0f;
+            old[y] = (y < a.crop_y) ? col[y * rstep] : 0.0f;
         });
     }
     static_for<0, G::NX>([&](auto yi) {
         constexpr int y = decltype(yi)::value;
         if (y < a.crop_y) {
-            if constexpr (ACC) col[y * a.crop_x] = old[y] + get(yi) * a.scale;
-            else col[y * a.crop_x] = get(yi) * a.scale;
+            if constexpr (ACC) col[y * rstep] = old[y] + get(yi) * a.scale;
+            else col[y * rstep] = get(yi) * a.scale;
         }
     });
 }
@@ -372,10 +377,13 @@ FC_HD void inv_y_finish(int tid, int blk, const InvArgs &a, cf (&z)[G::N])
     const int ma = blk * G::T + 2 * p, mb = ma + 1;
     fft_dif<N, true, 0, first_outputs_mask<N>(NX)>(z);
     if (x >= a.crop_x) return;
-    store_column<G, ACC>(a.dst + ((size_t)ma * a.crop_y) * a.crop_x + x, ma < a.M, a, [&](auto yi) {
+    // output (y, x) goes to window element (y, x), or (crop_y-1-y, crop_x-1-x) if flipped
+    const int first = a.flip ? (a.crop_y - 1) * a.crop_x + (a.crop_x - 1 - x) : x;
+    const int rstep = a.flip ? -a.crop_x : a.crop_x;
+    store_column<G, ACC>(a.dst + ((size_t)ma * a.crop_y) * a.crop_x + first, rstep, ma < a.M, a, [&](auto yi) {
         return z[brev<N>(decltype(yi)::value)].x;
     });
-    store_column<G, ACC>(a.dst + ((size_t)mb * a.crop_y) * a.crop_x + x, mb < a.M, a, [&](auto yi) {
+    store_column<G, ACC>(a.dst + ((size_t)mb * a.crop_y) * a.crop_x + first, rstep, mb < a.M, a, [&](auto yi) {
         return z[brev<N>(decltype(yi)::value)].y;
     });
 }

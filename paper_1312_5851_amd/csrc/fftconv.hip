@@ -265,6 +265,8 @@ int launch_forward(fftconv_plan_t p, int slot, const float *src, void *ws, hipSt
     FwdKernel kernel = use_tiles ? e->fwd_tiled : e->fwd;
     if (int rc = allow_lds(kernel, e->lds_bytes)) return rc;
     FwdArgs a{src, slot_ptr(p, ws, slot), (int)M, ext_y, ext_x, t};
+    // true convolution = correlation with the kernels rotated by 180 degrees: rotate them on the way in
+    a.flip = (slot == FFTCONV_SPEC_W && (p->d.flags & FFTCONV_TRUE_CONV)) ? 1 : 0;
     const unsigned blocks = (unsigned)((M + e->T - 1) / e->T);
     StageTimer timer(p, stage, stream);
     hipLaunchKernelGGL(kernel, dim3(blocks), dim3(e->threads), e->lds_bytes, stream, a);
@@ -376,6 +378,8 @@ int launch_inverse(fftconv_plan_t p, int pass, float *dst, void *ws, hipStream_t
     a.spec = slot_ptr(p, ws, result_slot(p, pass));
     a.dst = dst;
     a.M = (int)M;
+    // ... and rotate their gradient on the way out
+    a.flip = (pass == FFTCONV_ACCGRAD && (p->d.flags & FFTCONV_TRUE_CONV)) ? 1 : 0;
     a.scale = 1.0f / ((float)p->N * (float)p->N);
     const unsigned blocks = (unsigned)((M + e->T - 1) / e->T);
     StageTimer timer(p, FFTCONV_STAGE_IFFT_Y + pass, stream);
@@ -420,7 +424,7 @@ int fftconv_plan2d(fftconv_plan_t *out, const fftconv_desc2d *d)
     if (d->S < 1 || d->f < 1 || d->fo < 1 || d->nh < 1 || d->nw < 1 || d->kh < 1 || d->kw < 1 || d->kh > d->nh ||
         d->kw > d->nw)
         return FFTCONV_EINVAL;
-    if ((d->flags & ~(unsigned)FFTCONV_RECOMPUTE) != 0) return FFTCONV_EUNSUPPORTED;
+    if ((d->flags & ~(unsigned)(FFTCONV_RECOMPUTE | FFTCONV_TRUE_CONV)) != 0) return FFTCONV_EUNSUPPORTED;
     const int noh = d->nh - d->kh + 1, now = d->nw - d->kw + 1;
     int N = fft_size_for(d->nh > d->nw ? d->nh : d->nw), Ly = 0, Lx = 0, nty = 1, ntx = 1, nty2 = 1, ntx2 = 1;
     if (N < 0) {

@@ -19,6 +19,7 @@ FFTCONV_OK = 0
 SPEC_X, SPEC_W, SPEC_G, SPEC_OUT, SPEC_G2 = 1, 2, 4, 8, 16
 FPROP, BPROP, ACCGRAD = 0, 1, 2
 RECOMPUTE = 1   # plan flag: memory-efficient mode (no spectral cache, three-slot workspace)
+TRUE_CONV = 2   # plan flag: true convolution (kernel index reversed) instead of cross-correlation
 NUM_STAGES = 9
 PROFILE_ALL = 0x1FF
 STAGE_NAMES = ("fft_x", "fft_w", "fft_g", "cgemm_fprop", "cgemm_bprop", "cgemm_accgrad",

@@ -22,21 +22,21 @@ def replay():
 FP = ctypes.POINTER(ctypes.c_float)
 
 
-def forward(lib, src, N):
+def forward(lib, src, N, flip=0):
     M, ext_y, ext_x = src.shape
     B = N * N // 2 + 2
     spec = np.full((B, M, 2), np.nan, np.float32)
-    assert lib.replay_fft2d_r2c(N, src.ctypes.data_as(FP), spec.ctypes.data_as(FP), M, ext_y, ext_x) == 0
+    assert lib.replay_fft2d_r2c(N, src.ctypes.data_as(FP), spec.ctypes.data_as(FP), M, ext_y, ext_x, flip) == 0
     return spec[..., 0].astype(np.float64) + 1j * spec[..., 1]
 
 
-def inverse(lib, spec, N, crop, into=None):
+def inverse(lib, spec, N, crop, into=None, flip=0):
     """crop: an int (square window) or (rows, columns)."""
     cy, cx = crop if isinstance(crop, tuple) else (crop, crop)
     s = np.ascontiguousarray(np.stack([spec.real, spec.imag], -1).astype(np.float32))
     M = spec.shape[1]
     dst = np.full((M, cy, cx), np.nan, np.float32) if into is None else into.copy()
-    assert lib.replay_ifft2d_c2r_crop(N, s.ctypes.data_as(FP), dst.ctypes.data_as(FP), M, cy, cx, 0 if into is None else 1) == 0
+    assert lib.replay_ifft2d_c2r_crop(N, s.ctypes.data_as(FP), dst.ctypes.data_as(FP), M, cy, cx, 0 if into is None else 1, flip) == 0
     return dst
 
 
@@ -239,3 +239,29 @@ def test_tiled_rectangular_windows_and_scatter(replay):
                 h, w = min(Ly, H - oy), min(Lx, W - ox)
                 ref = patches[(s * ty * tx + t) * C + c, kh - 1:kh - 1 + h, kw - 1:kw - 1 + w]
                 assert np.abs(dst[s, c, oy:oy + h, ox:ox + w] - ref).max() < 3e-6
+
+
+@pytest.mark.parametrize("N", [8, 24, 32, 64])
+def test_flipped_load_and_store(replay, N):
+    """The kernels of a true convolution are read rotated by 180 degrees, their gradient is stored rotated."""
+    rng = np.random.default_rng(400 + N)
+    T = replay.replay_maps_per_block(N)
+    for ey, ex in ((3, 3), (N // 4, N // 2 + 1), (1, 5), (N, N - 1)):
+        M = T + 1
+        src = rng.uniform(-1, 1, (M, ey, ex)).astype(np.float32)
+        got = forward(replay, src, N, flip=1)
+        ref = reference_spectrum_rect(np.ascontiguousarray(src[:, ::-1, ::-1]), N)
+        assert np.abs(got - ref).max() <= 3e-6 * max(np.abs(ref).max(), 1), (N, ey, ex)
+        full = rng.uniform(-1, 1, (M, N, N))
+        back = inverse(replay, reference_spectrum(full, N), N, (ey, ex), flip=1)
+        assert np.abs(back - full[:, :ey, :ex][:, ::-1, ::-1]).max() < 3e-6
+        base = rng.uniform(-1, 1, (M, ey, ex)).astype(np.float32)
+        acc = inverse(replay, reference_spectrum(full, N), N, (ey, ex), into=base, flip=1)
+        assert np.abs(acc - (base + full[:, :ey, :ex][:, ::-1, ::-1])).max() < 3e-6
+
+
+def reference_spectrum_rect(maps, N):
+    M, ey, ex = maps.shape
+    pad = np.zeros((M, N, N)); pad[:, :ey, :ex] = maps
+    ky, kx = stored_bins(N)
+    return np.fft.fft2(pad)[:, ky, kx].T

@@ -351,6 +351,25 @@ def test_few_input_maps_both_contraction_paths(fc, layer, monkeypatch):
         check(dw, ref[2], f"{layer.name} accgrad ({tag})")
 
 
+@pytest.mark.parametrize("dims", [(2, 3, 4, 16, 16, 5, 5), (3, 2, 2, 29, 20, 6, 3), (2, 5, 3, 70, 41, 3, 6), (1, 2, 2, 8, 8, 8, 8)],
+                         ids=lambda d: "x".join(map(str, d)))
+def test_true_convolution_flag(fc, dims):
+    """Plan flag TRUE_CONV: the kernels enter rotated by 180 degrees and their gradient leaves rotated."""
+    S, f, fo, nh, nw, kh, kw = dims
+    x, w, g = rect_inputs(600 + nh, *dims)
+    xd, wd, gd = dev(x), dev(w), dev(g)
+    for flags in (fc.TRUE_CONV, fc.TRUE_CONV | fc.RECOMPUTE):
+        plan = fc.Plan(S, f, fo, (nh, nw), (kh, kw), flags=flags)
+        y, dx, dw = plan.fprop(xd, wd), plan.bprop(gd, wd), plan.accgrad(gd, xd)
+        dw2 = plan.accgrad(gd, xd, dw.clone(), accumulate=True)
+        torch.cuda.synchronize()
+        check(y.cpu().numpy(), direct.fprop(x, w, true_conv=True), f"true conv fprop flags={flags}")
+        check(dx.cpu().numpy(), direct.bprop(g, w, (nh, nw), true_conv=True), f"true conv bprop flags={flags}")
+        ref = direct.accgrad(g, x, (kh, kw), true_conv=True)
+        check(dw.cpu().numpy(), ref, f"true conv accgrad flags={flags}")
+        check(dw2.cpu().numpy(), 2 * ref, f"true conv accgrad accumulate flags={flags}")
+
+
 def test_transposed_layer_gives_transposed_results(fc):
     """Swapping height and width of every tensor swaps them in every result (bitwise is not
     expected: the two axes are transformed in different phases)."""

@@ -299,3 +299,27 @@ def test_rectangular_brute_force_and_delta_kernel():
     for a0, b0 in ((0, 0), (1, 3), (0, 2)):
         wd = np.zeros((1, 1, 2, 4)); wd[0, 0, a0, b0] = 1.0
         assert np.array_equal(direct.fprop(x, wd)[0, 0], x[0, 0, a0:a0 + 5, b0:b0 + 6])
+
+
+# ---------------------------------------------------------------- true-convolution reading of "*"
+
+@pytest.mark.parametrize("dims", [(1, 1, 1, 8, 8, 3, 3), (2, 3, 2, 7, 11, 3, 2), (2, 2, 3, 9, 6, 4, 5)])
+def test_true_convolution_option(dims):
+    """With true_conv the passes are the valid true convolution (scipy convolve2d) and its adjoints."""
+    S, f, fo, nh, nw, kh, kw = dims
+    x, w, g = rand_rect(31, *dims)
+    y = direct.fprop(x, w, true_conv=True)
+    ref = np.zeros_like(y)
+    for s, j, i in itertools.product(range(S), range(fo), range(f)):
+        ref[s, j] += sps.convolve2d(x[s, i], w[j, i], "valid")
+    np.testing.assert_allclose(y, ref, rtol=1e-12, atol=1e-12)
+    dx = direct.bprop(g, w, (nh, nw), true_conv=True)
+    dw = direct.accgrad(g, x, (kh, kw), true_conv=True)
+    a, b, c = np.vdot(y, g), np.vdot(x, dx), np.vdot(w, dw)
+    assert abs(a - b) <= 1e-12 * abs(a) + 1e-12 and abs(a - c) <= 1e-12 * abs(a) + 1e-12
+    # gradient by finite differences of <fprop(x, w), g> in one kernel entry (linear in w: exact up to rounding)
+    e = np.zeros_like(w); e[fo - 1, 0, kh - 1, 0] = 1.0
+    fd = np.vdot(direct.fprop(x, w + e, true_conv=True) - y, g)
+    assert abs(fd - dw[fo - 1, 0, kh - 1, 0]) <= 1e-10 * (1 + abs(fd))
+    # and it differs from the cross-correlation unless the kernel is symmetric
+    assert not np.allclose(y, direct.fprop(x, w))
