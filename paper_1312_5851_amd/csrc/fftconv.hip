@@ -294,25 +294,36 @@ typedef void (*SkinnyKernel)(SkinnyArgs);
 const SkinnyKernel kSkinnyAccgrad[4] = {skinny_accgrad_kernel<1>, skinny_accgrad_kernel<2>, skinny_accgrad_kernel<3>,
                                         skinny_accgrad_kernel<4>};
 
-// accGrad of a layer with at most four input maps: a streaming kernel on the vector ALU instead
-// of matrix-core tiles that would be nine tenths padding.
-int launch_skinny_accgrad(fftconv_plan_t p, void *ws, hipStream_t stream)
+const SkinnyKernel kSkinnyBprop[4] = {skinny_bprop_kernel<1>, skinny_bprop_kernel<2>, skinny_bprop_kernel<3>,
+                                      skinny_bprop_kernel<4>};
+
+// accGrad and bprop of a layer with at most four input maps: streaming kernels on the vector
+// ALU instead of matrix-core tiles that would be nine tenths padding.
+int launch_skinny(fftconv_plan_t p, int pass, void *ws, hipStream_t stream)
 {
     SkinnyArgs a{};
-    a.X = slot_ptr(p, ws, FFTCONV_SPEC_X);
-    a.G = slot_ptr(p, ws, FFTCONV_SPEC_G);
-    const int sc = result_slot(p, FFTCONV_ACCGRAD);
+    const int sc = result_slot(p, pass);
     a.C = slot_ptr(p, ws, sc);
-    a.M = p->d.S * p->nty * p->ntx;
     a.N = p->d.fo;
     a.bins = p->B;
-    a.jblocks = (p->d.fo + 63) / 64;
+    if (pass == FFTCONV_ACCGRAD) {
+        a.X = slot_ptr(p, ws, FFTCONV_SPEC_X);
+        a.G = slot_ptr(p, ws, FFTCONV_SPEC_G);
+        a.M = p->d.S * p->nty * p->ntx;
+        a.jblocks = (p->d.fo + 63) / 64;
+    } else {
+        a.X = slot_ptr(p, ws, FFTCONV_SPEC_W);
+        a.G = slot_ptr(p, ws, tiled(p) ? FFTCONV_SPEC_G2 : FFTCONV_SPEC_G);
+        a.M = p->d.S * p->nty2 * p->ntx2;
+        a.jblocks = (a.M + 63) / 64;
+    }
     const long blocks = (long)a.bins * a.jblocks;
     if (blocks <= 0 || blocks > 0x7fffffffL) return FFTCONV_EUNSUPPORTED;
-    StageTimer timer(p, FFTCONV_STAGE_CGEMM_ACCGRAD, stream);
-    hipLaunchKernelGGL(kSkinnyAccgrad[p->d.f - 1], dim3((unsigned)blocks), dim3(kSkinnyThreads), 0, stream, a);
+    SkinnyKernel kernel = pass == FFTCONV_ACCGRAD ? kSkinnyAccgrad[p->d.f - 1] : kSkinnyBprop[p->d.f - 1];
+    StageTimer timer(p, FFTCONV_STAGE_CGEMM_FPROP + pass, stream);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kSkinnyThreads), 0, stream, a);
     if (int rc = check_launch()) return rc;
-    if (sc != FFTCONV_SPEC_OUT) p->valid &= ~(unsigned)sc;   // the w slot now holds the result spectrum
+    if (sc != FFTCONV_SPEC_OUT) p->valid &= ~(unsigned)sc;   // an operand slot now holds the result spectrum
     return timer.finish();
 }
 
@@ -321,8 +332,7 @@ int launch_contract(fftconv_plan_t p, int pass, void *ws, hipStream_t stream)
     int Md, Nd, Kd, sa, sb;
     pass_dims(p, pass, Md, Nd, Kd, sa, sb);
     if ((p->valid & (unsigned)sa) == 0 || (p->valid & (unsigned)sb) == 0) return FFTCONV_ENOTREADY;
-    if (p->d.f <= 4 && pass == FFTCONV_ACCGRAD && !std::getenv("FFTCONV_NO_SKINNY"))
-        return launch_skinny_accgrad(p, ws, stream);
+    if (p->d.f <= 4 && pass != FFTCONV_FPROP && !std::getenv("FFTCONV_NO_SKINNY")) return launch_skinny(p, pass, ws, stream);
     const GemmEntry &e = kGemmTable[p->gemm_tile[pass]];
     GemmArgs g;
     g.A = slot_ptr(p, ws, sa);

@@ -1,16 +1,17 @@
-// Per-bin contraction of accGrad for layers with very few input maps (f <= 4, e.g. RGB
-// first layers).
+// Per-bin contraction of accGrad and bprop for layers with very few input maps (f <= 4, e.g.
+// RGB first layers).
 //
-// With N = f as small as 3 the complex product of Sec. 2.2 has less than 3 flops per byte: the
+// With N = f as small as 3 the complex products of Sec. 2.2 have less than 3 flops per byte: the
 // pass is bound by streaming Gh through HBM, and a 32 x 32 matrix-core tile would spend nine
-// tenths of its work on padding (measured: 76 us against 46 us here for S=128, f=3, f'=96, N=64).
-// This kernel does the few multiply-adds on the vector ALU and is laid out only for coalesced
-// streaming: lanes run along the output-map index j, which is contiguous in Gh.
+// tenths of its work on padding (measured: accGrad 76 us against 46 us here for S=128, f=3,
+// f'=96, N=64).  These kernels do the few multiply-adds on the vector ALU and are laid out only
+// for coalesced streaming of Gh, whose rows are contiguous along the output-map index j.
 //
-//   accGrad dWh[b][j][i] = sum_m conj(Gh[b][m][j]) * Xh[b][m][i]
-// m runs over samples (times tiles for a tiled layer).  (fprop and bprop with f <= 4 keep the
-// matrix-core kernel: a streaming kernel of the same kind measured no faster for fprop, and the
-// large operand of bprop is contiguous along the summed index instead.)
+//   accGrad dWh[b][j][i] = sum_m conj(Gh[b][m][j]) * Xh[b][m][i]     lanes along j, loop over m
+//   bprop   dXh[b][m][i] = sum_j      Gh[b][m][j]  * Wh[b][j][i]     64 x 64 tiles of Gh through LDS,
+//                                                                    then lanes along m, loop over j
+// m runs over samples (times tiles for a tiled layer).  (fprop with f <= 4 keeps the matrix-core
+// kernel: a streaming kernel of the same kind measured no faster.)
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -19,12 +20,12 @@
 namespace fftconv {
 
 struct SkinnyArgs {
-    const cf *X;   // Xh  [bins][M][F]
+    const cf *X;   // accGrad: Xh [bins][M][F];  bprop: Wh [bins][N][F]
     const cf *G;   // Gh  [bins][M][N]
-    cf *C;         // dWh [bins][N][F]
+    cf *C;         // accGrad: dWh [bins][N][F];  bprop: dXh [bins][M][F]
     int M, N;      // rows m (samples x tiles), output maps j
     int bins;
-    int jblocks;   // ceil(N / 64)
+    int jblocks;   // accGrad: ceil(N / 64);  bprop: row blocks ceil(M / 64)
 };
 
 constexpr int kSkinnyThreads = 256;
@@ -83,6 +84,80 @@ __global__ __launch_bounds__(kSkinnyThreads) void skinny_accgrad_kernel(SkinnyAr
 #pragma unroll
             for (int q = 1; q < kSkinnyWaves; ++q) s = s + part[q][jl][i];
             out[i] = s;
+        }
+    }
+}
+
+// bprop: grid = bins * ceil(M / 64) workgroups of kSkinnyThreads threads.  A workgroup owns 64
+// rows m.  Gh comes in as 64 x 64 tiles with lanes along j (coalesced) and is handed over through
+// LDS; then lane = row, each of the four waves sums a quarter of the tile's j range with the
+// matching Wh values read as LDS broadcasts; the quarters are added at the end.
+template <int F>
+__global__ __launch_bounds__(kSkinnyThreads) void skinny_bprop_kernel(SkinnyArgs a)
+{
+    constexpr int TS = 65;                       // tile row stride (odd: lanes along rows hit distinct banks)
+    constexpr int U = 64 / kSkinnyWaves;         // tile rows per wave and load pass
+    __shared__ cf tile[64 * TS];
+    __shared__ cf wt[64 * F];
+    const int tid = (int)threadIdx.x, lane = tid % 64, wv = wave_index();
+    const int mb = (int)blockIdx.x % a.jblocks, bin = (int)blockIdx.x / a.jblocks;
+    const int m0 = mb * 64;
+    const cf *Gb = a.G + (size_t)bin * a.M * a.N;
+    const cf *Wb = a.X + (size_t)bin * a.N * F;
+    const int nchunks = (a.N + 63) / 64;
+
+    cf regs[U], wreg = mk(0.0f, 0.0f);
+    bool ok[U], wok = false;
+    auto prefetch = [&](int c) {
+        const int j = c * 64 + lane;
+        const int jc = j < a.N ? j : a.N - 1;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int row = m0 + wv + kSkinnyWaves * u;
+            ok[u] = row < a.M && j < a.N;
+            regs[u] = Gb[(size_t)(row < a.M ? row : a.M - 1) * a.N + jc];   // clamped address, masked at the store
+        }
+        if (tid < 64 * F) {
+            const int jw = c * 64 + tid / F;
+            wok = jw < a.N;
+            wreg = Wb[(size_t)(wok ? jw : a.N - 1) * F + tid % F];
+        }
+    };
+    cf acc[F];
+#pragma unroll
+    for (int i = 0; i < F; ++i) acc[i] = mk(0.0f, 0.0f);
+    prefetch(0);
+    for (int c = 0; c < nchunks; ++c) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) tile[(wv + kSkinnyWaves * u) * TS + lane] = ok[u] ? regs[u] : mk(0.0f, 0.0f);
+        if (tid < 64 * F) wt[tid] = wok ? wreg : mk(0.0f, 0.0f);
+        __syncthreads();
+        if (c + 1 < nchunks) prefetch(c + 1);
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj) {
+            const int j = wv * 16 + jj;
+            const cf g = tile[lane * TS + j];
+#pragma unroll
+            for (int i = 0; i < F; ++i) {
+                const cf w = wt[j * F + i];
+                acc[i] = mk(acc[i].x + (g.x * w.x - g.y * w.y), acc[i].y + (g.x * w.y + g.y * w.x));
+            }
+        }
+        __syncthreads();
+    }
+    // add the four quarters (the tile is free now)
+    cf *part = tile;
+#pragma unroll
+    for (int i = 0; i < F; ++i) part[(wv * 64 + lane) * F + i] = acc[i];
+    __syncthreads();
+    if (wv == 0 && m0 + lane < a.M) {
+        cf *out = a.C + ((size_t)bin * a.M + m0 + lane) * F;
+#pragma unroll
+        for (int i = 0; i < F; ++i) {
+            cf sum = part[lane * F + i];
+#pragma unroll
+            for (int q = 1; q < kSkinnyWaves; ++q) sum = sum + part[(q * 64 + lane) * F + i];
+            out[i] = sum;
         }
     }
 }

@@ -329,11 +329,12 @@ def test_random_layers_parity(fc, seed):
 
 
 @pytest.mark.parametrize("layer", [SMALL_LAYERS[2], SMALL_LAYERS[7], wl.Layer("f3_wide", 5, 3, 70, 20, 5, 0.1, 82),
-                                   wl.Layer("f4_tiled", 2, 4, 33, 70, 7, 0.1, 83), wl.Layer("f1", 3, 1, 40, 16, 3, 0.1, 84)],
+                                   wl.Layer("f4_tiled", 2, 4, 33, 70, 7, 0.1, 83), wl.Layer("f1", 3, 1, 40, 16, 3, 0.1, 84),
+                                   wl.Layer("f2_rows", 150, 2, 130, 8, 3, 0.1, 85)],
                          ids=lambda l: l.name)
 def test_few_input_maps_both_contraction_paths(fc, layer, monkeypatch):
-    """Layers with f <= 4 run the contraction of accGrad through a streaming kernel on the vector
-    ALU; the matrix-core kernel must give the same results (to rounding) on the same layers."""
+    """Layers with f <= 4 run the contractions of accGrad and bprop through streaming kernels on the
+    vector ALU; the matrix-core kernel must give the same results (to rounding) on the same layers."""
     print(f"\ncase {layer}", flush=True)
     x, w, g = wl.make_inputs(layer)
     ref = (direct.fprop(x, w), direct.bprop(g, w, layer.n), direct.accgrad(g, x, layer.k))
