@@ -1,8 +1,8 @@
-// In-register complex FFTs of size 2^m or 3 * 2^m with compile-time indexing.
+// In-register complex FFTs of size 2^m, 3 * 2^m or 5 * 2^m with compile-time indexing.
 //
 // Every array index below is a compile-time constant after template expansion,
 // so an N-point transform lives entirely in N complex registers of one lane
-// (no scratch memory).  Sizes with a factor 3 (12, 24, 48) exist so that an
+// (no scratch memory).  Sizes with a factor 3 (12, 24, 48) or 5 (20, 40) exist so that an
 // input need not be padded all the way to the next power of two, the limitation
 // the paper points out in Sec. 4.  The same header compiles for gfx950 device code and,
 // without HIP, for a host build that replays the kernels' phases on the CPU.
@@ -76,9 +76,9 @@ constexpr double sin64(int j) { return cos64(j + 48); }   // sin(t) = cos(t - pi
 
 constexpr int ilog2(int n) { return n <= 1 ? 0 : 1 + ilog2(n >> 1); }
 
-// N = radix3_part(N) * pow2_part(N) with radix3_part in {1, 3}.
-constexpr int radix3_part(int N) { return N % 3 == 0 ? 3 : 1; }
-constexpr int pow2_part(int N) { return N / radix3_part(N); }
+// N = odd_radix(N) * pow2_part(N) with odd_radix in {1, 3, 5}.
+constexpr int odd_radix(int N) { return N % 3 == 0 ? 3 : (N % 5 == 0 ? 5 : 1); }
+constexpr int pow2_part(int N) { return N / odd_radix(N); }
 constexpr bool fft_size_ok(int N) { const int M = pow2_part(N); return M >= 2 && (M & (M - 1)) == 0 && N <= 64; }
 
 // Bit reversal of i within log2(M) bits.
@@ -91,12 +91,12 @@ constexpr int bitrev(int i, int M)
 }
 
 // Position at which fft_dif leaves output X[k].  For N = 2^m the bit reversal of k; for
-// N = 3 * M the radix-3 stage sends the outputs k = 3 q + r to block r, whose M-point
-// transform leaves X[3 q + r] at bit-reversed q.
+// N = R * M (R = 3 or 5) the radix-R stage sends the outputs k = R q + r to block r, whose
+// M-point transform leaves X[R q + r] at bit-reversed q.
 template <int N>
 constexpr int brev(int k)
 {
-    constexpr int R = radix3_part(N), M = pow2_part(N);
+    constexpr int R = odd_radix(N), M = pow2_part(N);
     return (k % R) * M + bitrev(k / R, M);
 }
 
@@ -137,7 +137,7 @@ constexpr double sin_n(int q) { return 64 % N == 0 ? sin64(q * (64 / N)) : cos_r
 template <int N, int Q, bool INV>
 FC_HD cf twiddle_mul(cf v)
 {
-    static_assert(fft_size_ok(N), "transform sizes are 2^m or 3 * 2^m, at most 64");
+    static_assert(fft_size_ok(N), "transform sizes are 2^m, 3 * 2^m or 5 * 2^m, at most 64");
     constexpr int q = ((Q % N) + N) % N;
     if constexpr (q == 0) {
         return v;
@@ -166,16 +166,22 @@ FC_HD cf twiddle_mul(cf v)
 // "element i is known to be exactly zero at compile time".
 constexpr uint64_t low_mask(int n) { return n >= 64 ? ~0ull : ((1ull << n) - 1ull); }
 
-// Mask after the radix-3 stage of an N = 3 M point transform: output r of butterfly j
-// (position r M + j) is zero iff all three inputs j, j + M, j + 2 M are.
+// Mask after the radix-R stage of an N = R M point transform (R = 3 or 5): output r of
+// butterfly j (position r M + j) is zero iff all R inputs j, j + M, ... are.
 template <int N>
-constexpr uint64_t radix3_stage_mask(uint64_t zm)
+constexpr uint64_t odd_stage_mask(uint64_t zm)
 {
-    constexpr int M = N / 3;
+    constexpr int R = odd_radix(N), M = N / R;
     uint64_t out = 0;
-    for (int j = 0; j < M; ++j)
-        if (((zm >> j) & 1) && ((zm >> (j + M)) & 1) && ((zm >> (j + 2 * M)) & 1))
-            out |= (1ull << j) | (1ull << (j + M)) | (1ull << (j + 2 * M));
+    for (int j = 0; j < M; ++j) {
+        bool all = true;
+        uint64_t bits = 0;
+        for (int q = 0; q < R; ++q) {
+            all = all && ((zm >> (j + q * M)) & 1);
+            bits |= 1ull << (j + q * M);
+        }
+        if (all) out |= bits;
+    }
     return out;
 }
 
@@ -192,11 +198,11 @@ constexpr uint64_t dif_stage_mask(uint64_t zm, int h)
     return out;
 }
 
-// Known zeros in front of radix-2 stage `stage` (after the radix-3 stage, if N has one).
+// Known zeros in front of radix-2 stage `stage` (after the radix-3 or radix-5 stage, if N has one).
 template <int N>
 constexpr uint64_t dif_mask_before_stage(uint64_t zm, int stage)
 {
-    if (radix3_part(N) == 3) zm = radix3_stage_mask<N>(zm);
+    if (odd_radix(N) > 1) zm = odd_stage_mask<N>(zm);
     int h = pow2_part(N) / 2;
     for (int s = 0; s < stage; ++s) {
         zm = dif_stage_mask<N>(zm, h);
@@ -209,7 +215,7 @@ constexpr uint64_t dif_mask_before_stage(uint64_t zm, int stage)
 // the transform" (positions are the ones brev<N> names).  need_after_stage<N>(final, s)
 // is the set of positions whose value after radix-2 stage s is still needed by some
 // requested output; s = -1 gives what is needed in front of the first radix-2 stage,
-// i.e. of the radix-3 stage's outputs.
+// i.e. of the radix-3 or radix-5 stage's outputs.
 template <int N>
 constexpr uint64_t need_after_stage(uint64_t need_final, int stage)
 {
@@ -261,9 +267,73 @@ FC_HD void radix3_butterfly(cf &a, cf &b, cf &c)
     }
 }
 
+// Of the R inputs j, j + M, ... of an odd-radix butterfly: how many leading ones can be
+// non-zero, and whether the known zeros form a suffix.
+constexpr int leading_nonzero(uint64_t zm, int j, int M, int R)
+{
+    int nz = 0;
+    for (int q = 0; q < R; ++q)
+        if (!((zm >> (j + q * M)) & 1)) nz = q + 1;
+    return nz;
+}
+constexpr bool zero_suffix(uint64_t zm, int j, int M, int R)
+{
+    for (int q = 0; q < leading_nonzero(zm, j, M, R); ++q)
+        if ((zm >> (j + q * M)) & 1) return false;
+    return true;
+}
+
+// Radix-5 decimation-in-frequency butterfly j of an N = 5 M point transform, in place on
+// x_q = v[j + q M]:
+//     y_r = (sum_q w^{r q} x_q) * exp(-/+ 2 pi i r j / N),   w = exp(-/+ 2 pi i / 5)
+// written with the sums and differences of the pairs (x1, x4) and (x2, x3).  NZ: the first NZ
+// inputs can be non-zero (zero padding is a suffix).  NEED bit r: output r is read later.
+template <int N, bool INV, int J, int NZ, unsigned NEED>
+FC_HD void radix5_butterfly(cf &x0, cf &x1, cf &x2, cf &x3, cf &x4)
+{
+    static_assert(NZ >= 1 && NZ <= 5, "at least the first input is non-zero");
+    constexpr float c1 = (float)cos_ratio(1, 5), c2 = (float)cos_ratio(2, 5);     // cos(2 pi/5), cos(4 pi/5)
+    constexpr float s1 = (float)cos_ratio(-1, 20), s2 = (float)cos_ratio(3, 20);  // sin(2 pi/5), sin(4 pi/5)
+    cf y0, y1, y2, y3, y4;
+    if constexpr (NZ == 1) {
+        y0 = y1 = y2 = y3 = y4 = x0;
+    } else {
+        cf sa, da;                 // x1 + x4, x1 - x4
+        if constexpr (NZ >= 5) { sa = x1 + x4; da = x1 - x4; }
+        else { sa = x1; da = x1; }
+        cf t1, t2, u1, u2;
+        if constexpr (NZ >= 3) {
+            cf sb, db;             // x2 + x3, x2 - x3
+            if constexpr (NZ >= 4) { sb = x2 + x3; db = x2 - x3; }
+            else { sb = x2; db = x2; }
+            y0 = x0 + sa + sb;
+            t1 = mk(x0.x + c1 * sa.x + c2 * sb.x, x0.y + c1 * sa.y + c2 * sb.y);
+            t2 = mk(x0.x + c2 * sa.x + c1 * sb.x, x0.y + c2 * sa.y + c1 * sb.y);
+            u1 = mk(s1 * da.x + s2 * db.x, s1 * da.y + s2 * db.y);
+            u2 = mk(s2 * da.x - s1 * db.x, s2 * da.y - s1 * db.y);
+        } else {
+            y0 = x0 + sa;
+            t1 = mk(x0.x + c1 * sa.x, x0.y + c1 * sa.y);
+            t2 = mk(x0.x + c2 * sa.x, x0.y + c2 * sa.y);
+            u1 = mk(s1 * da.x, s1 * da.y);
+            u2 = mk(s2 * da.x, s2 * da.y);
+        }
+        const cf e1 = mk(u1.y, -u1.x), e2 = mk(u2.y, -u2.x);   // -i u
+        y1 = INV ? t1 - e1 : t1 + e1;
+        y4 = INV ? t1 + e1 : t1 - e1;
+        y2 = INV ? t2 - e2 : t2 + e2;
+        y3 = INV ? t2 + e2 : t2 - e2;
+    }
+    if constexpr (NEED & 1u) x0 = y0;
+    if constexpr (NEED & 2u) x1 = twiddle_mul<N, J, INV>(y1);
+    if constexpr (NEED & 4u) x2 = twiddle_mul<N, 2 * J, INV>(y2);
+    if constexpr (NEED & 8u) x3 = twiddle_mul<N, 3 * J, INV>(y3);
+    if constexpr (NEED & 16u) x4 = twiddle_mul<N, 4 * J, INV>(y4);
+}
+
 // Decimation-in-frequency FFT, in place, natural-order input, outputs left at the
-// positions brev<N> names: X[k] = v[brev<N>(k)].  One radix-3 stage first if N = 3 * 2^m,
-// then radix-2 stages.
+// positions brev<N> names: X[k] = v[brev<N>(k)].  One radix-3 or radix-5 stage first if N has
+// that factor, then radix-2 stages.
 // ZMASK marks inputs known to be zero (their registers are never read), which
 // removes the arithmetic a zero-padded map does not need.  NEED marks the
 // output positions that will be read; the others are left undefined, which
@@ -271,9 +341,21 @@ FC_HD void radix3_butterfly(cf &a, cf &b, cf &c)
 template <int N, bool INV, uint64_t ZMASK = 0, uint64_t NEED = ~0ull>
 FC_HD void fft_dif(cf (&v)[N])
 {
-    static_assert(fft_size_ok(N), "transform sizes are 2^m or 3 * 2^m, at most 64");
+    static_assert(fft_size_ok(N), "transform sizes are 2^m, 3 * 2^m or 5 * 2^m, at most 64");
     constexpr int M = pow2_part(N);
-    if constexpr (radix3_part(N) == 3) {
+    if constexpr (odd_radix(N) == 5) {
+        constexpr uint64_t nd = need_after_stage<N>(NEED, -1);
+        static_for<0, M>([&](auto ji) {
+            constexpr int j = decltype(ji)::value;
+            constexpr int nz = leading_nonzero(ZMASK, j, N / 5, 5);
+            static_assert(zero_suffix(ZMASK, j, N / 5, 5), "zero padding is a suffix");
+            constexpr unsigned need = (unsigned)(((nd >> j) & 1) | (((nd >> (j + M)) & 1) << 1) | (((nd >> (j + 2 * M)) & 1) << 2) |
+                                                 (((nd >> (j + 3 * M)) & 1) << 3) | (((nd >> (j + 4 * M)) & 1) << 4));
+            if constexpr (nz > 0)
+                radix5_butterfly<N, INV, j, nz, need>(v[j], v[j + M], v[j + 2 * M], v[j + 3 * M], v[j + 4 * M]);
+        });
+    }
+    if constexpr (odd_radix(N) == 3) {
         constexpr uint64_t nd = need_after_stage<N>(NEED, -1);
         static_for<0, M>([&](auto ji) {
             constexpr int j = decltype(ji)::value;

@@ -12,29 +12,32 @@ namespace fftconv {
     X(8, 64, 8)   X(8, 64, 4)                 \
     X(12, 32, 12) X(12, 32, 6)                \
     X(16, 32, 16) X(16, 32, 8)  X(16, 32, 4)  \
+    X(20, 32, 20) X(20, 32, 10) X(20, 32, 5)  \
     X(24, 16, 24) X(24, 16, 12) X(24, 16, 6)  \
     X(32, 16, 32) X(32, 16, 16) X(32, 16, 8)  \
+    X(40, 16, 40) X(40, 16, 20) X(40, 16, 10) \
     X(48, 16, 48) X(48, 16, 24) X(48, 16, 12) \
     X(64, 16, 64) X(64, 16, 32) X(64, 16, 16)
 
-// Transform size for an n x n input: the smallest of 8, 12, 16, 24, 32, 48, 64 that holds
-// it.  The paper pads to the next power of two and names the waste for sizes just above
-// one as its limitation (Sec. 4); the sizes 3 * 2^m halve the worst-case padding.
+// Transform size for an n x n input: the smallest of 8, 12, 16, 20, 24, 32, 40, 48, 64 that
+// holds it.  The paper pads to the next power of two and names the waste for sizes just above
+// one as its limitation (Sec. 4), with n = 34 -> 64 as its example; the sizes 3 * 2^m and
+// 5 * 2^m bring that case down to 40 and keep the padded area below 1.8 x the map for n >= 8.
 inline int fft_size_for(int n)
 {
-    static const int sizes[] = {8, 12, 16, 24, 32, 48, 64};
+    static const int sizes[] = {8, 12, 16, 20, 24, 32, 40, 48, 64};
     for (int N : sizes)
         if (N >= n) return N;
     return -1;
 }
 
-constexpr int maps_per_block(int N) { return N <= 8 ? 64 : (N <= 16 ? 32 : 16); }
+constexpr int maps_per_block(int N) { return N <= 8 ? 64 : (N <= 20 ? 32 : 16); }
 
-// LDS hand-overs between the two phases: two from N = 48 up, where one would not fit the
+// LDS hand-overs between the two phases: two from N = 40 up, where one would not fit the
 // 160 KB of LDS or would leave room for a single workgroup per CU.  (At N = 32 two rounds
 // let four workgroups share a CU instead of two; inside the full step that measured the same
 // as one round, so N = 32 keeps the simpler single round.)
-constexpr int rounds_for(int N) { return N >= 48 ? 2 : 1; }
+constexpr int rounds_for(int N) { return N >= 40 ? 2 : 1; }
 
 // Smallest compiled extent class that covers `ext` columns of an N-point transform.
 inline int extent_class(int N, int ext)

@@ -76,9 +76,9 @@ def fig3_layers():
     """The three axes of the paper's speed figure (Sec. 3): image size, kernel size and
     minibatch size, each varied alone around f=96, f'=256.  The figure's tick values are
     not given in the text; the points here bracket the table's layers and include image
-    sizes that are not a power of two (Sec. 4 pads those up)."""
+    sizes that are not a power of two (Sec. 4 pads those up; n = 34 is its example)."""
     out = []
-    for i, n in enumerate((8, 12, 16, 24, 32, 48, 64)):
+    for i, n in enumerate((8, 12, 16, 20, 24, 32, 34, 40, 48, 64)):
         out.append(Layer(f"fig3_n{n}", 128, 96, 256, n, 5, 0.02, BASE_SEED + 300 + i))
     for i, k in enumerate((3, 7, 9, 11, 13)):          # k = 5 is the n = 32 point above
         out.append(Layer(f"fig3_k{k}", 128, 96, 256, 32, k, 0.02, BASE_SEED + 320 + i))

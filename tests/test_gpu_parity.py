@@ -197,6 +197,7 @@ TILED_LAYERS = [
     wl.Layer("n224_k11_f3", 1, 3, 4, 224, 11, 0.05, 96),  # first-layer-like image size
     wl.Layer("n80_k1", 2, 2, 2, 80, 1, 0.1, 97),          # k = 1: no overlap at all
     wl.Layer("n77_k6_ragged", 3, 5, 7, 77, 6, 0.1, 98),   # odd map counts: ragged transform groups
+    wl.Layer("n72_k5", 2, 2, 3, 72, 5, 0.1, 101),         # tiles of a 5 * 2^m transform size
 ]
 
 
@@ -386,16 +387,22 @@ def test_transposed_layer_gives_transposed_results(fc):
 EDGE_LAYERS = [
     wl.Layer("n64_k1", 2, 3, 2, 64, 1, 0.1, 61),          # largest transform, k = 1
     wl.Layer("n64_k64", 2, 2, 3, 64, 64, 0.05, 62),       # k = n = 64: one output pixel
-    wl.Layer("n33", 2, 3, 2, 33, 2, 0.1, 63),             # just above 32 -> N = 48
+    wl.Layer("n33", 2, 3, 2, 33, 2, 0.1, 63),             # just above 32 -> N = 40
     wl.Layer("n49", 2, 3, 2, 49, 4, 0.1, 72),             # just above 48 -> N = 64 with a lot of padding
-    wl.Layer("n17_k17", 3, 2, 2, 17, 17, 0.1, 64),        # N = 24, k = n
+    wl.Layer("n17_k17", 3, 2, 2, 17, 17, 0.1, 64),        # N = 20, k = n
     wl.Layer("n25_k25", 3, 2, 2, 25, 25, 0.1, 73),        # N = 32, k = n
     wl.Layer("n48_k48", 2, 2, 3, 48, 48, 0.05, 74),       # N = 48 with no padding, k = n
     wl.Layer("n24_k2", 3, 4, 5, 24, 2, 0.1, 75),          # N = 24 with no padding
     wl.Layer("n12_k12", 5, 3, 2, 12, 12, 0.1, 76),        # N = 12, k = n
     wl.Layer("n11_k4", 35, 3, 2, 11, 4, 0.1, 77),         # N = 12, 105 / 70 maps: ragged tiles of 32
-    wl.Layer("n40_k9", 2, 9, 4, 40, 9, 0.05, 78),         # N = 48, w in the smallest extent class
+    wl.Layer("n40_k9", 2, 9, 4, 40, 9, 0.05, 78),         # N = 40 with no padding, w in the smallest extent class
     wl.Layer("n44_k20", 2, 3, 9, 44, 20, 0.05, 79),       # N = 48, middle extent classes
+    wl.Layer("n34_k5", 3, 5, 4, 34, 5, 0.05, 86),         # the size Sec. 4 names as padded to 64: N = 40 here
+    wl.Layer("n37_k13", 19, 3, 2, 37, 13, 0.05, 87),      # N = 40, middle extent classes, ragged tiles of 16 maps
+    wl.Layer("n41_k3", 2, 3, 2, 41, 3, 0.1, 88),          # just above 40 -> N = 48
+    wl.Layer("n18_k3", 35, 3, 2, 18, 3, 0.1, 89),         # N = 20, 105 / 70 maps: ragged tiles of 32
+    wl.Layer("n20_k20", 3, 2, 3, 20, 20, 0.1, 90),        # N = 20 with no padding, k = n
+    wl.Layer("n21_k6", 3, 4, 5, 21, 6, 0.1, 100),         # just above 20 -> N = 24
     wl.Layer("n8_k3", 5, 3, 4, 8, 3, 0.1, 65),            # N = 8
     wl.Layer("n5_k2", 3, 2, 2, 5, 2, 0.1, 66),            # n below the smallest transform
     wl.Layer("n1", 4, 3, 2, 1, 1, 0.1, 67),               # 1x1 maps
@@ -517,7 +524,7 @@ def test_stage_calls_compose_to_a_pass(fc):
     check(y.cpu().numpy(), direct.fprop(x, w), "stages fprop")
 
 
-@pytest.mark.parametrize("n,N_expected", [(20, 24), (28, 32), (11, 12), (40, 48), (52, 64)])
+@pytest.mark.parametrize("n,N_expected", [(20, 20), (21, 24), (28, 32), (11, 12), (34, 40), (44, 48), (52, 64)])
 def test_spectrum_stage_against_fft2(fc, n, N_expected):
     """Forward stage alone: slot contents equal the half spectrum of the zero-padded maps."""
     layer = wl.Layer("stage", 3, 5, 4, n, 6, 0.1, 31)
