@@ -206,8 +206,10 @@ def measure(layer, args, inputs=None):
     B = plan.num_bins
     algo_flops = plan.contraction_flops * 8.0 / 6.0   # = 8 S f f' B for a layer that is not tiled
     roofline = None
-    if all(gemm_live[n] for n in gemm_names):
-        gemm_ms = float(np.mean([gemm_live[n] for n in gemm_names]))
+    # (a layer with f <= 4 has no contraction launch in fprop: its product is formed inside the inverse transform)
+    timed = [n for n in gemm_names if gemm_live[n]]
+    if timed:
+        gemm_ms = float(np.mean([gemm_live[n] for n in timed]))
         achieved = algo_flops / (gemm_ms * 1e-3) / 1e12
         issued = plan.contraction_flops / (gemm_ms * 1e-3) / 1e12
         traffic = None
@@ -216,7 +218,8 @@ def measure(layer, args, inputs=None):
             traffic = json.load(open(tpath)).get("cgemm_hbm_bytes_per_launch")
         roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                     "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": traffic,
-                    "kernel": "bin_cgemm_kernel (mean of the fprop/bprop/accGrad launches)",
+                    "kernel": ("bin_cgemm_kernel" if layer.f > 4 else "skinny_bprop_kernel, skinny_accgrad_kernel") +
+                              " (mean of the " + "/".join(n[6:] for n in timed) + " launches)",
                     "avg_launch_ms": gemm_ms, "launches_timed": gemm_live_launches,
                     "timing": f"HIP events around the contraction launches of every {EVENT_EVERY}th timed step",
                     "flops_per_launch": algo_flops,
@@ -295,7 +298,7 @@ def write_report(args):
              "|---|---|---|---|---|---|---|---|---|---|"]
     for layer, r in zip(layers, recs):
         st, ps = r["stages"], r["passes"]
-        pct = lambda n: f"{100 * st[n].get('frac_hbm_peak', st[n].get('frac_mfma_peak', 0)):.0f}"
+        pct = lambda n: f"{100 * st[n].get('frac_hbm_peak', st[n].get('frac_mfma_peak', 0)):.0f}" if n in st else "-"
         lines.append(f"| {layer.name} | {layer.S},{layer.f},{layer.fo},{layer.n},{layer.k} | {r['ms_per_step']:.3f} | "
                      f"{r['memory_efficient_mode']['ms_per_step']:.3f} | {r['value'] / 1e3:.1f} | " +
                      " | ".join(f"{ps[p]['warm_ms']:.3f} / {ps[p]['cold_ms']:.3f}" for p in ("fprop", "bprop", "accgrad")) +

@@ -13,8 +13,11 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(_HERE), "include")
 
+# translation units of the library; they share no device code and compile side by side
+HIP_SOURCES = ["fftconv.hip", "fft_fused.hip"]
+
 HIPCC_FLAGS = [
-    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
+    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
     # keep the compiler from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
@@ -41,12 +44,22 @@ def _sources_newer(target: str) -> bool:
 
 
 def build_library(force: bool = True, extra_flags=()) -> str:
-    """Compile csrc/fftconv.hip for gfx950 into libfftconv.so."""
+    """Compile the HIP sources under csrc/ for gfx950 and link them into libfftconv.so."""
     out = lib_path()
     if force or _sources_newer(out):
         hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-        cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, "-I", INCLUDE, "-o", out, os.path.join(CSRC, "fftconv.hip")]
-        subprocess.run(cmd, check=True)
+        objdir = os.path.join(_HERE, "_build")
+        os.makedirs(objdir, exist_ok=True)
+        jobs = []
+        for src in HIP_SOURCES:
+            obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
+            cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, "-I", INCLUDE, "-c", "-o", obj, os.path.join(CSRC, src)]
+            jobs.append((obj, cmd, subprocess.Popen(cmd)))
+        failed = [cmd for _, cmd, proc in jobs if proc.wait() != 0]
+        if failed:
+            raise subprocess.CalledProcessError(1, failed[0])
+        link = [hipcc, "--offload-arch=gfx950", "-fPIC", "-shared", "-o", out, *[obj for obj, _, _ in jobs]]
+        subprocess.run(link, check=True)
     return out
 
 

@@ -48,7 +48,7 @@ static void replay_forward(const FwdArgs &a)
     }
 }
 
-template <class G, bool TILED = false>
+template <class G, bool TILED = false, int FUSE = 0>
 static void replay_inverse(const InvArgs &a, bool acc)
 {
     std::vector<cf> lds(G::LDS_ELEMS);
@@ -58,7 +58,7 @@ static void replay_inverse(const InvArgs &a, bool acc)
         for (int tid = 0; tid < G::THREADS; ++tid) {
             std::memset(z[tid].data(), 0xFF, sizeof(cf) * G::N);
             std::memset(v[tid].data(), 0xFF, sizeof(cf) * G::N);
-            inv_x_compute<G>(tid % G::XTHREADS, blk, tid / G::XTHREADS, a, regs<G>(v, tid));
+            inv_x_compute<G, FUSE>(tid % G::XTHREADS, blk, tid / G::XTHREADS, a, regs<G>(v, tid));
         }
         static_for<0, G::ROUNDS>([&](auto ri) {
             constexpr int r = decltype(ri)::value;
@@ -128,6 +128,23 @@ int replay_ifft2d_c2r_tiled(int N, const float *spec, float *dst, int M, int cro
     const int T = maps_per_block(N);
 #define X(n_, t_, nx_) \
     if constexpr (n_ == nx_) { if (N == n_ && T == t_) { replay_inverse<TileGeom<n_, t_, nx_, rounds_for(n_)>, true>(a, false); return 0; } }
+    FFTCONV_FOR_EACH_GEOM(X)
+#undef X
+    return 1;
+}
+
+// Fused fprop of a layer with F = 3 input maps (full-extent geometries only): the bins of output
+// map m = s * fo + j are formed from xs [B][Mx] and wsp [B][Mw] instead of being read.
+int replay_ifft2d_c2r_crop_fused3(int N, const float *xs, const float *wsp, float *dst, int M, int fo, int Mx, int Mw,
+                                  int crop_y, int crop_x)
+{
+    InvArgs a{nullptr, dst, M, crop_y, crop_x, 1.0f / (float)(N * N)};
+    a.xs = reinterpret_cast<const cf *>(xs);
+    a.wsp = reinterpret_cast<const cf *>(wsp);
+    a.fo = fo; a.Mx = Mx; a.Mw = Mw;
+    const int T = maps_per_block(N);
+#define X(n_, t_, nx_) \
+    if constexpr (n_ == nx_) { if (N == n_ && T == t_) { replay_inverse<TileGeom<n_, t_, nx_, rounds_for(n_)>, false, 3>(a, false); return 0; } }
     FFTCONV_FOR_EACH_GEOM(X)
 #undef X
     return 1;

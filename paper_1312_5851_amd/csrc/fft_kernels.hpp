@@ -77,6 +77,11 @@ struct InvArgs {
     int c0_y, c0_x;       // tiled kernels: first stored row / column of the transform's output
     Tiling t;             // read by the tiled kernels only
     int flip;             // untiled kernels: store every window rotated by 180 degrees
+    // Read by the fused kernels only (fprop of a layer with very few input maps): instead of
+    // reading `spec`, bin c of output map m = s * fo + j is formed on the fly as
+    // sum_i xs[c * Mx + s * F + i] * conj(wsp[c * Mw + j * F + i]), the product of Sec. 2.2.
+    const cf *xs, *wsp;   // spectra of x [B][Mx] and of w [B][Mw]
+    int fo, Mx, Mw;       // output maps per sample; transforms in xs (samples x F) and in wsp (fo x F)
 };
 
 struct TileOrigin {
@@ -272,7 +277,8 @@ FC_HD void fwd_x_finish(int xt, int blk, int round, const FwdArgs &a, cf (&v)[G:
 
 // x-phase, step 1: lane xt = (slot, map) of its team loads a row of one map's spectrum and
 // inverse-transforms it along kx.  Leaves the bit-reversed transform in v.
-template <class G>
+// FUSE = F > 0: the bins are not read but formed from the spectra of x and w (see InvArgs).
+template <class G, int FUSE = 0>
 FC_HD void inv_x_compute(int xt, int blk, int round, const InvArgs &a, cf (&v)[G::N])
 {
     constexpr int N = G::N, NX = G::NX;
@@ -281,12 +287,38 @@ FC_HD void inv_x_compute(int xt, int blk, int round, const InvArgs &a, cf (&v)[G
     const int mg = blk * G::T + m;
     // Lanes beyond the last map read the last map's bins (valid memory) instead of
     // branching around each load; what they compute is never stored.
-    const cf *in = a.spec + (mg < a.M ? mg : a.M - 1);
+    const int mc = mg < a.M ? mg : a.M - 1;
     const size_t M = (size_t)a.M;
+    const cf *src = nullptr, *xp = nullptr, *wp = nullptr;
+    if constexpr (FUSE > 0) {
+        xp = a.xs + (size_t)(mc / a.fo) * FUSE;
+        wp = a.wsp + (size_t)(mc % a.fo) * FUSE;
+    } else {
+        src = a.spec + mc;
+    }
+    struct Bins {
+        const cf *src, *xp, *wp;
+        size_t M, Mx, Mw;
+        FC_HD cf operator[](size_t c) const   // stored bin c of the lane's map
+        {
+            if constexpr (FUSE == 0) {
+                return src[c * M];
+            } else {
+                const cf *x = xp + c * Mx, *w = wp + c * Mw;
+                cf acc = mk(x[0].x * w[0].x + x[0].y * w[0].y, x[0].y * w[0].x - x[0].x * w[0].y);   // x conj(w)
+                static_for<1, FUSE>([&](auto ii) {
+                    constexpr int i = decltype(ii)::value;
+                    acc = mk(acc.x + (x[i].x * w[i].x + x[i].y * w[i].y), acc.y + (x[i].y * w[i].x - x[i].x * w[i].y));
+                });
+                return acc;
+            }
+        }
+    };
+    const Bins in{src, xp, wp, M, (size_t)a.Mx, (size_t)a.Mw};
     if (r != 0) {
         static_for<0, N>([&](auto ki) {
             constexpr int kx = decltype(ki)::value;
-            v[kx] = in[((size_t)(N + 2) + (size_t)(r - 1) * N + kx) * M];
+            v[kx] = in[(size_t)(N + 2) + (size_t)(r - 1) * N + kx];
         });
     } else {
         // rows ky = 0 and ky = N/2 are Hermitian in kx, so their inverse transforms are
@@ -295,8 +327,8 @@ FC_HD void inv_x_compute(int xt, int blk, int round, const InvArgs &a, cf (&v)[G
         cf y0[N / 2 + 1], yh[N / 2 + 1];
         static_for<0, N / 2 + 1>([&](auto ki) {
             constexpr int kx = decltype(ki)::value;
-            y0[kx] = in[(size_t)kx * M];
-            yh[kx] = in[(size_t)(N / 2 + 1 + kx) * M];
+            y0[kx] = in[(size_t)kx];
+            yh[kx] = in[(size_t)(N / 2 + 1 + kx)];
         });
         static_for<0, N / 2 + 1>([&](auto ki) {
             constexpr int kx = decltype(ki)::value;
@@ -462,7 +494,7 @@ __global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void fft2d_r2c_kerne
     fwd_x_finish<G>(xt, blk, team, a, v);
 }
 
-template <class G, bool ACC>   // ACC: dst += result instead of dst = result
+template <class G, bool ACC, int FUSE = 0>   // ACC: dst += result instead of dst = result
 __global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void ifft2d_c2r_crop_kernel(InvArgs a)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -470,7 +502,7 @@ __global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void ifft2d_c2r_crop
     const int tid = (int)threadIdx.x, blk = xcd_contiguous_block();
     const int team = tid / G::XTHREADS, xt = tid % G::XTHREADS;
     cf z[G::N], v[G::N];
-    inv_x_compute<G>(xt, blk, team, a, v);
+    inv_x_compute<G, FUSE>(xt, blk, team, a, v);
     static_for<0, G::ROUNDS>([&](auto ri) {
         constexpr int r = decltype(ri)::value;
         if constexpr (r > 0) __syncthreads();   // every lane has gathered the previous rows
@@ -482,7 +514,7 @@ __global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void ifft2d_c2r_crop
 }
 
 // Same schedule, output scattered to tiles of a larger image (never accumulating).
-template <class G>
+template <class G, int FUSE = 0>
 __global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void ifft2d_c2r_tiled_kernel(InvArgs a)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -490,7 +522,7 @@ __global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void ifft2d_c2r_tile
     const int tid = (int)threadIdx.x, blk = xcd_contiguous_block();
     const int team = tid / G::XTHREADS, xt = tid % G::XTHREADS;
     cf z[G::N], v[G::N];
-    inv_x_compute<G>(xt, blk, team, a, v);
+    inv_x_compute<G, FUSE>(xt, blk, team, a, v);
     static_for<0, G::ROUNDS>([&](auto ri) {
         constexpr int r = decltype(ri)::value;
         if constexpr (r > 0) __syncthreads();

@@ -13,6 +13,7 @@
 #include "../../include/fftconv.h"
 #include "contract_kernels.hpp"
 #include "fft_dispatch.hpp"
+#include "fft_fused.hpp"
 #include "skinny_kernels.hpp"
 
 using namespace fftconv;
@@ -33,7 +34,6 @@ struct ProfileRecord {
 // ------------------------------------------------------------------ kernel tables
 
 typedef void (*FwdKernel)(FwdArgs);
-typedef void (*InvKernel)(InvArgs);
 typedef void (*GemmKernel)(GemmArgs);
 
 struct FftEntry {
@@ -360,7 +360,7 @@ int launch_contract(fftconv_plan_t p, int pass, void *ws, hipStream_t stream)
     return timer.finish();
 }
 
-int launch_inverse(fftconv_plan_t p, int pass, float *dst, void *ws, hipStream_t stream, int accumulate)
+int launch_inverse(fftconv_plan_t p, int pass, float *dst, void *ws, hipStream_t stream, int accumulate, bool fused = false)
 {
     long M;
     InvArgs a{};
@@ -384,6 +384,13 @@ int launch_inverse(fftconv_plan_t p, int pass, float *dst, void *ws, hipStream_t
     const FftEntry *e = find_fft(p->N, use_tiles ? p->N : (a.crop_y > a.crop_x ? a.crop_y : a.crop_x));
     if (!e || (use_tiles && !e->inv_tiled)) return FFTCONV_EUNSUPPORTED;
     InvKernel kernel = use_tiles ? e->inv_tiled : (accumulate ? e->inv_acc : e->inv);
+    if (fused) {
+        kernel = fused_inverse_kernel(e->N, e->T, e->NX, d.f, use_tiles);
+        if (!kernel) return FFTCONV_EUNSUPPORTED;
+        a.xs = slot_ptr(p, ws, FFTCONV_SPEC_X);
+        a.wsp = slot_ptr(p, ws, FFTCONV_SPEC_W);
+        a.fo = d.fo; a.Mx = (int)p->maps_x; a.Mw = (int)p->maps_w;
+    }
     if (int rc = allow_lds(kernel, e->lds_bytes)) return rc;
     a.spec = slot_ptr(p, ws, result_slot(p, pass));
     a.dst = dst;
@@ -396,6 +403,18 @@ int launch_inverse(fftconv_plan_t p, int pass, float *dst, void *ws, hipStream_t
     hipLaunchKernelGGL(kernel, dim3(blocks), dim3(e->threads), e->lds_bytes, stream, a);
     if (int rc = check_launch()) return rc;
     return timer.finish();
+}
+
+// fprop of a layer with at most four input maps: the products are formed inside the inverse
+// transform (nullptr: not applicable, or no such kernel for this geometry).
+InvKernel fused_fprop_kernel(fftconv_plan_t p, int pass, int accumulate)
+{
+    if (pass != FFTCONV_FPROP || accumulate || p->d.f > kMaxFusedMaps || std::getenv("FFTCONV_NO_FUSED")) return nullptr;
+    const bool use_tiles = tiled(p);
+    const int crop_y = use_tiles ? p->Ly : p->noh, crop_x = use_tiles ? p->Lx : p->now;
+    const FftEntry *e = find_fft(p->N, use_tiles ? p->N : (crop_y > crop_x ? crop_y : crop_x));
+    if (!e) return nullptr;
+    return fused_inverse_kernel(e->N, e->T, e->NX, p->d.f, use_tiles);
 }
 
 int run_pass(fftconv_plan_t p, int pass, const float *src_a, const float *src_b, float *dst, void *ws, void *stream,
@@ -411,8 +430,10 @@ int run_pass(fftconv_plan_t p, int pass, const float *src_a, const float *src_b,
         if (int rc = launch_forward(p, sa, src_a, ws, s)) return rc;
     if ((p->valid & (unsigned)sb) == 0)
         if (int rc = launch_forward(p, sb, src_b, ws, s)) return rc;
-    if (int rc = launch_contract(p, pass, ws, s)) return rc;
-    const int rc = launch_inverse(p, pass, dst, ws, s, accumulate);
+    const bool fused = fused_fprop_kernel(p, pass, accumulate) != nullptr;
+    if (!fused)
+        if (int rc = launch_contract(p, pass, ws, s)) return rc;
+    const int rc = launch_inverse(p, pass, dst, ws, s, accumulate, fused);
     if (recompute_mode(p)) p->valid = 0;
     return rc;
 }

@@ -266,3 +266,28 @@ def reference_spectrum_rect(maps, N):
     pad = np.zeros((M, N, N)); pad[:, :ey, :ex] = maps
     ky, kx = stored_bins(N)
     return np.fft.fft2(pad)[:, ky, kx].T
+
+
+@pytest.mark.parametrize("N,k", [(16, 3), (20, 2), (40, 5), (64, 9)])
+def test_fused_product_inverse_is_the_valid_correlation(replay, N, k):
+    """fprop with three input maps: the inverse transform forms its bins from the spectra of x and w
+    (Sec. 2.2) and must leave the valid cross-correlation, summed over the input maps, written out
+    here as plain sums.  Five output maps per sample, so that a group of maps spans several samples."""
+    rng = np.random.default_rng(500 + N)
+    Sn, f, fo = 7, 3, 5
+    x = rng.uniform(-1, 1, (Sn, f, N, N)).astype(np.float32)
+    w = rng.normal(0, 0.3, (fo, f, k, k)).astype(np.float32)
+    no = N - k + 1
+    ref = np.zeros((Sn, fo, no, no))
+    for a in range(k):
+        for b in range(k):
+            ref += np.einsum("sipq,ji->sjpq", x[:, :, a:a + no, b:b + no].astype(np.float64), w[:, :, a, b].astype(np.float64))
+    def planar(spec):
+        return np.ascontiguousarray(np.stack([spec.real, spec.imag], -1).astype(np.float32))
+    xs = planar(reference_spectrum_rect(x.reshape(-1, N, N), N))
+    ws = planar(reference_spectrum_rect(w.reshape(-1, k, k), N))
+    M = Sn * fo
+    dst = np.full((M, no, no), np.nan, np.float32)
+    assert replay.replay_ifft2d_c2r_crop_fused3(N, xs.ctypes.data_as(FP), ws.ctypes.data_as(FP), dst.ctypes.data_as(FP),
+                                               M, fo, Sn * f, fo * f, no, no) == 0
+    assert np.abs(dst.reshape(ref.shape) - ref).max() <= 2e-5 * np.abs(ref).max(), N

@@ -335,15 +335,17 @@ def test_random_layers_parity(fc, seed):
                          ids=lambda l: l.name)
 def test_few_input_maps_both_contraction_paths(fc, layer, monkeypatch):
     """Layers with f <= 4 run the contractions of accGrad and bprop through streaming kernels on the
-    vector ALU; the matrix-core kernel must give the same results (to rounding) on the same layers."""
+    vector ALU and form fprop's products inside the inverse transform; the matrix-core kernel must
+    give the same results (to rounding) on the same layers."""
     print(f"\ncase {layer}", flush=True)
     x, w, g = wl.make_inputs(layer)
     ref = (direct.fprop(x, w), direct.bprop(g, w, layer.n), direct.accgrad(g, x, layer.k))
     for env in (None, "1"):
-        if env:
+        if env:   # no streaming kernels, and fprop's product not fused into the inverse transform
             monkeypatch.setenv("FFTCONV_NO_SKINNY", env)
+            monkeypatch.setenv("FFTCONV_NO_FUSED", env)
         plan, y, dx, dw = run_three(fc, layer, x, w, g)
-        tag = "matrix cores" if env else "streaming"
+        tag = "matrix cores" if env else "streaming / fused"
         check(y, ref[0], f"{layer.name} fprop ({tag})")
         check(dx, ref[1], f"{layer.name} bprop ({tag})")
         check(dw, ref[2], f"{layer.name} accgrad ({tag})")
