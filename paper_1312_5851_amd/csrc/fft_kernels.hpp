@@ -82,6 +82,7 @@ struct InvArgs {
     // sum_i xs[c * Mx + s * F + i] * conj(wsp[c * Mw + j * F + i]), the product of Sec. 2.2.
     const cf *xs, *wsp;   // spectra of x [B][Mx] and of w [B][Mw]
     int fo, Mx, Mw;       // output maps per sample; transforms in xs (samples x F) and in wsp (fo x F)
+    int groups_per_sample;   // fo / T if that is exact, else 0 (see fused_block_order)
 };
 
 struct TileOrigin {
@@ -472,6 +473,21 @@ __device__ __forceinline__ int xcd_contiguous_block()
     return xcd * per + (xcd < rem ? xcd : rem) + slot;
 }
 
+// Order of the map groups in a fused kernel.  A group reads its sample's part of xs and its
+// T output maps' part of wsp, every bin of both.  Walking the groups sample by sample makes the
+// groups that run together cover all of wsp (4.7 MB for f = 3, f' = 96, N = 64, more than an
+// XCD's 4 MB of L2, which then misses all the time: measured 129 MB fetched per launch for 11 MB
+// of operands).  Inside chunks of 16 samples the groups are therefore walked output-map range
+// first, so that the groups in flight share one or two ranges of wsp and 16 samples of xs.
+__device__ __forceinline__ int fused_block_order(int blk, int groups_per_sample)
+{
+    if (groups_per_sample <= 1) return blk;
+    const int chunk = 16 * groups_per_sample;
+    const int c = blk / chunk, r = blk % chunk;
+    if ((c + 1) * chunk > (int)gridDim.x) return blk;   // a ragged last chunk keeps its order
+    return c * chunk + (r % 16) * groups_per_sample + r / 16;
+}
+
 // Device kernels.  Launch with G::THREADS threads, ceil(M / G::T) blocks and G::LDS_BYTES
 // of dynamic LDS.
 // (the second launch bound is the number of waves per SIMD the register budget must allow)
@@ -499,7 +515,8 @@ __global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void ifft2d_c2r_crop
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     cf *lds = reinterpret_cast<cf *>(lds_raw);
-    const int tid = (int)threadIdx.x, blk = xcd_contiguous_block();
+    const int tid = (int)threadIdx.x;
+    const int blk = FUSE > 0 ? fused_block_order(xcd_contiguous_block(), a.groups_per_sample) : xcd_contiguous_block();
     const int team = tid / G::XTHREADS, xt = tid % G::XTHREADS;
     cf z[G::N], v[G::N];
     inv_x_compute<G, FUSE>(xt, blk, team, a, v);
@@ -519,7 +536,8 @@ __global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void ifft2d_c2r_tile
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     cf *lds = reinterpret_cast<cf *>(lds_raw);
-    const int tid = (int)threadIdx.x, blk = xcd_contiguous_block();
+    const int tid = (int)threadIdx.x;
+    const int blk = FUSE > 0 ? fused_block_order(xcd_contiguous_block(), a.groups_per_sample) : xcd_contiguous_block();
     const int team = tid / G::XTHREADS, xt = tid % G::XTHREADS;
     cf z[G::N], v[G::N];
     inv_x_compute<G, FUSE>(xt, blk, team, a, v);

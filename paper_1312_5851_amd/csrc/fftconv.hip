@@ -390,6 +390,7 @@ int launch_inverse(fftconv_plan_t p, int pass, float *dst, void *ws, hipStream_t
         a.xs = slot_ptr(p, ws, FFTCONV_SPEC_X);
         a.wsp = slot_ptr(p, ws, FFTCONV_SPEC_W);
         a.fo = d.fo; a.Mx = (int)p->maps_x; a.Mw = (int)p->maps_w;
+        a.groups_per_sample = (d.fo % e->T == 0 && !std::getenv("FFTCONV_NO_FUSED_ORDER")) ? d.fo / e->T : 0;
     }
     if (int rc = allow_lds(kernel, e->lds_bytes)) return rc;
     a.spec = slot_ptr(p, ws, result_slot(p, pass));
