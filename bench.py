@@ -251,6 +251,10 @@ def measure(layer, args, inputs=None):
         if name in ext:
             images, e, transforms = ext[name]
             nbytes = images * 4 * e * e + transforms * 8 * B
+            if name == "ifft_y" and stages.get("cgemm_fprop") is None:
+                # fprop of a layer with f <= 4: no output spectrum exists, the kernel reads the spectra of x and w
+                nbytes = images * 4 * e * e + 8 * B * (plan.slot_maps(fc.SPEC_X) + plan.slot_maps(fc.SPEC_W))
+                rec["fused_product"] = True
             rec["algorithmic_bytes"] = nbytes
             rec["GBps"] = nbytes / (ms * 1e-3) / 1e9
             rec["frac_hbm_peak"] = rec["GBps"] / PEAK_HBM_GBS

@@ -28,6 +28,14 @@
  * errors; on an argument error nothing is launched.
  *
  * A plan is not thread-safe; use one plan per host thread / stream.
+ *
+ * Environment switches, read at every call, for measurements and tests (results are the same
+ * up to rounding order): FFTCONV_GEMM_TILE=0..7 forces a tile shape of the contraction kernel;
+ * FFTCONV_NO_XCD_REMAP, FFTCONV_NO_FULL_TILES select its plainer block numbering / its guarded
+ * loads; FFTCONV_NO_SKINNY sends bprop and accGrad of layers with f <= 4 through the
+ * matrix-core kernel instead of the streaming ones; FFTCONV_NO_FUSED makes fprop of such
+ * layers store and re-read the product spectrum instead of forming it inside the inverse
+ * transform, FFTCONV_NO_FUSED_ORDER keeps that kernel's plain block order.
  */
 #ifndef FFTCONV_H
 #define FFTCONV_H
