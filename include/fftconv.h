@@ -35,7 +35,8 @@
  * loads; FFTCONV_NO_SKINNY sends bprop and accGrad of layers with f <= 4 through the
  * matrix-core kernel instead of the streaming ones; FFTCONV_NO_FUSED makes fprop of such
  * layers store and re-read the product spectrum instead of forming it inside the inverse
- * transform, FFTCONV_NO_FUSED_ORDER keeps that kernel's plain block order.
+ * transform (which needs fo to be a multiple of the 16 to 64 maps a workgroup transforms),
+ * FFTCONV_NO_FUSED_ORDER keeps that kernel's plain block order.
  */
 #ifndef FFTCONV_H
 #define FFTCONV_H

@@ -58,7 +58,14 @@ static void replay_inverse(const InvArgs &a, bool acc)
         for (int tid = 0; tid < G::THREADS; ++tid) {
             std::memset(z[tid].data(), 0xFF, sizeof(cf) * G::N);
             std::memset(v[tid].data(), 0xFF, sizeof(cf) * G::N);
-            inv_x_compute<G, FUSE>(tid % G::XTHREADS, blk, tid / G::XTHREADS, a, regs<G>(v, tid));
+        }
+        if constexpr (FUSE > 0) {
+            std::memset(lds.data(), 0xFF, sizeof(cf) * lds.size());
+            for (int tid = 0; tid < G::THREADS; ++tid) fused_stage_x<G, FUSE>(tid, blk, a, lds.data());
+        }
+        for (int tid = 0; tid < G::THREADS; ++tid) {
+            inv_x_load<G, FUSE>(tid % G::XTHREADS, blk, tid / G::XTHREADS, a, lds.data(), regs<G>(v, tid));
+            inv_x_transform<G>(regs<G>(v, tid));
         }
         static_for<0, G::ROUNDS>([&](auto ri) {
             constexpr int r = decltype(ri)::value;
@@ -134,10 +141,12 @@ int replay_ifft2d_c2r_tiled(int N, const float *spec, float *dst, int M, int cro
 }
 
 // Fused fprop of a layer with F = 3 input maps (full-extent geometries only): the bins of output
-// map m = s * fo + j are formed from xs [B][Mx] and wsp [B][Mw] instead of being read.
+// map m = s * fo + j are formed from xs [B][Mx] and wsp [B][Mw] instead of being read.  fo must be
+// a multiple of the geometry's maps per workgroup.
 int replay_ifft2d_c2r_crop_fused3(int N, const float *xs, const float *wsp, float *dst, int M, int fo, int Mx, int Mw,
                                   int crop_y, int crop_x)
 {
+    if (fo % maps_per_block(N) != 0) return 2;
     InvArgs a{nullptr, dst, M, crop_y, crop_x, 1.0f / (float)(N * N)};
     a.xs = reinterpret_cast<const cf *>(xs);
     a.wsp = reinterpret_cast<const cf *>(wsp);

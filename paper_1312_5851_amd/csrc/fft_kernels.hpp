@@ -80,9 +80,11 @@ struct InvArgs {
     // Read by the fused kernels only (fprop of a layer with very few input maps): instead of
     // reading `spec`, bin c of output map m = s * fo + j is formed on the fly as
     // sum_i xs[c * Mx + s * F + i] * conj(wsp[c * Mw + j * F + i]), the product of Sec. 2.2.
+    // These kernels need fo to be a multiple of T (the T maps of a workgroup then share a sample)
+    // and F * B complex numbers to fit the workgroup's LDS buffer.
     const cf *xs, *wsp;   // spectra of x [B][Mx] and of w [B][Mw]
     int fo, Mx, Mw;       // output maps per sample; transforms in xs (samples x F) and in wsp (fo x F)
-    int groups_per_sample;   // fo / T if that is exact, else 0 (see fused_block_order)
+    int groups_per_sample;   // fo / T, or 0 to keep the plain order of the map groups (see fused_block_order)
 };
 
 struct TileOrigin {
@@ -276,11 +278,35 @@ FC_HD void fwd_x_finish(int xt, int blk, int round, const FwdArgs &a, cf (&v)[G:
 
 // ------------------------------------------------------------------ inverse
 
-// x-phase, step 1: lane xt = (slot, map) of its team loads a row of one map's spectrum and
-// inverse-transforms it along kx.  Leaves the bit-reversed transform in v.
-// FUSE = F > 0: the bins are not read but formed from the spectra of x and w (see InvArgs).
+// Fused kernels, step 0: copy the part of xs that belongs to the workgroup's sample,
+// xs[c][s * F + i] for every stored bin c, to xl[c * F + i] in LDS.  Every lane would
+// otherwise load these values itself, T times over (measured on S=128, f=3, f'=96, N=64:
+// 99 -> 91 us for the kernel).
+template <class G, int FUSE>
+FC_HD void fused_stage_x(int tid, int blk, const InvArgs &a, cf *xl)
+{
+    constexpr int B = G::N * G::N / 2 + 2;
+    const cf *xp = a.xs + (size_t)((blk * G::T) / a.fo) * FUSE;
+    cf tmp[(B * FUSE + G::THREADS - 1) / G::THREADS];
+    static_for<0, (B * FUSE + G::THREADS - 1) / G::THREADS>([&](auto pi) {
+        constexpr int p = decltype(pi)::value;
+        const int e = p * G::THREADS + tid;
+        const int ec = e < B * FUSE ? e : B * FUSE - 1;
+        tmp[p] = xp[(size_t)(ec / FUSE) * a.Mx + ec % FUSE];
+    });
+    static_for<0, (B * FUSE + G::THREADS - 1) / G::THREADS>([&](auto pi) {
+        constexpr int p = decltype(pi)::value;
+        const int e = p * G::THREADS + tid;
+        if (e < B * FUSE) xl[e] = tmp[p];
+    });
+}
+
+// x-phase, step 1: lane xt = (slot, map) of its team loads a row of one map's spectrum
+// (natural order in v).
+// FUSE = F > 0: the bins are not read but formed from the copy of the sample's x spectrum that
+// fused_stage_x made at xl and from the spectrum of w (see InvArgs).
 template <class G, int FUSE = 0>
-FC_HD void inv_x_compute(int xt, int blk, int round, const InvArgs &a, cf (&v)[G::N])
+FC_HD void inv_x_load(int xt, int blk, int round, const InvArgs &a, const cf *xl, cf (&v)[G::N])
 {
     constexpr int N = G::N, NX = G::NX;
     const int slot = xt / G::T, m = xt % G::T;
@@ -292,20 +318,20 @@ FC_HD void inv_x_compute(int xt, int blk, int round, const InvArgs &a, cf (&v)[G
     const size_t M = (size_t)a.M;
     const cf *src = nullptr, *xp = nullptr, *wp = nullptr;
     if constexpr (FUSE > 0) {
-        xp = a.xs + (size_t)(mc / a.fo) * FUSE;
+        xp = xl;
         wp = a.wsp + (size_t)(mc % a.fo) * FUSE;
     } else {
         src = a.spec + mc;
     }
     struct Bins {
         const cf *src, *xp, *wp;
-        size_t M, Mx, Mw;
+        size_t M, Mw;
         FC_HD cf operator[](size_t c) const   // stored bin c of the lane's map
         {
             if constexpr (FUSE == 0) {
                 return src[c * M];
             } else {
-                const cf *x = xp + c * Mx, *w = wp + c * Mw;
+                const cf *x = xp + c * FUSE, *w = wp + c * Mw;
                 cf acc = mk(x[0].x * w[0].x + x[0].y * w[0].y, x[0].y * w[0].x - x[0].x * w[0].y);   // x conj(w)
                 static_for<1, FUSE>([&](auto ii) {
                     constexpr int i = decltype(ii)::value;
@@ -315,7 +341,7 @@ FC_HD void inv_x_compute(int xt, int blk, int round, const InvArgs &a, cf (&v)[G
             }
         }
     };
-    const Bins in{src, xp, wp, M, (size_t)a.Mx, (size_t)a.Mw};
+    const Bins in{src, xp, wp, M, (size_t)a.Mw};
     if (r != 0) {
         static_for<0, N>([&](auto ki) {
             constexpr int kx = decltype(ki)::value;
@@ -337,8 +363,18 @@ FC_HD void inv_x_compute(int xt, int blk, int round, const InvArgs &a, cf (&v)[G
             if constexpr (kx > 0 && kx < N / 2)
                 v[N - kx] = mk(y0[kx].x + yh[kx].y, yh[kx].x - y0[kx].y);        // conj y0 + i conj yh
         });
+        // The two branches end in stores to different elements of v.  Left alone, the compiler merges
+        // them into one store through a selected address, after which those elements live in scratch
+        // memory instead of registers; an empty statement it must keep makes the branch ends differ.
+        asm volatile("");
     }
-    fft_dif<N, true, 0, first_outputs_mask<N>(NX)>(v);
+}
+
+// x-phase, step 1b: inverse transform of the row along kx.  Leaves the bit-reversed transform in v.
+template <class G>
+FC_HD void inv_x_transform(cf (&v)[G::N])
+{
+    fft_dif<G::N, true, 0, first_outputs_mask<G::N>(G::NX)>(v);
 }
 
 // x-phase, step 2: hand the needed columns of the row to LDS.
@@ -457,7 +493,8 @@ FC_HD void inv_y_finish_tiled(int tid, int blk, const InvArgs &a, cf (&z)[G::N])
 // all lanes before the next one, which is what a barrier after each step guarantees.
 // Lane tid belongs to team tid / XTHREADS and is lane xt = tid % XTHREADS of it.
 //   forward: y_compute | per round r: (barrier,) y_write<r>, barrier, team r: x_read | x_finish
-//   inverse: x_compute | per round r: (barrier,) team r: x_write, barrier, y_gather<r> | y_finish
+//   inverse: (fused: stage_x, barrier,) x_load (, barrier) | x_transform |
+//            per round r: (barrier,) team r: x_write, barrier, y_gather<r> | y_finish
 
 #if defined(__HIPCC__)
 // Workgroups are dealt round-robin to the 8 XCDs of an MI355X (each with its own L2).  Renumber
@@ -486,6 +523,21 @@ __device__ __forceinline__ int fused_block_order(int blk, int groups_per_sample)
     const int c = blk / chunk, r = blk % chunk;
     if ((c + 1) * chunk > (int)gridDim.x) return blk;   // a ragged last chunk keeps its order
     return c * chunk + (r % 16) * groups_per_sample + r / 16;
+}
+
+// Steps 0 to 1b of one lane of a device workgroup (the host replay calls the steps one by one).
+template <class G, int FUSE>
+__device__ __forceinline__ void inv_x_phase(int tid, int xt, int blk, int team, const InvArgs &a, cf *lds, cf (&v)[G::N])
+{
+    if constexpr (FUSE > 0) {
+        fused_stage_x<G, FUSE>(tid, blk, a, lds);
+        __syncthreads();
+        inv_x_load<G, FUSE>(xt, blk, team, a, lds, v);
+        __syncthreads();   // the copy has been read: the buffer is free for the hand-over
+    } else {
+        inv_x_load<G, 0>(xt, blk, team, a, nullptr, v);
+    }
+    inv_x_transform<G>(v);
 }
 
 // Device kernels.  Launch with G::THREADS threads, ceil(M / G::T) blocks and G::LDS_BYTES
@@ -519,7 +571,7 @@ __global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void ifft2d_c2r_crop
     const int blk = FUSE > 0 ? fused_block_order(xcd_contiguous_block(), a.groups_per_sample) : xcd_contiguous_block();
     const int team = tid / G::XTHREADS, xt = tid % G::XTHREADS;
     cf z[G::N], v[G::N];
-    inv_x_compute<G, FUSE>(xt, blk, team, a, v);
+    inv_x_phase<G, FUSE>(tid, xt, blk, team, a, lds, v);
     static_for<0, G::ROUNDS>([&](auto ri) {
         constexpr int r = decltype(ri)::value;
         if constexpr (r > 0) __syncthreads();   // every lane has gathered the previous rows
@@ -540,7 +592,7 @@ __global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void ifft2d_c2r_tile
     const int blk = FUSE > 0 ? fused_block_order(xcd_contiguous_block(), a.groups_per_sample) : xcd_contiguous_block();
     const int team = tid / G::XTHREADS, xt = tid % G::XTHREADS;
     cf z[G::N], v[G::N];
-    inv_x_compute<G, FUSE>(xt, blk, team, a, v);
+    inv_x_phase<G, FUSE>(tid, xt, blk, team, a, lds, v);
     static_for<0, G::ROUNDS>([&](auto ri) {
         constexpr int r = decltype(ri)::value;
         if constexpr (r > 0) __syncthreads();

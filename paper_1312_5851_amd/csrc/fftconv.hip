@@ -390,7 +390,7 @@ int launch_inverse(fftconv_plan_t p, int pass, float *dst, void *ws, hipStream_t
         a.xs = slot_ptr(p, ws, FFTCONV_SPEC_X);
         a.wsp = slot_ptr(p, ws, FFTCONV_SPEC_W);
         a.fo = d.fo; a.Mx = (int)p->maps_x; a.Mw = (int)p->maps_w;
-        a.groups_per_sample = (d.fo % e->T == 0 && !std::getenv("FFTCONV_NO_FUSED_ORDER")) ? d.fo / e->T : 0;
+        a.groups_per_sample = std::getenv("FFTCONV_NO_FUSED_ORDER") ? 0 : d.fo / e->T;
     }
     if (int rc = allow_lds(kernel, e->lds_bytes)) return rc;
     a.spec = slot_ptr(p, ws, result_slot(p, pass));
@@ -414,7 +414,8 @@ InvKernel fused_fprop_kernel(fftconv_plan_t p, int pass, int accumulate)
     const bool use_tiles = tiled(p);
     const int crop_y = use_tiles ? p->Ly : p->noh, crop_x = use_tiles ? p->Lx : p->now;
     const FftEntry *e = find_fft(p->N, use_tiles ? p->N : (crop_y > crop_x ? crop_y : crop_x));
-    if (!e) return nullptr;
+    // the maps of a workgroup must share a sample, whose part of the x spectrum must fit the LDS buffer
+    if (!e || p->d.fo % e->T != 0 || (long)p->B * p->d.f * 8 > e->lds_bytes) return nullptr;
     return fused_inverse_kernel(e->N, e->T, e->NX, p->d.f, use_tiles);
 }
 

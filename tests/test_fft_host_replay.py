@@ -268,13 +268,13 @@ def reference_spectrum_rect(maps, N):
     return np.fft.fft2(pad)[:, ky, kx].T
 
 
-@pytest.mark.parametrize("N,k", [(16, 3), (20, 2), (40, 5), (64, 9)])
+@pytest.mark.parametrize("N,k", [(8, 2), (16, 3), (20, 2), (40, 5), (64, 9)])
 def test_fused_product_inverse_is_the_valid_correlation(replay, N, k):
     """fprop with three input maps: the inverse transform forms its bins from the spectra of x and w
     (Sec. 2.2) and must leave the valid cross-correlation, summed over the input maps, written out
-    here as plain sums.  Five output maps per sample, so that a group of maps spans several samples."""
+    here as plain sums.  64 output maps per sample: one to four groups of maps."""
     rng = np.random.default_rng(500 + N)
-    Sn, f, fo = 7, 3, 5
+    Sn, f, fo = 3, 3, 64
     x = rng.uniform(-1, 1, (Sn, f, N, N)).astype(np.float32)
     w = rng.normal(0, 0.3, (fo, f, k, k)).astype(np.float32)
     no = N - k + 1

@@ -331,7 +331,11 @@ def test_random_layers_parity(fc, seed):
 
 @pytest.mark.parametrize("layer", [SMALL_LAYERS[2], SMALL_LAYERS[7], wl.Layer("f3_wide", 5, 3, 70, 20, 5, 0.1, 82),
                                    wl.Layer("f4_tiled", 2, 4, 33, 70, 7, 0.1, 83), wl.Layer("f1", 3, 1, 40, 16, 3, 0.1, 84),
-                                   wl.Layer("f2_rows", 150, 2, 130, 8, 3, 0.1, 85)],
+                                   wl.Layer("f2_rows", 150, 2, 130, 8, 3, 0.1, 85),
+                                   # output maps a multiple of the transform group: fprop's product is fused
+                                   wl.Layer("f3_fo32_n14", 3, 3, 32, 14, 3, 0.1, 102), wl.Layer("f3_fo16_n60", 2, 3, 16, 60, 7, 0.1, 103),
+                                   wl.Layer("f4_fo32_tiled", 2, 4, 32, 70, 7, 0.1, 104), wl.Layer("f1_fo64_n8", 3, 1, 64, 8, 3, 0.1, 105),
+                                   wl.Layer("f2_fo48_n30", 5, 2, 48, 30, 5, 0.1, 106), wl.Layer("f3_fo64_n37", 2, 3, 64, 37, 4, 0.1, 107)],
                          ids=lambda l: l.name)
 def test_few_input_maps_both_contraction_paths(fc, layer, monkeypatch):
     """Layers with f <= 4 run the contractions of accGrad and bprop through streaming kernels on the
