@@ -206,7 +206,8 @@ def measure(layer, args, inputs=None):
     B = plan.num_bins
     algo_flops = plan.contraction_flops * 8.0 / 6.0   # = 8 S f f' B for a layer that is not tiled
     roofline = None
-    # (a layer with f <= 4 has no contraction launch in fprop: its product is formed inside the inverse transform)
+    # (a layer with f <= 4 has no contraction launch in fprop, whose product is formed inside the inverse
+    # transform, and one launch for bprop and accGrad together, timed with the pass that comes first)
     timed = [n for n in gemm_names if gemm_live[n]]
     if timed:
         gemm_ms = float(np.mean([gemm_live[n] for n in timed]))
@@ -218,7 +219,7 @@ def measure(layer, args, inputs=None):
             traffic = json.load(open(tpath)).get("cgemm_hbm_bytes_per_launch")
         roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                     "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": traffic,
-                    "kernel": ("bin_cgemm_kernel" if layer.f > 4 else "skinny_bprop_kernel, skinny_accgrad_kernel") +
+                    "kernel": ("bin_cgemm_kernel" if layer.f > 4 else "streaming kernels for f <= 4 (skinny_kernels.hpp)") +
                               " (mean of the " + "/".join(n[6:] for n in timed) + " launches)",
                     "avg_launch_ms": gemm_ms, "launches_timed": gemm_live_launches,
                     "timing": f"HIP events around the contraction launches of every {EVENT_EVERY}th timed step",

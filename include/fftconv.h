@@ -33,7 +33,8 @@
  * up to rounding order): FFTCONV_GEMM_TILE=0..7 forces a tile shape of the contraction kernel;
  * FFTCONV_NO_XCD_REMAP, FFTCONV_NO_FULL_TILES select its plainer block numbering / its guarded
  * loads; FFTCONV_NO_SKINNY sends bprop and accGrad of layers with f <= 4 through the
- * matrix-core kernel instead of the streaming ones; FFTCONV_NO_FUSED makes fprop of such
+ * matrix-core kernel instead of the streaming ones, FFTCONV_NO_SHARED_PASS keeps their two
+ * products in separate launches instead of one pass over the spectrum of dL/dy; FFTCONV_NO_FUSED makes fprop of such
  * layers store and re-read the product spectrum instead of forming it inside the inverse
  * transform (which needs fo to be a multiple of the 16 to 64 maps a workgroup transforms),
  * FFTCONV_NO_FUSED_ORDER keeps that kernel's plain block order.

@@ -142,6 +142,12 @@ struct fftconv_plan_s {
     long maps_x, maps_w, maps_g, maps_g2, maps_out;   // transforms per slot
     size_t off_x, off_w, off_g, off_g2, off_out, ws_bytes;
     unsigned valid;
+    // Layers with few input maps, spectra cached: bprop and accGrad form both of their result
+    // spectra in one pass over the spectrum of dL/dy (whichever runs first does), side by side in
+    // the OUT slot; `ready` says which of the two is waiting there for its pass (kReady*).
+    bool shared_pass_ok;
+    size_t off_shared_dw;   // byte offset of dWh inside the OUT slot (dXh is at its start)
+    unsigned ready;
     void *last_ws;
     int gemm_tile[3];
     unsigned profiling;   // stage mask
@@ -199,12 +205,23 @@ int bind_workspace(fftconv_plan_t p, void *ws)
     if (!ws || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0) return FFTCONV_EWORKSPACE;
     if (ws != p->last_ws) {
         p->valid = 0;
+        p->ready = 0;
         p->last_ws = ws;
     }
     return FFTCONV_OK;
 }
 
 bool recompute_mode(fftconv_plan_t p) { return (p->d.flags & FFTCONV_RECOMPUTE) != 0; }
+
+constexpr unsigned kReadyDX = 1u, kReadyDW = 2u;
+
+// A result spectrum waiting in the OUT slot goes stale with the operand spectra it was formed from.
+void operands_changed(fftconv_plan_t p, unsigned slots)
+{
+    if (slots & (FFTCONV_SPEC_G | FFTCONV_SPEC_G2)) p->ready = 0;
+    if (slots & FFTCONV_SPEC_X) p->ready &= ~kReadyDW;
+    if (slots & FFTCONV_SPEC_W) p->ready &= ~kReadyDX;
+}
 
 // Slot that receives a pass's result spectrum.  With the spectral cache it is the separate
 // OUT slot; in the memory-efficient mode it is the one of the three slots the pass does not
@@ -273,6 +290,7 @@ int launch_forward(fftconv_plan_t p, int slot, const float *src, void *ws, hipSt
     if (int rc = check_launch()) return rc;
     if (int rc = timer.finish()) return rc;
     p->valid |= (unsigned)slot;
+    operands_changed(p, (unsigned)slot);
     // in the three-slot workspace the blocks and the windows of dL/dy share one slot
     if (recompute_mode(p) && slot == FFTCONV_SPEC_G) p->valid &= ~(unsigned)FFTCONV_SPEC_G2;
     if (recompute_mode(p) && slot == FFTCONV_SPEC_G2) p->valid &= ~(unsigned)FFTCONV_SPEC_G;
@@ -324,6 +342,42 @@ int launch_skinny(fftconv_plan_t p, int pass, void *ws, hipStream_t stream)
     hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kSkinnyThreads), 0, stream, a);
     if (int rc = check_launch()) return rc;
     if (sc != FFTCONV_SPEC_OUT) p->valid &= ~(unsigned)sc;   // an operand slot now holds the result spectrum
+    else p->ready = 0;                                       // whatever waited in the OUT slot is overwritten
+    return timer.finish();
+}
+
+typedef void (*SharedPassKernel)(SharedPassArgs);
+const SharedPassKernel kSharedPass[4] = {skinny_bprop_accgrad_kernel<1>, skinny_bprop_accgrad_kernel<2>,
+                                         skinny_bprop_accgrad_kernel<3>, skinny_bprop_accgrad_kernel<4>};
+
+bool shared_pass(fftconv_plan_t p)
+{
+    return p->shared_pass_ok && !std::getenv("FFTCONV_NO_SKINNY") && !std::getenv("FFTCONV_NO_SHARED_PASS");
+}
+
+// Both result spectra of bprop and accGrad from one pass over the spectrum of dL/dy; timed as
+// the contraction of the pass that asked for it.
+int launch_shared_pass(fftconv_plan_t p, int pass, void *ws, hipStream_t stream)
+{
+    const unsigned need = FFTCONV_SPEC_X | FFTCONV_SPEC_W | FFTCONV_SPEC_G;
+    if ((p->valid & need) != need) return FFTCONV_ENOTREADY;
+    SharedPassArgs a{};
+    unsigned char *out = reinterpret_cast<unsigned char *>(slot_ptr(p, ws, FFTCONV_SPEC_OUT));
+    a.G = slot_ptr(p, ws, FFTCONV_SPEC_G);
+    a.X = slot_ptr(p, ws, FFTCONV_SPEC_X);
+    a.W = slot_ptr(p, ws, FFTCONV_SPEC_W);
+    a.DX = reinterpret_cast<cf *>(out);
+    a.DW = reinterpret_cast<cf *>(out + p->off_shared_dw);
+    a.M = p->d.S;
+    a.N = p->d.fo;
+    a.bins = p->B;
+    const int F = p->d.f;
+    const int lds_bytes = (64 * 65 + 2 * 64 * F + kSkinnyWaves * ((a.M + 63) / 64) * 64 * F) * 8;
+    SharedPassKernel kernel = kSharedPass[F - 1];
+    if (int rc = allow_lds(kernel, lds_bytes)) return rc;
+    StageTimer timer(p, FFTCONV_STAGE_CGEMM_FPROP + pass, stream);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)a.bins), dim3(kSkinnyThreads), lds_bytes, stream, a);
+    if (int rc = check_launch()) return rc;
     return timer.finish();
 }
 
@@ -356,11 +410,14 @@ int launch_contract(fftconv_plan_t p, int pass, void *ws, hipStream_t stream)
     if (sc != FFTCONV_SPEC_OUT) {   // an operand slot now holds a result spectrum
         p->valid &= ~(unsigned)sc;
         if (sc == FFTCONV_SPEC_G) p->valid &= ~(unsigned)FFTCONV_SPEC_G2;   // same place in the three-slot workspace
+    } else {
+        p->ready = 0;               // whatever waited in the OUT slot is overwritten
     }
     return timer.finish();
 }
 
-int launch_inverse(fftconv_plan_t p, int pass, float *dst, void *ws, hipStream_t stream, int accumulate, bool fused = false)
+int launch_inverse(fftconv_plan_t p, int pass, float *dst, void *ws, hipStream_t stream, int accumulate, bool fused = false,
+                   size_t spec_offset = 0)
 {
     long M;
     InvArgs a{};
@@ -393,7 +450,8 @@ int launch_inverse(fftconv_plan_t p, int pass, float *dst, void *ws, hipStream_t
         a.groups_per_sample = std::getenv("FFTCONV_NO_FUSED_ORDER") ? 0 : d.fo / e->T;
     }
     if (int rc = allow_lds(kernel, e->lds_bytes)) return rc;
-    a.spec = slot_ptr(p, ws, result_slot(p, pass));
+    a.spec = reinterpret_cast<const cf *>(reinterpret_cast<const unsigned char *>(slot_ptr(p, ws, result_slot(p, pass))) +
+                                          spec_offset);
     a.dst = dst;
     a.M = (int)M;
     // ... and rotate their gradient on the way out
@@ -433,9 +491,26 @@ int run_pass(fftconv_plan_t p, int pass, const float *src_a, const float *src_b,
     if ((p->valid & (unsigned)sb) == 0)
         if (int rc = launch_forward(p, sb, src_b, ws, s)) return rc;
     const bool fused = fused_fprop_kernel(p, pass, accumulate) != nullptr;
-    if (!fused)
+    size_t spec_offset = 0;
+    if (pass != FFTCONV_FPROP && shared_pass(p)) {
+        // bprop and accGrad share one pass over the spectrum of dL/dy when all three spectra are at hand
+        const unsigned mine = pass == FFTCONV_BPROP ? kReadyDX : kReadyDW, other = mine ^ (kReadyDX | kReadyDW);
+        const unsigned third = pass == FFTCONV_BPROP ? FFTCONV_SPEC_X : FFTCONV_SPEC_W;   // read by the other pass only
+        bool from_shared = true;
+        if (p->ready & mine) {
+            p->ready &= ~mine;                     // formed by the other pass: use it once
+        } else if (p->valid & third) {
+            if (int rc = launch_shared_pass(p, pass, ws, s)) return rc;
+            p->ready = other;
+        } else {
+            if (int rc = launch_contract(p, pass, ws, s)) return rc;
+            from_shared = false;
+        }
+        if (from_shared && pass == FFTCONV_ACCGRAD) spec_offset = p->off_shared_dw;
+    } else if (!fused) {
         if (int rc = launch_contract(p, pass, ws, s)) return rc;
-    const int rc = launch_inverse(p, pass, dst, ws, s, accumulate, fused);
+    }
+    const int rc = launch_inverse(p, pass, dst, ws, s, accumulate, fused, spec_offset);
     if (recompute_mode(p)) p->valid = 0;
     return rc;
 }
@@ -523,6 +598,12 @@ int fftconv_plan2d(fftconv_plan_t *out, const fftconv_desc2d *d)
         p->maps_out = -1;
     }
     p->valid = 0;
+    p->ready = 0;
+    // one pass over the spectrum of dL/dy for bprop and accGrad: few input maps, spectra cached, untiled,
+    // the partial sums of dXh fit the LDS, and dXh and dWh fit the OUT slot side by side
+    p->off_shared_dw = align_up((size_t)d->S * d->f * p->B * sizeof(cf));
+    p->shared_pass_ok = !lean && L == 0 && d->f <= 4 && d->S <= kSharedPassMaxRows &&
+                        p->off_shared_dw + (size_t)maps_w * p->B * sizeof(cf) <= (size_t)p->maps_out * p->B * sizeof(cf);
     p->last_ws = nullptr;
     p->profiling = 0;
     for (int pass = 0; pass < 3; ++pass) {
@@ -581,6 +662,7 @@ int fftconv_invalidate(fftconv_plan_t p, unsigned slots)
     if (!p || (slots & ~(unsigned)(FFTCONV_SPEC_X | FFTCONV_SPEC_W | FFTCONV_SPEC_G)) != 0) return FFTCONV_EINVAL;
     if (slots & FFTCONV_SPEC_G) slots |= FFTCONV_SPEC_G2;   // both are transforms of dL/dy
     p->valid &= ~slots;
+    operands_changed(p, slots);
     return FFTCONV_OK;
 }
 

@@ -31,7 +31,24 @@ struct SkinnyArgs {
 constexpr int kSkinnyThreads = 256;
 constexpr int kSkinnyWaves = kSkinnyThreads / 64;   // K slices a workgroup works on at a time
 
-FC_HD cf cmul_conj_b(cf a, cf b) { return mk(a.x * b.x + a.y * b.y, a.y * b.x - a.x * b.y); }   // a * conj(b)
+// acc + a * b and acc + conj(a) * b as four fused multiply-adds each (a product formed first and
+// added afterwards would take six instructions, and these kernels have little else to issue)
+__device__ __forceinline__ cf cmac(cf acc, cf a, cf b)
+{
+    acc.x = __builtin_fmaf(a.x, b.x, acc.x);
+    acc.y = __builtin_fmaf(a.x, b.y, acc.y);
+    acc.x = __builtin_fmaf(-a.y, b.y, acc.x);
+    acc.y = __builtin_fmaf(a.y, b.x, acc.y);
+    return acc;
+}
+__device__ __forceinline__ cf cmac_conj(cf acc, cf a, cf b)
+{
+    acc.x = __builtin_fmaf(a.x, b.x, acc.x);
+    acc.y = __builtin_fmaf(a.x, b.y, acc.y);
+    acc.x = __builtin_fmaf(a.y, b.y, acc.x);
+    acc.y = __builtin_fmaf(-a.y, b.x, acc.y);
+    return acc;
+}
 
 // A wave works on one row m at a time with its 64 lanes along j, so the row's F values of Xh are
 // the same for every lane: they are read through a wave-uniform address (scalar loads) and cost
@@ -69,7 +86,7 @@ __global__ __launch_bounds__(kSkinnyThreads) void skinny_accgrad_kernel(SkinnyAr
             const int m = m0 + u * kSkinnyWaves;
             if (m < a.M) {
 #pragma unroll
-                for (int i = 0; i < F; ++i) acc[i] = acc[i] + cmul_conj_b(x[u][i], g[u]);   // conj(g) * x
+                for (int i = 0; i < F; ++i) acc[i] = cmac_conj(acc[i], g[u], x[u][i]);   // conj(g) * x
             }
         }
     }
@@ -140,7 +157,7 @@ __global__ __launch_bounds__(kSkinnyThreads) void skinny_bprop_kernel(SkinnyArgs
 #pragma unroll
             for (int i = 0; i < F; ++i) {
                 const cf w = wt[j * F + i];
-                acc[i] = mk(acc[i].x + (g.x * w.x - g.y * w.y), acc[i].y + (g.x * w.y + g.y * w.x));
+                acc[i] = cmac(acc[i], g, w);
             }
         }
         __syncthreads();
@@ -158,6 +175,153 @@ __global__ __launch_bounds__(kSkinnyThreads) void skinny_bprop_kernel(SkinnyArgs
 #pragma unroll
             for (int q = 1; q < kSkinnyWaves; ++q) sum = sum + part[(q * 64 + lane) * F + i];
             out[i] = sum;
+        }
+    }
+}
+
+// bprop and accGrad in one pass over Gh.  Both products read the whole of Gh, the largest array of
+// a layer with few input maps, and nothing else of any size, so computing them together halves
+// the HBM traffic of the pair:
+//     dXh[b][m][i] = sum_j      Gh[b][m][j]  * Wh[b][j][i]
+//     dWh[b][j][i] = sum_m conj(Gh[b][m][j]) * Xh[b][m][i]
+// One workgroup per bin walks Gh[b] in 64 x 64 tiles, column block by column block.  A tile comes
+// in with lanes along j and is handed over through LDS; then, for dXh, lane = row and the four
+// waves each sum a quarter of the tile's columns; for dWh, lane = column and the four waves each
+// sum a quarter of the tile's rows.  dWh of a column block is complete when its last tile is done;
+// the partial sums of dXh live in LDS, one slot per (quarter, row), until the end.
+struct SharedPassArgs {
+    const cf *G;   // Gh  [bins][M][N]
+    const cf *X;   // Xh  [bins][M][F]
+    const cf *W;   // Wh  [bins][N][F]
+    cf *DX;        // dXh [bins][M][F]
+    cf *DW;        // dWh [bins][N][F]
+    int M, N, bins;
+};
+
+constexpr int kSharedPassMaxRows = 256;   // M above this: the partial sums of dXh would crowd the LDS
+
+template <int F>
+constexpr int shared_pass_lds_elems(int M)
+{
+    return 64 * 65 + 2 * 64 * F + kSkinnyWaves * ((M + 63) / 64) * 64 * F;
+}
+
+// grid = bins workgroups of kSkinnyThreads threads, shared_pass_lds_elems<F>(M) * 8 bytes of dynamic LDS
+template <int F>
+__global__ __launch_bounds__(kSkinnyThreads) void skinny_bprop_accgrad_kernel(SharedPassArgs a)
+{
+    constexpr int TS = 65, U = 64 / kSkinnyWaves;
+    extern __shared__ __align__(16) unsigned char shared_raw[];
+    cf *tile = reinterpret_cast<cf *>(shared_raw);      // [64][TS]
+    cf *wt = tile + 64 * TS;                            // Wh of the column block  [64][F]
+    cf *xt = wt + 64 * F;                               // Xh of the row block     [64][F]
+    cf *dxacc = xt + 64 * F;                            // [waves][rows padded to 64][F]
+    cf *red = tile;                                     // [waves][64][F], used between two column blocks only
+    static_assert(kSkinnyWaves * 64 * F <= 64 * TS, "the reduction buffer takes the tile's place");
+    const int tid = (int)threadIdx.x, lane = tid % 64, q = wave_index();
+    const int bin = (int)blockIdx.x;
+    const int nmb = (a.M + 63) / 64, njc = (a.N + 63) / 64, Mp = nmb * 64;
+    const cf *Gb = a.G + (size_t)bin * a.M * a.N;
+    const cf *Xb = a.X + (size_t)bin * a.M * F;
+    const cf *Wb = a.W + (size_t)bin * a.N * F;
+
+    // lane (row r, quarter q) owns dxacc[q][mb * 64 + r][*] until the final sum
+    for (int mb = 0; mb < nmb; ++mb)
+#pragma unroll
+        for (int i = 0; i < F; ++i) dxacc[((size_t)q * Mp + mb * 64 + lane) * F + i] = mk(0.0f, 0.0f);
+
+    cf regs[U], xreg = mk(0.0f, 0.0f), wreg = mk(0.0f, 0.0f);
+    bool ok[U], xok = false, wok = false;
+    auto prefetch = [&](int jc, int mb) {
+        const int j = jc * 64 + lane;
+        const int jcl = j < a.N ? j : a.N - 1;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int row = mb * 64 + q + kSkinnyWaves * u;
+            ok[u] = row < a.M && j < a.N;
+            regs[u] = Gb[(size_t)(row < a.M ? row : a.M - 1) * a.N + jcl];   // clamped address, masked at the hand-over
+        }
+        if (tid < 64 * F) {
+            const int m = mb * 64 + tid / F, jw = jc * 64 + tid / F;
+            xok = m < a.M;
+            wok = jw < a.N;
+            xreg = Xb[(size_t)(xok ? m : a.M - 1) * F + tid % F];
+            wreg = Wb[(size_t)(wok ? jw : a.N - 1) * F + tid % F];
+        }
+    };
+    prefetch(0, 0);
+    for (int jc = 0; jc < njc; ++jc) {
+        cf dw[F];
+#pragma unroll
+        for (int i = 0; i < F; ++i) dw[i] = mk(0.0f, 0.0f);
+        for (int mb = 0; mb < nmb; ++mb) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) tile[(q + kSkinnyWaves * u) * TS + lane] = ok[u] ? regs[u] : mk(0.0f, 0.0f);
+            if (tid < 64 * F) {
+                xt[tid] = xok ? xreg : mk(0.0f, 0.0f);
+                wt[tid] = wok ? wreg : mk(0.0f, 0.0f);
+            }
+            __syncthreads();
+            if (mb + 1 < nmb) prefetch(jc, mb + 1);
+            else if (jc + 1 < njc) prefetch(jc + 1, 0);
+            // dXh: row = lane, columns q * 16 .. q * 16 + 15 of the tile
+            cf pdx[F];
+#pragma unroll
+            for (int i = 0; i < F; ++i) pdx[i] = mk(0.0f, 0.0f);
+#pragma unroll
+            for (int jj = 0; jj < 16; ++jj) {
+                const int j = q * 16 + jj;
+                const cf g = tile[lane * TS + j];
+#pragma unroll
+                for (int i = 0; i < F; ++i) {
+                    const cf w = wt[j * F + i];
+                    pdx[i] = cmac(pdx[i], g, w);
+                }
+            }
+            cf *slot = dxacc + ((size_t)q * Mp + mb * 64 + lane) * F;
+#pragma unroll
+            for (int i = 0; i < F; ++i) slot[i] = slot[i] + pdx[i];
+            // dWh: column = lane, rows q * 16 .. q * 16 + 15 of the tile
+#pragma unroll
+            for (int mm = 0; mm < 16; ++mm) {
+                const int r = q * 16 + mm;
+                const cf g = tile[r * TS + lane];
+#pragma unroll
+                for (int i = 0; i < F; ++i) {
+                    const cf x = xt[r * F + i];
+                    dw[i] = cmac_conj(dw[i], g, x);
+                }
+            }
+            __syncthreads();
+        }
+        // dWh of this column block: add the four quarters
+#pragma unroll
+        for (int i = 0; i < F; ++i) red[(q * 64 + lane) * F + i] = dw[i];
+        __syncthreads();
+        if (q == 0 && jc * 64 + lane < a.N) {
+            cf *out = a.DW + ((size_t)bin * a.N + jc * 64 + lane) * F;
+#pragma unroll
+            for (int i = 0; i < F; ++i) {
+                cf sum = red[lane * F + i];
+#pragma unroll
+                for (int w = 1; w < kSkinnyWaves; ++w) sum = sum + red[(w * 64 + lane) * F + i];
+                out[i] = sum;
+            }
+        }
+        __syncthreads();
+    }
+    // dXh: add the four quarters; wave q takes the row blocks q, q + 4, ...
+    for (int mb = q; mb < nmb; mb += kSkinnyWaves) {
+        const int m = mb * 64 + lane;
+        if (m < a.M) {
+            cf *out = a.DX + ((size_t)bin * a.M + m) * F;
+#pragma unroll
+            for (int i = 0; i < F; ++i) {
+                cf sum = dxacc[(size_t)m * F + i];
+#pragma unroll
+                for (int w = 1; w < kSkinnyWaves; ++w) sum = sum + dxacc[((size_t)w * Mp + m) * F + i];
+                out[i] = sum;
+            }
         }
     }
 }

@@ -355,6 +355,51 @@ def test_few_input_maps_both_contraction_paths(fc, layer, monkeypatch):
         check(dw, ref[2], f"{layer.name} accgrad ({tag})")
 
 
+@pytest.mark.parametrize("layer", [wl.Layer("shared_f3", 70, 3, 70, 20, 5, 0.1, 110), wl.Layer("shared_f4_rows", 200, 4, 33, 12, 3, 0.1, 111),
+                                   wl.Layer("shared_f1", 5, 1, 130, 30, 7, 0.1, 112)], ids=lambda l: l.name)
+def test_bprop_and_accgrad_share_one_pass_over_the_gradient_spectrum(fc, layer):
+    """With f <= 4 and all three spectra cached, whichever of bprop / accGrad runs first forms both
+    result spectra and leaves the other's for it.  Every order of calls, and every change of an
+    operand in between, must give the oracle's results."""
+    print(f"\ncase {layer}", flush=True)
+    x, w, g = wl.make_inputs(layer)
+    rng = np.random.default_rng(layer.seed)
+    x2 = rng.uniform(-1, 1, x.shape).astype(np.float32)
+    w2 = (rng.standard_normal(w.shape) * 0.1).astype(np.float32)
+    g2 = rng.standard_normal(g.shape).astype(np.float32)
+    n, k = layer.n, layer.k
+    plan = fc.Plan(layer.S, layer.f, layer.fo, n, k)
+    xd, wd, gd, x2d, w2d, g2d = (dev(a) for a in (x, w, g, x2, w2, g2))
+    # the usual order
+    plan.fprop(xd, wd)
+    check(plan.bprop(gd, wd).cpu().numpy(), direct.bprop(g, w, n), "bprop first")
+    check(plan.accgrad(gd, xd).cpu().numpy(), direct.accgrad(g, x, k), "accgrad second")
+    # again, nothing invalidated: both are formed anew (the waiting result was used up)
+    check(plan.accgrad(gd, xd).cpu().numpy(), direct.accgrad(g, x, k), "accgrad first")
+    check(plan.bprop(gd, wd).cpu().numpy(), direct.bprop(g, w, n), "bprop second")
+    # an operand of the waiting result changes between the two passes
+    check(plan.bprop(gd, wd).cpu().numpy(), direct.bprop(g, w, n), "bprop before x changes")
+    plan.invalidate(fc.SPEC_X)
+    check(plan.accgrad(gd, x2d).cpu().numpy(), direct.accgrad(g, x2, k), "accgrad after x changed")
+    check(plan.accgrad(gd, x2d).cpu().numpy(), direct.accgrad(g, x2, k), "accgrad before w changes")
+    plan.invalidate(fc.SPEC_W)
+    check(plan.bprop(gd, w2d).cpu().numpy(), direct.bprop(g, w2, n), "bprop after w changed")
+    plan.invalidate(fc.SPEC_G)
+    check(plan.accgrad(g2d, x2d).cpu().numpy(), direct.accgrad(g2, x2, k), "accgrad after g changed")
+    check(plan.bprop(g2d, w2d).cpu().numpy(), direct.bprop(g2, w2, n), "bprop after g changed")
+    # a pass in between that writes its own result spectrum
+    check(plan.bprop(g2d, w2d).cpu().numpy(), direct.bprop(g2, w2, n), "bprop before fprop")
+    y = torch.zeros(layer.S, layer.fo, n - k + 1, n - k + 1, device="cuda")
+    plan.forward_transform(fc.SPEC_X, x2d); plan.contract(fc.FPROP); plan.inverse_transform(fc.FPROP, y)
+    check(y.cpu().numpy(), direct.fprop(x2, w2), "fprop by stages")
+    check(plan.accgrad(g2d, x2d).cpu().numpy(), direct.accgrad(g2, x2, k), "accgrad after the stages of fprop")
+    # only two spectra at hand: the plain path
+    plan.invalidate()
+    check(plan.bprop(gd, wd).cpu().numpy(), direct.bprop(g, w, n), "bprop with no x spectrum")
+    dw = plan.accgrad(gd, xd)
+    check(plan.accgrad(gd, xd, dw, accumulate=True).cpu().numpy(), 2 * direct.accgrad(g, x, k), "accgrad accumulating")
+
+
 @pytest.mark.parametrize("dims", [(2, 3, 4, 16, 16, 5, 5), (3, 2, 2, 29, 20, 6, 3), (2, 5, 3, 70, 41, 3, 6), (1, 2, 2, 8, 8, 8, 8)],
                          ids=lambda d: "x".join(map(str, d)))
 def test_true_convolution_flag(fc, dims):
