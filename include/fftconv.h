@@ -169,7 +169,15 @@ unsigned fftconv_valid_slots(fftconv_plan_t p);
 int fftconv_fprop(fftconv_plan_t p, const float *x, const float *w, float *y, void *ws, void *stream);
 
 /* Eq. (2), summed over j: dx[s,i] = sum_j g[s,j] * w[j,i]^T (adjoint of fprop in x).
- * Uses the g and w slots; stores the full n x n window.  dx is overwritten. */
+ * Uses the g and w slots; stores the full n x n window.  dx is overwritten.
+ *
+ * Layers with f <= 4 (spectra cached, n <= 64, S <= 256): if the slots of x, w and g are
+ * all valid, the first of fftconv_bprop / fftconv_accgrad to be called forms the result
+ * spectra of both in one pass over the spectrum of dL/dy and leaves the other's in
+ * FFTCONV_SPEC_OUT; the other pass, called next with the same tensors, only
+ * inverse-transforms it.  The waiting spectrum is used once, and is dropped when one of
+ * its operand slots is invalidated or transformed again or another call writes
+ * FFTCONV_SPEC_OUT; results are those of separate calls up to rounding order. */
 int fftconv_bprop(fftconv_plan_t p, const float *g, const float *w, float *dx, void *ws, void *stream);
 
 /* Eq. (3), summed over the minibatch: dw[j,i] = sum_s g[s,j] * x[s,i] (adjoint of
