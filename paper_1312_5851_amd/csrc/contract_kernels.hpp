@@ -26,8 +26,8 @@
 // out Ps[k][r] (non-K index fastest), so the 32x2 operand fragment of an MFMA is
 // one ds_read_b64 per lane: lane l reads Ps[k0 + l/32][r0 + l%32].  LDS holds two
 // chunks: while chunk c is multiplied, chunk c+1 is written to the other half
-// (its global loads were issued one chunk earlier) and chunk c+2's loads are
-// issued; one barrier per chunk.  Fragments are double-buffered in registers so
+// (its global loads were issued SETS chunks earlier, into one of SETS register sets;
+// one set by default) and the loads of chunk c+1+SETS are issued; one barrier per chunk.  Fragments are double-buffered in registers so
 // the LDS latency of step ks+1 hides behind the MFMAs of step ks.
 //
 // Vector-ALU instructions and MFMAs of the waves on a SIMD do not overlap (counters:
