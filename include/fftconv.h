@@ -9,8 +9,8 @@
  * FFTCONV_TRUE_CONV: as the true convolution).
  *
  * Every pass follows Sec. 2.2: each 2-D map is Fourier-transformed once (zero
- * padded to N x N, N = the smallest of 8, 12, 16, 20, 24, 32, 40, 48, 64 that is >= n;
- * Sec. 4 pads to a power of two, the sizes 3 * 2^m and 5 * 2^m cut its padding waste), the products are
+ * padded to N x N, N = the smallest of 8, 12, 14, 16, 20, 24, 28, 32, 40, 48, 56, 64 that is >= n;
+ * Sec. 4 pads to a power of two, the sizes 3 * 2^m, 5 * 2^m and 7 * 2^m cut its padding waste), the products are
  * accumulated per frequency bin over the summed index, and the result is
  * inverse-transformed and cropped.  The spectra of x, w and dL/dy are kept in a
  * caller-owned workspace and reused by later passes (the "keep the Fourier
@@ -115,7 +115,7 @@ int fftconv_plan(fftconv_plan_t *out, const fftconv_desc *d);
 int fftconv_plan2d(fftconv_plan_t *out, const fftconv_desc2d *d);   /* same, rectangular maps / kernels */
 int fftconv_plan_destroy(fftconv_plan_t p);
 
-/* Transform size N (2^m, 3 * 2^m or 5 * 2^m, >= n) and number of stored bins B = N*N/2 + 2:
+/* Transform size N (2^m, 3 * 2^m, 5 * 2^m or 7 * 2^m, >= n) and number of stored bins B = N*N/2 + 2:
  * the part of the spectrum a real map determines (Sec. 2.3), i.e. every bin that
  * is not the complex conjugate of another stored bin. */
 int fftconv_fft_size(fftconv_plan_t p);

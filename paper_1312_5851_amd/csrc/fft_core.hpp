@@ -1,9 +1,9 @@
-// In-register complex FFTs of size 2^m, 3 * 2^m or 5 * 2^m with compile-time indexing.
+// In-register complex FFTs of size 2^m, 3 * 2^m, 5 * 2^m or 7 * 2^m with compile-time indexing.
 //
 // Every array index below is a compile-time constant after template expansion,
 // so an N-point transform lives entirely in N complex registers of one lane
-// (no scratch memory).  Sizes with a factor 3 (12, 24, 48) or 5 (20, 40) exist so that an
-// input need not be padded all the way to the next power of two, the limitation
+// (no scratch memory).  Sizes with a factor 3 (12, 24, 48), 5 (20, 40) or 7 (14, 28, 56) exist
+// so that an input need not be padded all the way to the next power of two, the limitation
 // the paper points out in Sec. 4.  The same header compiles for gfx950 device code and,
 // without HIP, for a host build that replays the kernels' phases on the CPU.
 //
@@ -76,8 +76,8 @@ constexpr double sin64(int j) { return cos64(j + 48); }   // sin(t) = cos(t - pi
 
 constexpr int ilog2(int n) { return n <= 1 ? 0 : 1 + ilog2(n >> 1); }
 
-// N = odd_radix(N) * pow2_part(N) with odd_radix in {1, 3, 5}.
-constexpr int odd_radix(int N) { return N % 3 == 0 ? 3 : (N % 5 == 0 ? 5 : 1); }
+// N = odd_radix(N) * pow2_part(N) with odd_radix in {1, 3, 5, 7}.
+constexpr int odd_radix(int N) { return N % 3 == 0 ? 3 : (N % 5 == 0 ? 5 : (N % 7 == 0 ? 7 : 1)); }
 constexpr int pow2_part(int N) { return N / odd_radix(N); }
 constexpr bool fft_size_ok(int N) { const int M = pow2_part(N); return M >= 2 && (M & (M - 1)) == 0 && N <= 64; }
 
@@ -91,7 +91,7 @@ constexpr int bitrev(int i, int M)
 }
 
 // Position at which fft_dif leaves output X[k].  For N = 2^m the bit reversal of k; for
-// N = R * M (R = 3 or 5) the radix-R stage sends the outputs k = R q + r to block r, whose
+// N = R * M (R = 3, 5 or 7) the radix-R stage sends the outputs k = R q + r to block r, whose
 // M-point transform leaves X[R q + r] at bit-reversed q.
 template <int N>
 constexpr int brev(int k)
@@ -137,7 +137,7 @@ constexpr double sin_n(int q) { return 64 % N == 0 ? sin64(q * (64 / N)) : cos_r
 template <int N, int Q, bool INV>
 FC_HD cf twiddle_mul(cf v)
 {
-    static_assert(fft_size_ok(N), "transform sizes are 2^m, 3 * 2^m or 5 * 2^m, at most 64");
+    static_assert(fft_size_ok(N), "transform sizes are 2^m, 3 * 2^m, 5 * 2^m or 7 * 2^m, at most 64");
     constexpr int q = ((Q % N) + N) % N;
     if constexpr (q == 0) {
         return v;
@@ -166,7 +166,7 @@ FC_HD cf twiddle_mul(cf v)
 // "element i is known to be exactly zero at compile time".
 constexpr uint64_t low_mask(int n) { return n >= 64 ? ~0ull : ((1ull << n) - 1ull); }
 
-// Mask after the radix-R stage of an N = R M point transform (R = 3 or 5): output r of
+// Mask after the radix-R stage of an N = R M point transform (R = 3, 5 or 7): output r of
 // butterfly j (position r M + j) is zero iff all R inputs j, j + M, ... are.
 template <int N>
 constexpr uint64_t odd_stage_mask(uint64_t zm)
@@ -198,7 +198,7 @@ constexpr uint64_t dif_stage_mask(uint64_t zm, int h)
     return out;
 }
 
-// Known zeros in front of radix-2 stage `stage` (after the radix-3 or radix-5 stage, if N has one).
+// Known zeros in front of radix-2 stage `stage` (after the odd-radix stage, if N has one).
 template <int N>
 constexpr uint64_t dif_mask_before_stage(uint64_t zm, int stage)
 {
@@ -215,7 +215,7 @@ constexpr uint64_t dif_mask_before_stage(uint64_t zm, int stage)
 // the transform" (positions are the ones brev<N> names).  need_after_stage<N>(final, s)
 // is the set of positions whose value after radix-2 stage s is still needed by some
 // requested output; s = -1 gives what is needed in front of the first radix-2 stage,
-// i.e. of the radix-3 or radix-5 stage's outputs.
+// i.e. of the odd-radix stage's outputs.
 template <int N>
 constexpr uint64_t need_after_stage(uint64_t need_final, int stage)
 {
@@ -283,6 +283,14 @@ constexpr bool zero_suffix(uint64_t zm, int j, int M, int R)
     return true;
 }
 
+// Bit r set: output r of the odd-radix butterfly j (position j + r M) is read later.
+constexpr unsigned odd_need_bits(uint64_t need, int j, int M, int R)
+{
+    unsigned bits = 0;
+    for (int r = 0; r < R; ++r) bits |= (unsigned)((need >> (j + r * M)) & 1) << r;
+    return bits;
+}
+
 // Radix-5 decimation-in-frequency butterfly j of an N = 5 M point transform, in place on
 // x_q = v[j + q M]:
 //     y_r = (sum_q w^{r q} x_q) * exp(-/+ 2 pi i r j / N),   w = exp(-/+ 2 pi i / 5)
@@ -331,9 +339,60 @@ FC_HD void radix5_butterfly(cf &x0, cf &x1, cf &x2, cf &x3, cf &x4)
     if constexpr (NEED & 16u) x4 = twiddle_mul<N, 4 * J, INV>(y4);
 }
 
+// Radix-7 decimation-in-frequency butterfly j of an N = 7 M point transform, in place on
+// x_q = v[j + q M], written like the radix-5 one with the pairs (x1, x6), (x2, x5), (x3, x4):
+//     y_0 = x0 + sum_k s_k,   s_k = x_k + x_{7-k},  d_k = x_k - x_{7-k}
+//     y_r, y_{7-r} = t_r -/+ i u_r  (forward),   t_r = x0 + sum_k cos(2 pi r k / 7) s_k,
+//                                                u_r = sum_k sin(2 pi r k / 7) d_k,   r, k = 1..3
+// then the twiddle exp(-/+ 2 pi i r j / N).  NZ and NEED as for radix 5.
+template <int N, bool INV, int J, int NZ, unsigned NEED>
+FC_HD void radix7_butterfly(cf (&v)[N])
+{
+    static_assert(NZ >= 1 && NZ <= 7, "at least the first input is non-zero");
+    constexpr int M = N / 7;
+    cf y[7];
+    const cf x0 = v[J];
+    if constexpr (NZ == 1) {
+        static_for<0, 7>([&](auto ri) { y[decltype(ri)::value] = x0; });
+    } else {
+        constexpr int P = NZ >= 4 ? 3 : NZ - 1;   // pairs with at least their first member non-zero
+        cf s[3], d[3];
+        static_for<0, P>([&](auto ki) {
+            constexpr int k = decltype(ki)::value + 1;
+            if constexpr (7 - k < NZ) {
+                s[k - 1] = v[J + k * M] + v[J + (7 - k) * M];
+                d[k - 1] = v[J + k * M] - v[J + (7 - k) * M];
+            } else {
+                s[k - 1] = v[J + k * M];
+                d[k - 1] = v[J + k * M];
+            }
+        });
+        y[0] = x0;
+        static_for<0, P>([&](auto ki) { y[0] = y[0] + s[decltype(ki)::value]; });
+        static_for<1, 4>([&](auto ri) {
+            constexpr int r = decltype(ri)::value;
+            cf t = x0, u = mk(0.0f, 0.0f);
+            static_for<0, P>([&](auto ki) {
+                constexpr int k = decltype(ki)::value + 1;
+                constexpr float c = (float)cos_ratio(r * k, 7), sn = (float)cos_ratio(4L * (r * k) - 7, 28);
+                t = mk(t.x + c * s[k - 1].x, t.y + c * s[k - 1].y);
+                if constexpr (k == 1) u = mk(sn * d[0].x, sn * d[0].y);
+                else u = mk(u.x + sn * d[k - 1].x, u.y + sn * d[k - 1].y);
+            });
+            const cf e = mk(u.y, -u.x);   // -i u
+            y[r] = INV ? t - e : t + e;
+            y[7 - r] = INV ? t + e : t - e;
+        });
+    }
+    static_for<0, 7>([&](auto ri) {
+        constexpr int r = decltype(ri)::value;
+        if constexpr ((NEED >> r) & 1u) v[J + r * M] = twiddle_mul<N, r * J, INV>(y[r]);
+    });
+}
+
 // Decimation-in-frequency FFT, in place, natural-order input, outputs left at the
-// positions brev<N> names: X[k] = v[brev<N>(k)].  One radix-3 or radix-5 stage first if N has
-// that factor, then radix-2 stages.
+// positions brev<N> names: X[k] = v[brev<N>(k)].  One radix-3, radix-5 or radix-7 stage first
+// if N has that factor, then radix-2 stages.
 // ZMASK marks inputs known to be zero (their registers are never read), which
 // removes the arithmetic a zero-padded map does not need.  NEED marks the
 // output positions that will be read; the others are left undefined, which
@@ -341,7 +400,7 @@ FC_HD void radix5_butterfly(cf &x0, cf &x1, cf &x2, cf &x3, cf &x4)
 template <int N, bool INV, uint64_t ZMASK = 0, uint64_t NEED = ~0ull>
 FC_HD void fft_dif(cf (&v)[N])
 {
-    static_assert(fft_size_ok(N), "transform sizes are 2^m, 3 * 2^m or 5 * 2^m, at most 64");
+    static_assert(fft_size_ok(N), "transform sizes are 2^m, 3 * 2^m, 5 * 2^m or 7 * 2^m, at most 64");
     constexpr int M = pow2_part(N);
     if constexpr (odd_radix(N) == 5) {
         constexpr uint64_t nd = need_after_stage<N>(NEED, -1);
@@ -353,6 +412,16 @@ FC_HD void fft_dif(cf (&v)[N])
                                                  (((nd >> (j + 3 * M)) & 1) << 3) | (((nd >> (j + 4 * M)) & 1) << 4));
             if constexpr (nz > 0)
                 radix5_butterfly<N, INV, j, nz, need>(v[j], v[j + M], v[j + 2 * M], v[j + 3 * M], v[j + 4 * M]);
+        });
+    }
+    if constexpr (odd_radix(N) == 7) {
+        constexpr uint64_t nd = need_after_stage<N>(NEED, -1);
+        static_for<0, M>([&](auto ji) {
+            constexpr int j = decltype(ji)::value;
+            constexpr int nz = leading_nonzero(ZMASK, j, N / 7, 7);
+            static_assert(zero_suffix(ZMASK, j, N / 7, 7), "zero padding is a suffix");
+            constexpr unsigned need = odd_need_bits(nd, j, N / 7, 7);
+            if constexpr (nz > 0) radix7_butterfly<N, INV, j, nz, need>(v);
         });
     }
     if constexpr (odd_radix(N) == 3) {

@@ -11,21 +11,25 @@ namespace fftconv {
 #define FFTCONV_FOR_EACH_GEOM(X) \
     X(8, 64, 8)   X(8, 64, 4)                 \
     X(12, 32, 12) X(12, 32, 6)                \
+    X(14, 32, 14) X(14, 32, 7)                \
     X(16, 32, 16) X(16, 32, 8)  X(16, 32, 4)  \
     X(20, 32, 20) X(20, 32, 10) X(20, 32, 5)  \
     X(24, 16, 24) X(24, 16, 12) X(24, 16, 6)  \
+    X(28, 16, 28) X(28, 16, 14) X(28, 16, 7)  \
     X(32, 16, 32) X(32, 16, 16) X(32, 16, 8)  \
     X(40, 16, 40) X(40, 16, 20) X(40, 16, 10) \
     X(48, 16, 48) X(48, 16, 24) X(48, 16, 12) \
+    X(56, 16, 56) X(56, 16, 28) X(56, 16, 14) \
     X(64, 16, 64) X(64, 16, 32) X(64, 16, 16)
 
-// Transform size for an n x n input: the smallest of 8, 12, 16, 20, 24, 32, 40, 48, 64 that
-// holds it.  The paper pads to the next power of two and names the waste for sizes just above
-// one as its limitation (Sec. 4), with n = 34 -> 64 as its example; the sizes 3 * 2^m and
-// 5 * 2^m bring that case down to 40 and keep the padded area below 1.8 x the map for n >= 8.
+// Transform size for an n x n input: the smallest of 8, 12, 14, 16, 20, 24, 28, 32, 40, 48, 56,
+// 64 that holds it.  The paper pads to the next power of two and names the waste for sizes just
+// above one as its limitation (Sec. 4), with n = 34 -> 64 as its example; the sizes 3 * 2^m,
+// 5 * 2^m and 7 * 2^m bring that case down to 40, fit the map sizes 14, 28 and 56 of
+// image-classification networks exactly, and keep the padded area below 1.5 x the map for n >= 10.
 inline int fft_size_for(int n)
 {
-    static const int sizes[] = {8, 12, 16, 20, 24, 32, 40, 48, 64};
+    static const int sizes[] = {8, 12, 14, 16, 20, 24, 28, 32, 40, 48, 56, 64};
     for (int N : sizes)
         if (N >= n) return N;
     return -1;

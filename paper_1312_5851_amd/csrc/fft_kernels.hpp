@@ -121,9 +121,9 @@ struct TileGeom {
     static constexpr int LDS_BYTES = LDS_ELEMS * 8;
     static constexpr int YITEMS = (T / 2) * NX;        // lanes active in the y-phase: (map pair, column)
     // waves per SIMD the register allocation should allow (what LDS lets a CU hold):
-    // N = 64 needs 128 registers for one transform alone, so two; N = 48 (96 registers, two
-    // workgroups of six waves per CU) and N = 40 (two of five waves) three; N = 32 fits four
-    static constexpr int WAVES_PER_SIMD = N >= 64 ? 2 : (N >= 40 ? 3 : (N == 32 && ROUNDS == 2 ? 4 : 1));
+    // N = 64 and 56 need 128 and 112 registers for one transform alone, so two; N = 48 (96 registers,
+    // two workgroups of six waves per CU) and N = 40 (two of five waves) three; N = 32 fits four
+    static constexpr int WAVES_PER_SIMD = N >= 56 ? 2 : (N >= 40 ? 3 : (N == 32 && ROUNDS == 2 ? 4 : 1));
     static_assert(T % 2 == 0, "maps are processed in pairs");
     static_assert(NX <= N, "extent class cannot exceed the transform size");
     static_assert(ROWS % ROUNDS == 0 && YITEMS <= THREADS, "geometry");

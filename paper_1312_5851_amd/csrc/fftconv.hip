@@ -539,7 +539,7 @@ int fftconv_plan2d(fftconv_plan_t *out, const fftconv_desc2d *d)
         // Larger than the largest transform: cut into tiles of (N - kh + 1) x (N - kw + 1) outputs
         // (overlap-save).  Pick the tile transform that needs the fewest transformed points over
         // the tiles of y and of dx together.
-        static const int sizes[] = {16, 20, 24, 32, 40, 48, 64};
+        static const int sizes[] = {16, 20, 24, 28, 32, 40, 48, 56, 64};
         double best = -1.0;
         for (int cand : sizes) {
             const int ly = cand - d->kh + 1, lx = cand - d->kw + 1;

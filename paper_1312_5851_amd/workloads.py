@@ -78,7 +78,7 @@ def fig3_layers():
     not given in the text; the points here bracket the table's layers and include image
     sizes that are not a power of two (Sec. 4 pads those up; n = 34 is its example)."""
     out = []
-    for i, n in enumerate((8, 12, 16, 20, 24, 32, 34, 40, 48, 64)):
+    for i, n in enumerate((8, 12, 14, 16, 20, 24, 28, 32, 34, 40, 48, 56, 64)):
         out.append(Layer(f"fig3_n{n}", 128, 96, 256, n, 5, 0.02, BASE_SEED + 300 + i))
     for i, k in enumerate((3, 7, 9, 11, 13)):          # k = 5 is the n = 32 point above
         out.append(Layer(f"fig3_k{k}", 128, 96, 256, 32, k, 0.02, BASE_SEED + 320 + i))

@@ -48,17 +48,18 @@ def naive_dft2(pad):
     return np.einsum("ky,myx,lx->mkl", W, pad, W)
 
 
-SIZES = [8, 12, 16, 20, 24, 32, 40, 48, 64]
+SIZES = [8, 12, 14, 16, 20, 24, 28, 32, 40, 48, 56, 64]
 
 
 def test_size_rules(replay):
-    assert [replay.replay_fft_size(n) for n in (1, 8, 9, 12, 13, 16, 17, 20, 21, 24, 25, 32, 33, 34, 40, 41, 48, 49, 64)] == \
-        [8, 8, 12, 12, 16, 16, 20, 20, 24, 24, 32, 32, 40, 40, 40, 48, 48, 64, 64]
+    assert [replay.replay_fft_size(n) for n in (1, 8, 9, 12, 13, 14, 15, 16, 17, 20, 21, 24, 25, 28, 29, 32, 33, 34, 40, 41, 48, 49, 56, 57, 64)] == \
+        [8, 8, 12, 12, 14, 14, 16, 16, 20, 20, 24, 24, 28, 28, 32, 32, 40, 40, 40, 48, 48, 56, 56, 64, 64]
     assert replay.replay_fft_size(65) == -1
-    assert [replay.replay_maps_per_block(N) for N in SIZES] == [64, 32, 32, 32, 16, 16, 16, 16, 16]
+    assert [replay.replay_maps_per_block(N) for N in SIZES] == [64, 32, 32, 32, 32, 16, 16, 16, 16, 16, 16, 16]
     assert replay.replay_extent_class(12, 3) == 6 and replay.replay_extent_class(24, 5) == 6
     assert replay.replay_extent_class(48, 13) == 24 and replay.replay_extent_class(48, 25) == 48
     assert replay.replay_extent_class(20, 5) == 5 and replay.replay_extent_class(40, 11) == 20
+    assert replay.replay_extent_class(14, 3) == 7 and replay.replay_extent_class(28, 7) == 7 and replay.replay_extent_class(56, 29) == 56
     assert replay.replay_extent_class(32, 5) == 8 and replay.replay_extent_class(32, 9) == 16
     assert replay.replay_extent_class(32, 28) == 32 and replay.replay_extent_class(8, 2) == 4
 
@@ -95,7 +96,7 @@ def test_inverse_crops_scales_and_accumulates(replay, N):
             assert np.abs(acc - (base + full[:, :crop, :crop])).max() < 3e-6
 
 
-@pytest.mark.parametrize("N", [16, 20, 24])
+@pytest.mark.parametrize("N", [16, 20, 24, 28])
 def test_impulse_constant_and_round_trip(replay, N):
     imp = np.zeros((3, N, N), np.float32); imp[:, 0, 0] = 1
     s = forward(replay, imp, N)
@@ -128,7 +129,7 @@ def tile_windows(img, N, tiles_x, tiles, step, org, ext):
     return out
 
 
-@pytest.mark.parametrize("N,H,k", [(16, 37, 5), (20, 45, 4), (24, 50, 3), (32, 70, 11), (40, 90, 7), (48, 65, 4), (64, 100, 9)])
+@pytest.mark.parametrize("N,H,k", [(16, 37, 5), (20, 45, 4), (24, 50, 3), (28, 60, 5), (32, 70, 11), (40, 90, 7), (48, 65, 4), (56, 120, 8), (64, 100, 9)])
 def test_tiled_forward_windows(replay, N, H, k):
     """The three kinds of windows a tiled layer transforms: dense N x N windows of x (stride L),
     L x L blocks of dL/dy, and the windows of dL/dy that start k-1 before a tile of dx."""
@@ -151,7 +152,7 @@ def test_tiled_forward_windows(replay, N, H, k):
         assert np.abs(got - ref).max() <= 3e-6 * max(np.abs(ref).max(), 1), (what, N, H, k)
 
 
-@pytest.mark.parametrize("N,H,k,c0", [(16, 37, 5, 0), (16, 37, 5, 4), (20, 45, 4, 3), (24, 50, 3, 2), (40, 90, 7, 6), (48, 65, 4, 0), (64, 100, 9, 8)])
+@pytest.mark.parametrize("N,H,k,c0", [(16, 37, 5, 0), (16, 37, 5, 4), (20, 45, 4, 3), (24, 50, 3, 2), (28, 60, 5, 4), (40, 90, 7, 6), (48, 65, 4, 0), (56, 120, 8, 7), (64, 100, 9, 8)])
 def test_tiled_inverse_scatters_each_tile_once(replay, N, H, k, c0):
     """Rows / columns [c0, c0 + L) of every transform's output land at the tile's place;
     the tiles cover the image exactly once and nothing else is written."""
@@ -242,7 +243,7 @@ def test_tiled_rectangular_windows_and_scatter(replay):
                 assert np.abs(dst[s, c, oy:oy + h, ox:ox + w] - ref).max() < 3e-6
 
 
-@pytest.mark.parametrize("N", [8, 24, 32, 40, 64])
+@pytest.mark.parametrize("N", [8, 14, 24, 32, 40, 56, 64])
 def test_flipped_load_and_store(replay, N):
     """The kernels of a true convolution are read rotated by 180 degrees, their gradient is stored rotated."""
     rng = np.random.default_rng(400 + N)
@@ -268,7 +269,7 @@ def reference_spectrum_rect(maps, N):
     return np.fft.fft2(pad)[:, ky, kx].T
 
 
-@pytest.mark.parametrize("N,k", [(8, 2), (16, 3), (20, 2), (40, 5), (64, 9)])
+@pytest.mark.parametrize("N,k", [(8, 2), (14, 3), (16, 3), (20, 2), (40, 5), (56, 6), (64, 9)])
 def test_fused_product_inverse_is_the_valid_correlation(replay, N, k):
     """fprop with three input maps: the inverse transform forms its bins from the spectra of x and w
     (Sec. 2.2) and must leave the valid cross-correlation, summed over the input maps, written out

@@ -439,9 +439,15 @@ EDGE_LAYERS = [
     wl.Layer("n64_k1", 2, 3, 2, 64, 1, 0.1, 61),          # largest transform, k = 1
     wl.Layer("n64_k64", 2, 2, 3, 64, 64, 0.05, 62),       # k = n = 64: one output pixel
     wl.Layer("n33", 2, 3, 2, 33, 2, 0.1, 63),             # just above 32 -> N = 40
-    wl.Layer("n49", 2, 3, 2, 49, 4, 0.1, 72),             # just above 48 -> N = 64 with a lot of padding
+    wl.Layer("n49", 2, 3, 2, 49, 4, 0.1, 72),             # just above 48 -> N = 56
+    wl.Layer("n57", 2, 3, 2, 57, 4, 0.1, 113),            # just above 56 -> N = 64
+    wl.Layer("n56_k3", 3, 5, 4, 56, 3, 0.05, 114),        # N = 56 with no padding (a map size of image-classification networks)
+    wl.Layer("n28_k5", 19, 3, 5, 28, 5, 0.1, 115),        # N = 28 with no padding, ragged tiles of 16 maps
+    wl.Layer("n14_k3", 35, 3, 2, 14, 3, 0.1, 116),        # N = 14 with no padding, ragged tiles of 32 maps
+    wl.Layer("n14_k14", 3, 2, 3, 14, 14, 0.1, 117),       # N = 14, k = n
+    wl.Layer("n27_k13", 2, 3, 4, 27, 13, 0.05, 118),      # N = 28, middle extent classes
     wl.Layer("n17_k17", 3, 2, 2, 17, 17, 0.1, 64),        # N = 20, k = n
-    wl.Layer("n25_k25", 3, 2, 2, 25, 25, 0.1, 73),        # N = 32, k = n
+    wl.Layer("n25_k25", 3, 2, 2, 25, 25, 0.1, 73),        # N = 28, k = n
     wl.Layer("n48_k48", 2, 2, 3, 48, 48, 0.05, 74),       # N = 48 with no padding, k = n
     wl.Layer("n24_k2", 3, 4, 5, 24, 2, 0.1, 75),          # N = 24 with no padding
     wl.Layer("n12_k12", 5, 3, 2, 12, 12, 0.1, 76),        # N = 12, k = n
@@ -575,7 +581,7 @@ def test_stage_calls_compose_to_a_pass(fc):
     check(y.cpu().numpy(), direct.fprop(x, w), "stages fprop")
 
 
-@pytest.mark.parametrize("n,N_expected", [(20, 20), (21, 24), (28, 32), (11, 12), (34, 40), (44, 48), (52, 64)])
+@pytest.mark.parametrize("n,N_expected", [(20, 20), (21, 24), (28, 28), (30, 32), (11, 12), (13, 14), (34, 40), (44, 48), (52, 56), (60, 64)])
 def test_spectrum_stage_against_fft2(fc, n, N_expected):
     """Forward stage alone: slot contents equal the half spectrum of the zero-padded maps."""
     layer = wl.Layer("stage", 3, 5, 4, n, 6, 0.1, 31)
