@@ -37,7 +37,8 @@
  * products in separate launches instead of one pass over the spectrum of dL/dy; FFTCONV_NO_FUSED makes fprop of such
  * layers store and re-read the product spectrum instead of forming it inside the inverse
  * transform (which needs fo to be a multiple of the 16 to 64 maps a workgroup transforms),
- * FFTCONV_NO_FUSED_ORDER keeps that kernel's plain block order.
+ * FFTCONV_NO_FUSED_ORDER keeps that kernel's plain block order.  Read when a plan is made:
+ * FFTCONV_NO_OVERLAP_ADD keeps the second transform of dL/dy for bprop of tiled layers.
  */
 #ifndef FFTCONV_H
 #define FFTCONV_H
@@ -90,8 +91,8 @@ enum {
 };
 
 /* Spectral cache slots (bit flags) and the scratch slot holding a pass's result spectrum.
- * FFTCONV_SPEC_G2 exists only for tiled layers (n > 64, see fftconv_tiling): the windows
- * of dL/dy that bprop transforms, which differ from the blocks accGrad transforms. */
+ * FFTCONV_SPEC_G2 exists only for tiled layers (n > 64, see fftconv_tiling) whose bprop
+ * transforms windows of dL/dy of its own, which differ from the blocks accGrad transforms. */
 enum { FFTCONV_SPEC_X = 1, FFTCONV_SPEC_W = 2, FFTCONV_SPEC_G = 4, FFTCONV_SPEC_OUT = 8, FFTCONV_SPEC_G2 = 16 };
 
 /* Passes: Eq. (1), (2), (3) of Sec. 2.1. */
@@ -128,7 +129,11 @@ int fftconv_num_bins(fftconv_plan_t p);
  * multiplies the same windows with the transforms of the zero-padded blocks of dL/dy and
  * sums over samples and tiles; bprop transforms, for each block of dx, the N x N window of
  * dL/dy that starts k - 1 rows and columns before it and keeps rows / columns [k-1, N) of
- * the inverse transform (the part of a circular result that no wrap-around touches).  The
+ * the inverse transform (the part of a circular result that no wrap-around touches).
+ * When f * 8 <= fo (and L >= k - 1) bprop instead multiplies the blocks of dL/dy that accGrad
+ * transforms and adds the whole N x N inverse transform of each at the block's origin into dx
+ * (overlap-add, in four launches over tiles whose windows do not overlap): dL/dy is transformed
+ * once, there is no FFTCONV_SPEC_G2 slot, and tiles_dx equals tiles_y.  The
  * tiles of a sample act as extra samples for the contraction.  (Rectangular layers: L, the
  * block counts, the window offsets and the kept rows / columns are per axis, with kh and kw.)
  * Each array is (rows, columns): tile = (Ly, Lx), (0, 0) if not tiled; tiles_y and tiles_dx =
@@ -139,7 +144,7 @@ int fftconv_tiling(fftconv_plan_t p, int tile[2], int tiles_y[2], int tiles_dx[2
  * per map for S*f + fo*f + S*fo maps, the count of Sec. 2.3) plus one result
  * spectrum of 8*B*max(S*fo, S*f, fo*f) bytes; each slot 256-byte aligned.
  * With FFTCONV_RECOMPUTE: the three slots only.  Tiled layers hold one transform per
- * tile (fftconv_slot_maps) and one more slot, FFTCONV_SPEC_G2. */
+ * tile (fftconv_slot_maps) and, unless bprop uses overlap-add, one more slot, FFTCONV_SPEC_G2. */
 size_t fftconv_workspace_bytes(fftconv_plan_t p);
 
 /* Layout of one slot inside the workspace: byte offset and number of maps M.
@@ -189,7 +194,7 @@ int fftconv_accgrad(fftconv_plan_t p, const float *g, const float *x, float *dw,
 /* ---- single stages (same kernels; for stage tests and per-stage timing) - */
 
 /* Forward transform of one tensor into its slot (slot = FFTCONV_SPEC_X, _W, _G, or _G2
- * for a tiled layer), unconditionally; marks the slot valid. */
+ * for a tiled layer that has that slot), unconditionally; marks the slot valid. */
 int fftconv_forward_transform(fftconv_plan_t p, int slot, const float *src, void *ws, void *stream);
 
 /* Per-bin contraction of a pass on cached spectra into the OUT slot (under

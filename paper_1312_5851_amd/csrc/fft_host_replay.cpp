@@ -127,11 +127,14 @@ int replay_fft2d_r2c_tiled(int N, const float *src, float *spec, int M, int ext_
     return 1;
 }
 
+// add / parity: overlap-add of the windows of one parity class of tiles (parity -1: every tile).
 int replay_ifft2d_c2r_tiled(int N, const float *spec, float *dst, int M, int crop_y, int crop_x, int c0_y, int c0_x,
-                            int H, int W, int C, int tiles_x, int tiles, int step_y, int step_x)
+                            int H, int W, int C, int tiles_x, int tiles, int step_y, int step_x, int add, int parity)
 {
     InvArgs a{reinterpret_cast<const cf *>(spec), dst, M, crop_y, crop_x, 1.0f / (float)(N * N), c0_y, c0_x,
               {H, W, C, tiles_x, tiles, step_y, step_x, 0, 0}};
+    a.add = add;
+    a.parity = parity;
     const int T = maps_per_block(N);
 #define X(n_, t_, nx_) \
     if constexpr (n_ == nx_) { if (N == n_ && T == t_) { replay_inverse<TileGeom<n_, t_, nx_, rounds_for(n_)>, true>(a, false); return 0; } }

@@ -76,6 +76,9 @@ struct InvArgs {
     float scale;          // 1 / N^2
     int c0_y, c0_x;       // tiled kernels: first stored row / column of the transform's output
     Tiling t;             // read by the tiled kernels only
+    int add;              // tiled kernels: 1 = add the window to what dst holds (overlap-add), 0 = overwrite
+    int parity;           // tiled kernels: -1 = every tile; else only the tiles with 2 * (ty % 2) + tx % 2 == parity,
+                          // whose windows do not overlap each other
     int flip;             // untiled kernels: store every window rotated by 180 degrees
     // Read by the fused kernels only (fprop of a layer with very few input maps): instead of
     // reading `spec`, bin c of output map m = s * fo + j is formed on the fly as
@@ -89,6 +92,7 @@ struct InvArgs {
 
 struct TileOrigin {
     int image, oy, ox;
+    int parity;           // 2 * (ty % 2) + tx % 2
 };
 
 FC_HD TileOrigin tile_origin(int m, const Tiling &t)
@@ -99,6 +103,7 @@ FC_HD TileOrigin tile_origin(int m, const Tiling &t)
     o.image = s * t.C + c;
     o.oy = (tile / t.tiles_x) * t.step_y + t.org_y;
     o.ox = (tile % t.tiles_x) * t.step_x + t.org_x;
+    o.parity = 2 * ((tile / t.tiles_x) % 2) + (tile % t.tiles_x) % 2;
     return o;
 }
 
@@ -458,7 +463,9 @@ FC_HD void inv_y_finish(int tid, int blk, const InvArgs &a, cf (&z)[G::N])
 }
 
 // Tiled variant of step 2: rows and columns [c0, c0 + crop) of the transform's output go to
-// the tile's place in a larger image, clipped at the image border.
+// the tile's place in a larger image, clipped at the image border.  With a.add they are added to
+// what is there (overlap-add: the windows of neighbouring tiles overlap, so one launch handles
+// only tiles of one parity class, which do not).
 template <class G>
 FC_HD void inv_y_finish_tiled(int tid, int blk, const InvArgs &a, cf (&z)[G::N])
 {
@@ -474,6 +481,7 @@ FC_HD void inv_y_finish_tiled(int tid, int blk, const InvArgs &a, cf (&z)[G::N])
         const int m = blk * G::T + 2 * p + which;
         if (m >= a.M) return;
         const TileOrigin o = tile_origin(m, a.t);
+        if (a.parity >= 0 && o.parity != a.parity) return;
         if (o.ox + xs >= a.t.W) return;
         const int rows = a.crop_y < a.t.H - o.oy ? a.crop_y : a.t.H - o.oy;
         float *col = a.dst + ((size_t)o.image * a.t.H + o.oy) * a.t.W + o.ox + xs;
@@ -482,7 +490,9 @@ FC_HD void inv_y_finish_tiled(int tid, int blk, const InvArgs &a, cf (&z)[G::N])
             const int ys = y - a.c0_y;
             if (ys >= 0 && ys < rows) {
                 const cf v = z[brev<N>(y)];
-                col[(size_t)ys * a.t.W] = (which == 0 ? v.x : v.y) * a.scale;
+                const float r = (which == 0 ? v.x : v.y) * a.scale;
+                float *out = col + (size_t)ys * a.t.W;
+                *out = a.add ? *out + r : r;
             }
         });
     });

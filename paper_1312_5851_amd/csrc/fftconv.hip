@@ -139,6 +139,10 @@ struct fftconv_plan_s {
     // are Ly x Lx output blocks, nty x ntx of them for y (and for the blocks of dL/dy and the
     // windows of x), nty2 x ntx2 for dx (and for the windows of dL/dy that bprop reads).
     int Ly, Lx, nty, ntx, nty2, ntx2;
+    // Tiled layers with far fewer input than output maps: bprop multiplies the same zero-padded
+    // blocks of dL/dy that accGrad transforms (no second transform of dL/dy, no G2 slot) and
+    // adds the overlapping N x N windows of the result into dx (overlap-add).
+    bool overlap_add;
     long maps_x, maps_w, maps_g, maps_g2, maps_out;   // transforms per slot
     size_t off_x, off_w, off_g, off_g2, off_out, ws_bytes;
     unsigned valid;
@@ -189,6 +193,11 @@ struct StageTimer {
 };
 
 int check_launch() { return hipGetLastError() == hipSuccess ? FFTCONV_OK : FFTCONV_ELAUNCH; }
+
+__global__ __launch_bounds__(256) void fill_zero_kernel(float *dst, size_t count)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x) dst[i] = 0.0f;
+}
 
 template <class K>
 int allow_lds(K kernel, int bytes)
@@ -270,7 +279,7 @@ int launch_forward(fftconv_plan_t p, int slot, const float *src, void *ws, hipSt
             t = Tiling{p->noh, p->now, d.fo, p->ntx, p->nty * p->ntx, p->Ly, p->Lx, 0, 0};
             break;
         case FFTCONV_SPEC_G2:  // N x N windows of dL/dy starting (kh-1, kw-1) before each tile of dx
-            if (!tiled(p)) return FFTCONV_EINVAL;
+            if (!tiled(p) || p->overlap_add) return FFTCONV_EINVAL;
             M = p->maps_g2; ext_y = ext_x = p->N; stage = FFTCONV_STAGE_FFT_G;
             t = Tiling{p->noh, p->now, d.fo, p->ntx2, p->nty2 * p->ntx2, p->Ly, p->Lx, -(d.kh - 1), -(d.kw - 1)};
             break;
@@ -303,7 +312,11 @@ void pass_dims(fftconv_plan_t p, int pass, int &Md, int &Nd, int &Kd, int &slot_
     const int St = p->d.S * p->nty * p->ntx, St2 = p->d.S * p->nty2 * p->ntx2;
     switch (pass) {
         case FFTCONV_FPROP: Md = St; Nd = p->d.fo; Kd = p->d.f; slot_a = FFTCONV_SPEC_X; slot_b = FFTCONV_SPEC_W; break;
-        case FFTCONV_BPROP: Md = St2; Nd = p->d.f; Kd = p->d.fo; slot_a = tiled(p) ? FFTCONV_SPEC_G2 : FFTCONV_SPEC_G; slot_b = FFTCONV_SPEC_W; break;
+        case FFTCONV_BPROP:
+            Md = St2; Nd = p->d.f; Kd = p->d.fo;
+            slot_a = tiled(p) && !p->overlap_add ? FFTCONV_SPEC_G2 : FFTCONV_SPEC_G;
+            slot_b = FFTCONV_SPEC_W;
+            break;
         default:            Md = p->d.fo; Nd = p->d.f; Kd = St; slot_a = FFTCONV_SPEC_G; slot_b = FFTCONV_SPEC_X; break;
     }
 }
@@ -331,7 +344,7 @@ int launch_skinny(fftconv_plan_t p, int pass, void *ws, hipStream_t stream)
         a.jblocks = (p->d.fo + 63) / 64;
     } else {
         a.X = slot_ptr(p, ws, FFTCONV_SPEC_W);
-        a.G = slot_ptr(p, ws, tiled(p) ? FFTCONV_SPEC_G2 : FFTCONV_SPEC_G);
+        a.G = slot_ptr(p, ws, tiled(p) && !p->overlap_add ? FFTCONV_SPEC_G2 : FFTCONV_SPEC_G);
         a.M = p->d.S * p->nty2 * p->ntx2;
         a.jblocks = (a.M + 63) / 64;
     }
@@ -432,6 +445,11 @@ int launch_inverse(fftconv_plan_t p, int pass, float *dst, void *ws, hipStream_t
             a.crop_y = tiled(p) ? p->Ly : d.nh; a.crop_x = tiled(p) ? p->Lx : d.nw;
             a.t = Tiling{d.nh, d.nw, d.f, p->ntx2, p->nty2 * p->ntx2, p->Ly, p->Lx, 0, 0};
             a.c0_y = d.kh - 1; a.c0_x = d.kw - 1;
+            if (p->overlap_add) {   // the whole N x N output of a block's transform, placed at the block's origin
+                a.crop_y = a.crop_x = p->N;
+                a.c0_y = a.c0_x = 0;
+                a.add = 1;
+            }
             break;
         default:              // dw is never tiled
             M = p->maps_w; a.crop_y = d.kh; a.crop_x = d.kw;
@@ -459,6 +477,20 @@ int launch_inverse(fftconv_plan_t p, int pass, float *dst, void *ws, hipStream_t
     a.scale = 1.0f / ((float)p->N * (float)p->N);
     const unsigned blocks = (unsigned)((M + e->T - 1) / e->T);
     StageTimer timer(p, FFTCONV_STAGE_IFFT_Y + pass, stream);
+    a.parity = -1;
+    if (a.add) {
+        // overlap-add: clear dx, then one launch per parity class of tiles (windows of one class are disjoint)
+        const size_t count = (size_t)d.S * d.f * d.nh * d.nw;
+        hipLaunchKernelGGL(fill_zero_kernel, dim3(1024), dim3(256), 0, stream, dst, count);
+        if (int rc = check_launch()) return rc;
+        for (int parity = 0; parity < 4; ++parity) {
+            if ((parity >= 2 && p->nty2 < 2) || (parity % 2 == 1 && p->ntx2 < 2)) continue;   // no tile of this class
+            a.parity = parity;
+            hipLaunchKernelGGL(kernel, dim3(blocks), dim3(e->threads), e->lds_bytes, stream, a);
+            if (int rc = check_launch()) return rc;
+        }
+        return timer.finish();
+    }
     hipLaunchKernelGGL(kernel, dim3(blocks), dim3(e->threads), e->lds_bytes, stream, a);
     if (int rc = check_launch()) return rc;
     return timer.finish();
@@ -554,6 +586,11 @@ int fftconv_plan2d(fftconv_plan_t *out, const fftconv_desc2d *d)
         }
         if (N < 0) return FFTCONV_EUNSUPPORTED;   // a kernel side above 64
     }
+    // Overlap-add for bprop when a second transform of dL/dy (f' maps per tile) costs more than four
+    // passes over the far smaller dx (f maps per tile); windows of one parity class must not overlap
+    const bool overlap_add = Ly > 0 && (long)d->f * 8 <= d->fo && Ly >= d->kh - 1 && Lx >= d->kw - 1 &&
+                             !std::getenv("FFTCONV_NO_OVERLAP_ADD");
+    if (overlap_add) { nty2 = nty; ntx2 = ntx; }   // dx is assembled from the windows of the blocks of dL/dy
     const long T = (long)nty * ntx, T2 = (long)nty2 * ntx2;
     const int L = Ly;   // non-zero iff tiled
     const bool lean = (d->flags & FFTCONV_RECOMPUTE) != 0;
@@ -561,7 +598,8 @@ int fftconv_plan2d(fftconv_plan_t *out, const fftconv_desc2d *d)
     // dX and Y and the windows of bprop, whose tile counts can differ
     const long Tmax = T > T2 ? T : T2;
     const long maps_x = (long)d->S * d->f * (lean ? Tmax : T), maps_w = (long)d->fo * d->f;
-    const long maps_g = (long)d->S * d->fo * (lean ? Tmax : T), maps_g2 = L > 0 && !lean ? (long)d->S * d->fo * T2 : 0;
+    const long maps_g = (long)d->S * d->fo * (lean ? Tmax : T),
+               maps_g2 = L > 0 && !lean && !overlap_add ? (long)d->S * d->fo * T2 : 0;
     const long out_y = (long)d->S * d->fo * T, out_dx = (long)d->S * d->f * T2;
     const long lim = 0x7fffffffL;
     if (maps_x > lim || maps_w > lim || maps_g > lim || maps_g2 > lim || out_y > lim || out_dx > lim)
@@ -579,6 +617,7 @@ int fftconv_plan2d(fftconv_plan_t *out, const fftconv_desc2d *d)
     p->ntx = ntx;
     p->nty2 = nty2;
     p->ntx2 = ntx2;
+    p->overlap_add = overlap_add;
     p->maps_x = (long)d->S * d->f * T;
     p->maps_w = maps_w;
     p->maps_g = (long)d->S * d->fo * T;
@@ -638,7 +677,7 @@ size_t fftconv_slot_offset(fftconv_plan_t p, int slot)
         case FFTCONV_SPEC_X: return p->off_x;
         case FFTCONV_SPEC_W: return p->off_w;
         case FFTCONV_SPEC_G: return p->off_g;
-        case FFTCONV_SPEC_G2: return tiled(p) ? p->off_g2 : (size_t)-1;
+        case FFTCONV_SPEC_G2: return tiled(p) && !p->overlap_add ? p->off_g2 : (size_t)-1;
         case FFTCONV_SPEC_OUT: return p->off_out;
         default: return (size_t)-1;
     }
@@ -651,7 +690,7 @@ long fftconv_slot_maps(fftconv_plan_t p, int slot)
         case FFTCONV_SPEC_X: return p->maps_x;
         case FFTCONV_SPEC_W: return p->maps_w;
         case FFTCONV_SPEC_G: return p->maps_g;
-        case FFTCONV_SPEC_G2: return tiled(p) ? p->maps_g2 : -1;
+        case FFTCONV_SPEC_G2: return tiled(p) && !p->overlap_add ? p->maps_g2 : -1;
         case FFTCONV_SPEC_OUT: return p->maps_out;
         default: return -1;
     }

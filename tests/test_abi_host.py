@@ -137,6 +137,29 @@ def test_large_maps_are_tiled(fc, n, k):
     assert lean.slot_offset(fc.SPEC_G2) == lean.slot_offset(fc.SPEC_G) == sizes[0] + sizes[1]
 
 
+@pytest.mark.parametrize("n,k", [(100, 5), (224, 11), (70, 20)])
+def test_tiled_layers_with_few_input_maps_use_overlap_add(fc, n, k, monkeypatch):
+    """f * 8 <= f': bprop multiplies the blocks of dL/dy that accGrad transforms and adds the overlapping
+    windows into dx, so there is no slot for a second transform of dL/dy and dx has one window per block."""
+    S, f, fo = 2, 3, 24
+    p = fc.Plan(S, f, fo, n, k)
+    N, ((L, _), (nt, _), (nt2, _)) = p.fft_size, p.tiling
+    assert L == N - k + 1 and nt == ceil_div(n - k + 1, L) and nt2 == nt
+    assert p.slot_maps(fc.SPEC_G2) == -1 and p.slot_offset(fc.SPEC_G2) == 2 ** 64 - 1
+    B = p.num_bins
+    sizes = [(8 * B * m + 255) // 256 * 256 for m in (S * nt * nt * f, fo * f, S * nt * nt * fo, S * nt * nt * fo)]
+    assert p.workspace_bytes == sum(sizes)
+    assert p.contraction_flops == 6.0 * S * f * fo * B * nt * nt
+    monkeypatch.setenv("FFTCONV_NO_OVERLAP_ADD", "1")       # read when the plan is made
+    q = fc.Plan(S, f, fo, n, k)
+    assert q.tiling[2][0] == ceil_div(n, L) and q.slot_maps(fc.SPEC_G2) == S * q.tiling[2][0] ** 2 * fo
+    assert q.workspace_bytes > p.workspace_bytes
+    # windows of one parity class must not overlap: a kernel larger than the block keeps the other scheme
+    monkeypatch.delenv("FFTCONV_NO_OVERLAP_ADD")
+    r = fc.Plan(S, f, fo, 70, 40)
+    assert r.tiling[0][0] < 39 and r.slot_maps(fc.SPEC_G2) > 0
+
+
 def test_rectangular_plans(fc):
     """Height and width of maps and kernels per axis; the transform stays square and covers the longer side."""
     p = fc.Plan(2, 3, 4, (20, 45), (3, 7))

@@ -169,7 +169,7 @@ def test_tiled_inverse_scatters_each_tile_once(replay, N, H, k, c0):
     buf = np.concatenate([guard, dst.ravel(), guard])
     view = buf[64:64 + dst.size]
     rc = replay.replay_ifft2d_c2r_tiled(N, sp.ctypes.data_as(FP), view.ctypes.data_as(FP), M, L, L, c0, c0, H, H, C,
-                                        tx, tx * tx, L, L)
+                                        tx, tx * tx, L, L, 0, -1)
     assert rc == 0
     assert np.all(np.isnan(buf[:64])) and np.all(np.isnan(buf[-64:]))
     got = view.reshape(S, C, H, H)
@@ -232,7 +232,7 @@ def test_tiled_rectangular_windows_and_scatter(replay):
     sp = np.ascontiguousarray(np.stack([spec.real, spec.imag], -1).astype(np.float32))
     dst = np.full((S, C, H, W), np.nan, np.float32)
     rc = replay.replay_ifft2d_c2r_tiled(N, sp.ctypes.data_as(FP), dst.ctypes.data_as(FP), M, Ly, Lx, kh - 1, kw - 1, H, W, C,
-                                        tx, ty * tx, Ly, Lx)
+                                        tx, ty * tx, Ly, Lx, 0, -1)
     assert rc == 0 and not np.isnan(dst).any()
     for s in range(S):
         for t in range(ty * tx):
@@ -241,6 +241,34 @@ def test_tiled_rectangular_windows_and_scatter(replay):
                 h, w = min(Ly, H - oy), min(Lx, W - ox)
                 ref = patches[(s * ty * tx + t) * C + c, kh - 1:kh - 1 + h, kw - 1:kw - 1 + w]
                 assert np.abs(dst[s, c, oy:oy + h, ox:ox + w] - ref).max() < 3e-6
+
+
+@pytest.mark.parametrize("N,Hy,Hx,kh,kw", [(16, 37, 30, 5, 3), (28, 70, 90, 6, 9), (48, 224, 100, 11, 11), (64, 65, 130, 3, 20)])
+def test_tiled_inverse_overlap_add(replay, N, Hy, Hx, kh, kw):
+    """Overlap-add: the whole N x N output of every block's transform is added at the block's origin
+    (blocks (N-kh+1) x (N-kw+1) apart, so neighbours overlap by kh-1 / kw-1), one parity class of
+    tiles per call; after the four calls every pixel holds the sum of the windows that cover it."""
+    rng = np.random.default_rng(11 * N + Hy)
+    Ly, Lx = N - kh + 1, N - kw + 1
+    S, C = 2, 3
+    ty, tx = -(-(Hy - kh + 1) // Ly), -(-(Hx - kw + 1) // Lx)      # blocks of the (Hy-kh+1) x (Hx-kw+1) gradient
+    M = S * ty * tx * C
+    patches = rng.uniform(-1, 1, (M, N, N))
+    spec = reference_spectrum(patches, N)
+    sp = np.ascontiguousarray(np.stack([spec.real, spec.imag], -1).astype(np.float32))
+    dst = np.zeros((S, C, Hy, Hx), np.float32)
+    for parity in range(4):
+        rc = replay.replay_ifft2d_c2r_tiled(N, sp.ctypes.data_as(FP), dst.ctypes.data_as(FP), M, N, N, 0, 0, Hy, Hx, C,
+                                            tx, ty * tx, Ly, Lx, 1, parity)
+        assert rc == 0
+    ref = np.zeros((S, C, Hy, Hx))
+    for s in range(S):
+        for t in range(ty * tx):
+            oy, ox = (t // tx) * Ly, (t % tx) * Lx
+            h, w = min(N, Hy - oy), min(N, Hx - ox)
+            for c in range(C):
+                ref[s, c, oy:oy + h, ox:ox + w] += patches[(s * ty * tx + t) * C + c, :h, :w]
+    assert np.abs(dst - ref).max() < 1e-5
 
 
 @pytest.mark.parametrize("N", [8, 14, 24, 32, 40, 56, 64])

@@ -50,7 +50,7 @@ def run_three(fc, layer, x, w, g):
     dx = plan.bprop(gd, wd)
     dw = plan.accgrad(gd, xd)
     torch.cuda.synchronize()
-    expect = fc.SPEC_X | fc.SPEC_W | fc.SPEC_G | (fc.SPEC_G2 if plan.tiling[0][0] else 0)
+    expect = fc.SPEC_X | fc.SPEC_W | fc.SPEC_G | (fc.SPEC_G2 if plan.slot_maps(fc.SPEC_G2) > 0 else 0)
     assert plan.valid_slots() == expect
     return plan, y.cpu().numpy(), dx.cpu().numpy(), dw.cpu().numpy()
 
@@ -198,12 +198,18 @@ TILED_LAYERS = [
     wl.Layer("n80_k1", 2, 2, 2, 80, 1, 0.1, 97),          # k = 1: no overlap at all
     wl.Layer("n77_k6_ragged", 3, 5, 7, 77, 6, 0.1, 98),   # odd map counts: ragged transform groups
     wl.Layer("n72_k5", 2, 2, 3, 72, 5, 0.1, 101),         # tiles of a 5 * 2^m transform size
+    # f * 8 <= f': bprop adds the overlapping windows of the blocks of dL/dy into dx (overlap-add)
+    wl.Layer("oa_n100_k5", 2, 2, 16, 100, 5, 0.1, 119),
+    wl.Layer("oa_n224_k11_f3", 1, 3, 24, 224, 11, 0.05, 120),   # first-layer-like: 5 x 5 blocks, all four parity classes
+    wl.Layer("oa_n70_k20", 1, 1, 8, 70, 20, 0.05, 121),         # windows overlap by more than half a block
+    wl.Layer("oa_n130_k3", 3, 2, 17, 130, 3, 0.1, 122),         # odd map counts, 3 x 3 blocks
 ]
 
 
 @pytest.mark.parametrize("layer", TILED_LAYERS, ids=lambda l: l.name)
 def test_full_parity_tiled_layers(fc, layer):
-    """n > 64: the maps are cut into overlapping tiles (overlap-save); all three passes against the oracle."""
+    """n > 64: the maps are cut into overlapping tiles (overlap-save; for bprop with f * 8 <= f' overlap-add);
+    all three passes against the oracle."""
     print(f"\ncase {layer}", flush=True)
     x, w, g = wl.make_inputs(layer)
     plan = fc.Plan(layer.S, layer.f, layer.fo, layer.n, layer.k)
@@ -222,7 +228,9 @@ def test_full_parity_tiled_layers(fc, layer):
     dx = plan.bprop(gd, wd, outs[1][1])
     y = plan.fprop(xd, wd, outs[0][1])
     torch.cuda.synchronize()
-    assert plan.valid_slots() == fc.SPEC_X | fc.SPEC_W | fc.SPEC_G | fc.SPEC_G2
+    g2 = fc.SPEC_G2 if plan.slot_maps(fc.SPEC_G2) > 0 else 0     # no second transform of dL/dy with overlap-add
+    assert (g2 == 0) == (layer.f * 8 <= layer.fo)
+    assert plan.valid_slots() == fc.SPEC_X | fc.SPEC_W | fc.SPEC_G | g2
     for buf, _ in outs:
         assert torch.isnan(buf[:G]).all() and torch.isnan(buf[-G:]).all(), "stray write outside an output tensor"
     check(y.cpu().numpy(), direct.fprop(x, w), f"{layer.name} fprop")
@@ -267,6 +275,8 @@ RECT_LAYERS = [
     (2, 3, 2, 70, 41, 3, 6),      # tiled along both axes with different blocks
     (1, 2, 3, 30, 150, 4, 11),    # tiled because of the width only
     (2, 2, 2, 200, 10, 9, 2),     # tiled because of the height only
+    (1, 1, 8, 30, 150, 4, 11),    # overlap-add along the width only
+    (2, 2, 16, 90, 70, 5, 9),     # overlap-add, different blocks per axis
 ]
 
 
