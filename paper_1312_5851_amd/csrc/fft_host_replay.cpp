@@ -105,6 +105,8 @@ int replay_ifft2d_c2r_crop(int N, const float *spec, float *dst, int M, int crop
 {
     InvArgs a{reinterpret_cast<const cf *>(spec), dst, M, crop_y, crop_x, 1.0f / (float)(N * N)};
     a.flip = flip;
+    a.parity = -1;
+    a.bin_stride = M;
     const int T = maps_per_block(N), NX = extent_class(N, crop_y > crop_x ? crop_y : crop_x);
 #define X(n_, t_, nx_) \
     if (N == n_ && T == t_ && NX == nx_) { replay_inverse<TileGeom<n_, t_, nx_, rounds_for(n_)>>(a, accumulate != 0); return 0; }
@@ -135,6 +137,15 @@ int replay_ifft2d_c2r_tiled(int N, const float *spec, float *dst, int M, int cro
               {H, W, C, tiles_x, tiles, step_y, step_x, 0, 0}};
     a.add = add;
     a.parity = parity;
+    a.bin_stride = M;
+    if (parity >= 0) {   // one parity class of tiles: the launch covers S * cls_tiles * C transforms
+        const int tiles_y = tiles / tiles_x;
+        const int cy = (tiles_y - parity / 2 + 1) / 2, cx = (tiles_x - parity % 2 + 1) / 2;
+        if (cy < 1 || cx < 1) return 0;
+        a.cls_cx = cx;
+        a.cls_tiles = cy * cx;
+        a.M = (M / (tiles * C)) * a.cls_tiles * C;
+    }
     const int T = maps_per_block(N);
 #define X(n_, t_, nx_) \
     if constexpr (n_ == nx_) { if (N == n_ && T == t_) { replay_inverse<TileGeom<n_, t_, nx_, rounds_for(n_)>, true>(a, false); return 0; } }
@@ -151,6 +162,8 @@ int replay_ifft2d_c2r_crop_fused3(int N, const float *xs, const float *wsp, floa
 {
     if (fo % maps_per_block(N) != 0) return 2;
     InvArgs a{nullptr, dst, M, crop_y, crop_x, 1.0f / (float)(N * N)};
+    a.parity = -1;
+    a.bin_stride = M;
     a.xs = reinterpret_cast<const cf *>(xs);
     a.wsp = reinterpret_cast<const cf *>(wsp);
     a.fo = fo; a.Mx = Mx; a.Mw = Mw;

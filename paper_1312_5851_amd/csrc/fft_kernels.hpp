@@ -77,8 +77,12 @@ struct InvArgs {
     int c0_y, c0_x;       // tiled kernels: first stored row / column of the transform's output
     Tiling t;             // read by the tiled kernels only
     int add;              // tiled kernels: 1 = add the window to what dst holds (overlap-add), 0 = overwrite
-    int parity;           // tiled kernels: -1 = every tile; else only the tiles with 2 * (ty % 2) + tx % 2 == parity,
-                          // whose windows do not overlap each other
+    // Overlap-add launches handle one parity class of tiles, 2 * (ty % 2) + tx % 2 == parity, whose windows
+    // do not overlap each other: the launch's transform ml = (s * cls_tiles + t') * C + c stands for tile
+    // (2 * (t' / cls_cx) + parity / 2, 2 * (t' % cls_cx) + parity % 2) of sample s.  parity = -1: every
+    // tile, in the order of the spectrum.
+    int parity, cls_cx, cls_tiles;
+    int bin_stride;       // transforms per bin in spec (equals M unless the launch handles one class)
     int flip;             // untiled kernels: store every window rotated by 180 degrees
     // Read by the fused kernels only (fprop of a layer with very few input maps): instead of
     // reading `spec`, bin c of output map m = s * fo + j is formed on the fly as
@@ -92,8 +96,17 @@ struct InvArgs {
 
 struct TileOrigin {
     int image, oy, ox;
-    int parity;           // 2 * (ty % 2) + tx % 2
 };
+
+// Position in the spectrum (and in the order tile_origin expects) of transform ml of a launch.
+FC_HD int launch_to_spectrum_index(int ml, const InvArgs &a)
+{
+    if (a.parity < 0) return ml;
+    const int C = a.t.C, sp = ml / C, c = ml % C;
+    const int s = sp / a.cls_tiles, tc = sp % a.cls_tiles;
+    const int ty = 2 * (tc / a.cls_cx) + a.parity / 2, tx = 2 * (tc % a.cls_cx) + a.parity % 2;
+    return (s * a.t.tiles + ty * a.t.tiles_x + tx) * C + c;
+}
 
 FC_HD TileOrigin tile_origin(int m, const Tiling &t)
 {
@@ -103,7 +116,6 @@ FC_HD TileOrigin tile_origin(int m, const Tiling &t)
     o.image = s * t.C + c;
     o.oy = (tile / t.tiles_x) * t.step_y + t.org_y;
     o.ox = (tile % t.tiles_x) * t.step_x + t.org_x;
-    o.parity = 2 * ((tile / t.tiles_x) % 2) + (tile % t.tiles_x) % 2;
     return o;
 }
 
@@ -319,8 +331,8 @@ FC_HD void inv_x_load(int xt, int blk, int round, const InvArgs &a, const cf *xl
     const int mg = blk * G::T + m;
     // Lanes beyond the last map read the last map's bins (valid memory) instead of
     // branching around each load; what they compute is never stored.
-    const int mc = mg < a.M ? mg : a.M - 1;
-    const size_t M = (size_t)a.M;
+    const int mc = launch_to_spectrum_index(mg < a.M ? mg : a.M - 1, a);
+    const size_t M = (size_t)a.bin_stride;
     const cf *src = nullptr, *xp = nullptr, *wp = nullptr;
     if constexpr (FUSE > 0) {
         xp = xl;
@@ -465,7 +477,7 @@ FC_HD void inv_y_finish(int tid, int blk, const InvArgs &a, cf (&z)[G::N])
 // Tiled variant of step 2: rows and columns [c0, c0 + crop) of the transform's output go to
 // the tile's place in a larger image, clipped at the image border.  With a.add they are added to
 // what is there (overlap-add: the windows of neighbouring tiles overlap, so one launch handles
-// only tiles of one parity class, which do not).
+// the tiles of one parity class, which do not).
 template <class G>
 FC_HD void inv_y_finish_tiled(int tid, int blk, const InvArgs &a, cf (&z)[G::N])
 {
@@ -480,8 +492,7 @@ FC_HD void inv_y_finish_tiled(int tid, int blk, const InvArgs &a, cf (&z)[G::N])
         constexpr int which = decltype(wi)::value;
         const int m = blk * G::T + 2 * p + which;
         if (m >= a.M) return;
-        const TileOrigin o = tile_origin(m, a.t);
-        if (a.parity >= 0 && o.parity != a.parity) return;
+        const TileOrigin o = tile_origin(launch_to_spectrum_index(m, a), a.t);
         if (o.ox + xs >= a.t.W) return;
         const int rows = a.crop_y < a.t.H - o.oy ? a.crop_y : a.t.H - o.oy;
         float *col = a.dst + ((size_t)o.image * a.t.H + o.oy) * a.t.W + o.ox + xs;

@@ -478,15 +478,21 @@ int launch_inverse(fftconv_plan_t p, int pass, float *dst, void *ws, hipStream_t
     const unsigned blocks = (unsigned)((M + e->T - 1) / e->T);
     StageTimer timer(p, FFTCONV_STAGE_IFFT_Y + pass, stream);
     a.parity = -1;
+    a.bin_stride = (int)M;
     if (a.add) {
         // overlap-add: clear dx, then one launch per parity class of tiles (windows of one class are disjoint)
         const size_t count = (size_t)d.S * d.f * d.nh * d.nw;
         hipLaunchKernelGGL(fill_zero_kernel, dim3(1024), dim3(256), 0, stream, dst, count);
         if (int rc = check_launch()) return rc;
         for (int parity = 0; parity < 4; ++parity) {
-            if ((parity >= 2 && p->nty2 < 2) || (parity % 2 == 1 && p->ntx2 < 2)) continue;   // no tile of this class
+            const int cy = (p->nty2 - parity / 2 + 1) / 2, cx = (p->ntx2 - parity % 2 + 1) / 2;   // tiles of this class per axis
+            if (cy < 1 || cx < 1) continue;
             a.parity = parity;
-            hipLaunchKernelGGL(kernel, dim3(blocks), dim3(e->threads), e->lds_bytes, stream, a);
+            a.cls_cx = cx;
+            a.cls_tiles = cy * cx;
+            a.M = d.S * a.cls_tiles * d.f;
+            const unsigned class_blocks = (unsigned)((a.M + e->T - 1) / e->T);
+            hipLaunchKernelGGL(kernel, dim3(class_blocks), dim3(e->threads), e->lds_bytes, stream, a);
             if (int rc = check_launch()) return rc;
         }
         return timer.finish();
@@ -586,9 +592,11 @@ int fftconv_plan2d(fftconv_plan_t *out, const fftconv_desc2d *d)
         }
         if (N < 0) return FFTCONV_EUNSUPPORTED;   // a kernel side above 64
     }
-    // Overlap-add for bprop when a second transform of dL/dy (f' maps per tile) costs more than four
-    // passes over the far smaller dx (f maps per tile); windows of one parity class must not overlap
-    const bool overlap_add = Ly > 0 && (long)d->f * 8 <= d->fo && Ly >= d->kh - 1 && Lx >= d->kw - 1 &&
+    // Overlap-add for bprop when a second transform of dL/dy (f' maps per tile) costs more than clearing dx
+    // and reading and writing its larger windows (f maps per tile).  Measured at S = 128: a gain of 21 % of
+    // the step for f = 3, f' = 96, losses of 2 to 12 % for f / f' = 96 / 256 and 64 / 64; windows of one
+    // parity class must not overlap
+    const bool overlap_add = Ly > 0 && (long)d->f * 4 <= d->fo && Ly >= d->kh - 1 && Lx >= d->kw - 1 &&
                              !std::getenv("FFTCONV_NO_OVERLAP_ADD");
     if (overlap_add) { nty2 = nty; ntx2 = ntx; }   // dx is assembled from the windows of the blocks of dL/dy
     const long T = (long)nty * ntx, T2 = (long)nty2 * ntx2;

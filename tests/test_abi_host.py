@@ -109,8 +109,9 @@ def ceil_div(a, b):
 @pytest.mark.parametrize("n,k", [(65, 3), (100, 5), (128, 3), (128, 11), (224, 11), (70, 64), (96, 7)])
 def test_large_maps_are_tiled(fc, n, k):
     """n > 64: L x L output tiles with L = N - k + 1, the N among 16..64 that needs the fewest
-    transformed points; slots hold one transform per tile; an extra slot for bprop's windows."""
-    S, f, fo = 2, 3, 4
+    transformed points; slots hold one transform per tile; an extra slot for bprop's windows
+    (more input than output maps: bprop by overlap-save)."""
+    S, f, fo = 2, 5, 4
     p = fc.Plan(S, f, fo, n, k)
     N, ((L, Lx), (nt, ntx), (nt2, ntx2)) = p.fft_size, p.tiling
     assert (L, nt, nt2) == (Lx, ntx, ntx2)
@@ -139,16 +140,16 @@ def test_large_maps_are_tiled(fc, n, k):
 
 @pytest.mark.parametrize("n,k", [(100, 5), (224, 11), (70, 20)])
 def test_tiled_layers_with_few_input_maps_use_overlap_add(fc, n, k, monkeypatch):
-    """f * 8 <= f': bprop multiplies the blocks of dL/dy that accGrad transforms and adds the overlapping
+    """f * 4 <= f': bprop multiplies the blocks of dL/dy that accGrad transforms and adds the overlapping
     windows into dx, so there is no slot for a second transform of dL/dy and dx has one window per block."""
-    S, f, fo = 2, 3, 24
+    S, f, fo = 2, 3, 12
     p = fc.Plan(S, f, fo, n, k)
     N, ((L, _), (nt, _), (nt2, _)) = p.fft_size, p.tiling
     assert L == N - k + 1 and nt == ceil_div(n - k + 1, L) and nt2 == nt
     assert p.slot_maps(fc.SPEC_G2) == -1 and p.slot_offset(fc.SPEC_G2) == 2 ** 64 - 1
     B = p.num_bins
     sizes = [(8 * B * m + 255) // 256 * 256 for m in (S * nt * nt * f, fo * f, S * nt * nt * fo, S * nt * nt * fo)]
-    assert p.workspace_bytes == sum(sizes)
+    assert p.workspace_bytes == sum(sizes)      # x, w, dL/dy and a result spectrum as large as that of y
     assert p.contraction_flops == 6.0 * S * f * fo * B * nt * nt
     monkeypatch.setenv("FFTCONV_NO_OVERLAP_ADD", "1")       # read when the plan is made
     q = fc.Plan(S, f, fo, n, k)
@@ -158,6 +159,7 @@ def test_tiled_layers_with_few_input_maps_use_overlap_add(fc, n, k, monkeypatch)
     monkeypatch.delenv("FFTCONV_NO_OVERLAP_ADD")
     r = fc.Plan(S, f, fo, 70, 40)
     assert r.tiling[0][0] < 39 and r.slot_maps(fc.SPEC_G2) > 0
+    assert fc.Plan(S, 4, 15, n, k).slot_maps(fc.SPEC_G2) > 0      # not few enough input maps
 
 
 def test_rectangular_plans(fc):
@@ -167,12 +169,14 @@ def test_rectangular_plans(fc):
     assert p.slot_maps(fc.SPEC_X) == 6 and p.slot_maps(fc.SPEC_G) == 8 and p.slot_maps(fc.SPEC_W) == 12
     sq, rect = fc.Plan(2, 3, 4, 20, 3), fc.Plan(2, 3, 4, (20, 20), (3, 3))
     assert sq.fft_size == rect.fft_size and sq.workspace_bytes == rect.workspace_bytes
-    # tiled, different block sizes and counts per axis
-    p = fc.Plan(2, 3, 4, (70, 200), (3, 9))
+    # tiled, different block sizes and counts per axis (more input than output maps: bprop by overlap-save)
+    p = fc.Plan(2, 5, 4, (70, 200), (3, 9))
     N, ((Ly, Lx), (ty, tx), (ty2, tx2)) = p.fft_size, p.tiling
     assert (Ly, Lx) == (N - 2, N - 8)
     assert (ty, tx) == (ceil_div(68, Ly), ceil_div(192, Lx)) and (ty2, tx2) == (ceil_div(70, Ly), ceil_div(200, Lx))
-    assert p.slot_maps(fc.SPEC_X) == 2 * 3 * ty * tx and p.slot_maps(fc.SPEC_G2) == 2 * 4 * ty2 * tx2
+    assert p.slot_maps(fc.SPEC_X) == 2 * 5 * ty * tx and p.slot_maps(fc.SPEC_G2) == 2 * 4 * ty2 * tx2
+    q = fc.Plan(2, 3, 12, (70, 200), (3, 9))    # overlap-add: dx is assembled from the windows of the blocks of dL/dy
+    assert q.tiling == ((Ly, Lx), (ty, tx), (ty, tx)) and q.slot_maps(fc.SPEC_G2) == -1
     for bad in (((8, 8), (9, 3)), ((8, 8), (3, 9)), ((0, 8), (1, 1)), ((8, 8), (0, 1))):
         with pytest.raises(fc.FftconvError) as ei:
             fc.Plan(1, 1, 1, *bad)
