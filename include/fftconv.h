@@ -176,7 +176,7 @@ int fftconv_fprop(fftconv_plan_t p, const float *x, const float *w, float *y, vo
 /* Eq. (2), summed over j: dx[s,i] = sum_j g[s,j] * w[j,i]^T (adjoint of fprop in x).
  * Uses the g and w slots; stores the full n x n window.  dx is overwritten.
  *
- * Layers with f <= 4 (spectra cached, n <= 64, S <= 256): if the slots of x, w and g are
+ * Layers with f <= 4 (spectra cached; tiled layers only if bprop uses overlap-add): if the slots of x, w and g are
  * all valid, the first of fftconv_bprop / fftconv_accgrad to be called forms the result
  * spectra of both in one pass over the spectrum of dL/dy and leaves the other's in
  * FFTCONV_SPEC_OUT; the other pass, called next with the same tensors, only

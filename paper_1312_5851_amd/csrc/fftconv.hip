@@ -151,6 +151,8 @@ struct fftconv_plan_s {
     // the OUT slot; `ready` says which of the two is waiting there for its pass (kReady*).
     bool shared_pass_ok;
     size_t off_shared_dw;   // byte offset of dWh inside the OUT slot (dXh is at its start)
+    size_t off_shared_part; // ... and of the partial sums of dWh, if a bin's rows are split over several workgroups
+    int shared_row_groups;
     unsigned ready;
     void *last_ws;
     int gemm_tile[3];
@@ -381,16 +383,26 @@ int launch_shared_pass(fftconv_plan_t p, int pass, void *ws, hipStream_t stream)
     a.W = slot_ptr(p, ws, FFTCONV_SPEC_W);
     a.DX = reinterpret_cast<cf *>(out);
     a.DW = reinterpret_cast<cf *>(out + p->off_shared_dw);
-    a.M = p->d.S;
+    a.DWpart = reinterpret_cast<cf *>(out + p->off_shared_part);
+    a.M = p->d.S * p->nty * p->ntx;   // the tiles of a sample are extra samples
     a.N = p->d.fo;
     a.bins = p->B;
+    a.row_groups = p->shared_row_groups;
     const int F = p->d.f;
-    const int lds_bytes = (64 * 65 + 2 * 64 * F + kSkinnyWaves * ((a.M + 63) / 64) * 64 * F) * 8;
+    const int rows = a.M < kSharedPassMaxRows ? a.M : kSharedPassMaxRows;
+    const int lds_bytes = (64 * 65 + 2 * 64 * F + kSkinnyWaves * ((rows + 63) / 64) * 64 * F) * 8;
+    const long blocks = (long)a.bins * a.row_groups;
+    if (blocks > 0x7fffffffL) return FFTCONV_EUNSUPPORTED;
     SharedPassKernel kernel = kSharedPass[F - 1];
     if (int rc = allow_lds(kernel, lds_bytes)) return rc;
     StageTimer timer(p, FFTCONV_STAGE_CGEMM_FPROP + pass, stream);
-    hipLaunchKernelGGL(kernel, dim3((unsigned)a.bins), dim3(kSkinnyThreads), lds_bytes, stream, a);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kSkinnyThreads), lds_bytes, stream, a);
     if (int rc = check_launch()) return rc;
+    if (a.row_groups > 1) {
+        hipLaunchKernelGGL(sum_row_groups_kernel, dim3(512), dim3(256), 0, stream, a.DWpart, a.DW,
+                           (size_t)a.bins * a.N * F, a.row_groups);
+        if (int rc = check_launch()) return rc;
+    }
     return timer.finish();
 }
 
@@ -646,11 +658,18 @@ int fftconv_plan2d(fftconv_plan_t *out, const fftconv_desc2d *d)
     }
     p->valid = 0;
     p->ready = 0;
-    // one pass over the spectrum of dL/dy for bprop and accGrad: few input maps, spectra cached, untiled,
-    // the partial sums of dXh fit the LDS, and dXh and dWh fit the OUT slot side by side
-    p->off_shared_dw = align_up((size_t)d->S * d->f * p->B * sizeof(cf));
-    p->shared_pass_ok = !lean && L == 0 && d->f <= 4 && d->S <= kSharedPassMaxRows &&
-                        p->off_shared_dw + (size_t)maps_w * p->B * sizeof(cf) <= (size_t)p->maps_out * p->B * sizeof(cf);
+    // one pass over the spectrum of dL/dy for bprop and accGrad: few input maps, spectra cached, both passes
+    // on the same transforms of dL/dy (untiled, or tiled with overlap-add), and dXh, dWh and the partial
+    // sums of dWh fit the OUT slot side by side
+    {
+        const size_t rows = (size_t)d->S * T, dw_bytes = align_up((size_t)maps_w * p->B * sizeof(cf));
+        p->shared_row_groups = (int)((rows + kSharedPassMaxRows - 1) / kSharedPassMaxRows);
+        p->off_shared_dw = align_up(rows * d->f * p->B * sizeof(cf));
+        p->off_shared_part = p->off_shared_dw + dw_bytes;
+        const size_t need = p->off_shared_part + (p->shared_row_groups > 1 ? (size_t)p->shared_row_groups * dw_bytes : 0);
+        p->shared_pass_ok = !lean && (L == 0 || overlap_add) && d->f <= 4 && p->maps_out > 0 &&
+                            need <= (size_t)p->maps_out * p->B * sizeof(cf);
+    }
     p->last_ws = nullptr;
     p->profiling = 0;
     for (int pass = 0; pass < 3; ++pass) {

@@ -184,7 +184,8 @@ __global__ __launch_bounds__(kSkinnyThreads) void skinny_bprop_kernel(SkinnyArgs
 // the HBM traffic of the pair:
 //     dXh[b][m][i] = sum_j      Gh[b][m][j]  * Wh[b][j][i]
 //     dWh[b][j][i] = sum_m conj(Gh[b][m][j]) * Xh[b][m][i]
-// One workgroup per bin walks Gh[b] in 64 x 64 tiles, column block by column block.  A tile comes
+// One workgroup per bin (per 256 rows of a bin, if it has more: the partial dWh of the row groups
+// are then added by sum_row_groups_kernel) walks Gh[b] in 64 x 64 tiles, column block by column block.  A tile comes
 // in with lanes along j and is handed over through LDS; then, for dXh, lane = row and the four
 // waves each sum a quarter of the tile's columns; for dWh, lane = column and the four waves each
 // sum a quarter of the tile's rows.  dWh of a column block is complete when its last tile is done;
@@ -195,10 +196,12 @@ struct SharedPassArgs {
     const cf *W;   // Wh  [bins][N][F]
     cf *DX;        // dXh [bins][M][F]
     cf *DW;        // dWh [bins][N][F]
+    cf *DWpart;    // row_groups > 1: partial sums of dWh, [row_groups][bins][N][F]
     int M, N, bins;
+    int row_groups;   // ceil(M / kSharedPassMaxRows) workgroups per bin, each on its own rows
 };
 
-constexpr int kSharedPassMaxRows = 256;   // M above this: the partial sums of dXh would crowd the LDS
+constexpr int kSharedPassMaxRows = 256;   // rows per workgroup: more, and the partial sums of dXh would crowd the LDS
 
 template <int F>
 constexpr int shared_pass_lds_elems(int M)
@@ -206,7 +209,7 @@ constexpr int shared_pass_lds_elems(int M)
     return 64 * 65 + 2 * 64 * F + kSkinnyWaves * ((M + 63) / 64) * 64 * F;
 }
 
-// grid = bins workgroups of kSkinnyThreads threads, shared_pass_lds_elems<F>(M) * 8 bytes of dynamic LDS
+// grid = bins * row_groups workgroups of kSkinnyThreads threads, shared_pass_lds_elems<F>(M) * 8 bytes of dynamic LDS
 template <int F>
 __global__ __launch_bounds__(kSkinnyThreads) void skinny_bprop_accgrad_kernel(SharedPassArgs a)
 {
@@ -219,10 +222,12 @@ __global__ __launch_bounds__(kSkinnyThreads) void skinny_bprop_accgrad_kernel(Sh
     cf *red = tile;                                     // [waves][64][F], used between two column blocks only
     static_assert(kSkinnyWaves * 64 * F <= 64 * TS, "the reduction buffer takes the tile's place");
     const int tid = (int)threadIdx.x, lane = tid % 64, q = wave_index();
-    const int bin = (int)blockIdx.x;
-    const int nmb = (a.M + 63) / 64, njc = (a.N + 63) / 64, Mp = nmb * 64;
-    const cf *Gb = a.G + (size_t)bin * a.M * a.N;
-    const cf *Xb = a.X + (size_t)bin * a.M * F;
+    const int bin = (int)blockIdx.x / a.row_groups, grp = (int)blockIdx.x % a.row_groups;
+    // this workgroup's rows [m0, m0 + Mr) of the bin
+    const int m0 = grp * kSharedPassMaxRows, Mr = a.M - m0 < kSharedPassMaxRows ? a.M - m0 : kSharedPassMaxRows;
+    const int nmb = (Mr + 63) / 64, njc = (a.N + 63) / 64, Mp = nmb * 64;
+    const cf *Gb = a.G + ((size_t)bin * a.M + m0) * a.N;
+    const cf *Xb = a.X + ((size_t)bin * a.M + m0) * F;
     const cf *Wb = a.W + (size_t)bin * a.N * F;
 
     // lane (row r, quarter q) owns dxacc[q][mb * 64 + r][*] until the final sum
@@ -238,14 +243,14 @@ __global__ __launch_bounds__(kSkinnyThreads) void skinny_bprop_accgrad_kernel(Sh
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int row = mb * 64 + q + kSkinnyWaves * u;
-            ok[u] = row < a.M && j < a.N;
-            regs[u] = Gb[(size_t)(row < a.M ? row : a.M - 1) * a.N + jcl];   // clamped address, masked at the hand-over
+            ok[u] = row < Mr && j < a.N;
+            regs[u] = Gb[(size_t)(row < Mr ? row : Mr - 1) * a.N + jcl];   // clamped address, masked at the hand-over
         }
         if (tid < 64 * F) {
             const int m = mb * 64 + tid / F, jw = jc * 64 + tid / F;
-            xok = m < a.M;
+            xok = m < Mr;
             wok = jw < a.N;
-            xreg = Xb[(size_t)(xok ? m : a.M - 1) * F + tid % F];
+            xreg = Xb[(size_t)(xok ? m : Mr - 1) * F + tid % F];
             wreg = Wb[(size_t)(wok ? jw : a.N - 1) * F + tid % F];
         }
     };
@@ -299,7 +304,8 @@ __global__ __launch_bounds__(kSkinnyThreads) void skinny_bprop_accgrad_kernel(Sh
         for (int i = 0; i < F; ++i) red[(q * 64 + lane) * F + i] = dw[i];
         __syncthreads();
         if (q == 0 && jc * 64 + lane < a.N) {
-            cf *out = a.DW + ((size_t)bin * a.N + jc * 64 + lane) * F;
+            // with several row groups per bin, partial sums [group][bin][j][i] that a second kernel adds up
+            cf *out = (a.row_groups > 1 ? a.DWpart + (size_t)grp * a.bins * a.N * F : a.DW) + ((size_t)bin * a.N + jc * 64 + lane) * F;
 #pragma unroll
             for (int i = 0; i < F; ++i) {
                 cf sum = red[lane * F + i];
@@ -313,8 +319,8 @@ __global__ __launch_bounds__(kSkinnyThreads) void skinny_bprop_accgrad_kernel(Sh
     // dXh: add the four quarters; wave q takes the row blocks q, q + 4, ...
     for (int mb = q; mb < nmb; mb += kSkinnyWaves) {
         const int m = mb * 64 + lane;
-        if (m < a.M) {
-            cf *out = a.DX + ((size_t)bin * a.M + m) * F;
+        if (m < Mr) {
+            cf *out = a.DX + ((size_t)bin * a.M + m0 + m) * F;
 #pragma unroll
             for (int i = 0; i < F; ++i) {
                 cf sum = dxacc[(size_t)m * F + i];
@@ -323,6 +329,16 @@ __global__ __launch_bounds__(kSkinnyThreads) void skinny_bprop_accgrad_kernel(Sh
                 out[i] = sum;
             }
         }
+    }
+}
+
+// dWh = sum over row groups of the partial sums the kernel above leaves, in a fixed order.
+__global__ __launch_bounds__(256) void sum_row_groups_kernel(const cf *part, cf *out, size_t count, int groups)
+{
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < count; e += (size_t)gridDim.x * blockDim.x) {
+        cf sum = part[e];
+        for (int g = 1; g < groups; ++g) sum = sum + part[(size_t)g * count + e];
+        out[e] = sum;
     }
 }
 
