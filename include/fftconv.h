@@ -38,7 +38,8 @@
  * layers store and re-read the product spectrum instead of forming it inside the inverse
  * transform (which needs fo to be a multiple of the 16 to 64 maps a workgroup transforms),
  * FFTCONV_NO_FUSED_ORDER keeps that kernel's plain block order.  Read when a plan is made:
- * FFTCONV_NO_OVERLAP_ADD keeps the second transform of dL/dy for bprop of tiled layers.
+ * FFTCONV_NO_OVERLAP_ADD keeps the second transform of dL/dy for bprop of tiled layers,
+ * FFTCONV_TILE_SIZE=N forces the transform size of the tiles.
  */
 #ifndef FFTCONV_H
 #define FFTCONV_H

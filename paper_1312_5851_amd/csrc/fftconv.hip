@@ -585,32 +585,35 @@ int fftconv_plan2d(fftconv_plan_t *out, const fftconv_desc2d *d)
     if ((d->flags & ~(unsigned)(FFTCONV_RECOMPUTE | FFTCONV_TRUE_CONV)) != 0) return FFTCONV_EUNSUPPORTED;
     const int noh = d->nh - d->kh + 1, now = d->nw - d->kw + 1;
     int N = fft_size_for(d->nh > d->nw ? d->nh : d->nw), Ly = 0, Lx = 0, nty = 1, ntx = 1, nty2 = 1, ntx2 = 1;
+    // Overlap-add for bprop of a tiled layer when a second transform of dL/dy (f' maps per tile) costs more
+    // than clearing dx and reading and writing its larger windows (f maps per tile).  Measured at S = 128: a
+    // gain of 21 % of the step for f = 3, f' = 96, losses of 2 to 12 % for f / f' = 96 / 256 and 64 / 64.
+    const bool few_input_maps = (long)d->f * 4 <= d->fo && !std::getenv("FFTCONV_NO_OVERLAP_ADD");
+    bool overlap_add = false;
     if (N < 0) {
         // Larger than the largest transform: cut into tiles of (N - kh + 1) x (N - kw + 1) outputs
         // (overlap-save).  Pick the tile transform that needs the fewest transformed points over
         // the tiles of y and of dx together.
         static const int sizes[] = {16, 20, 24, 28, 32, 40, 48, 56, 64};
         double best = -1.0;
+        const char *forced = std::getenv("FFTCONV_TILE_SIZE");   // for measurements: only this tile transform
         for (int cand : sizes) {
             const int ly = cand - d->kh + 1, lx = cand - d->kw + 1;
-            if (ly < 1 || lx < 1) continue;
+            if (ly < 1 || lx < 1 || (forced && std::atoi(forced) != cand)) continue;
             const long ay = (noh + ly - 1) / ly, ax = (now + lx - 1) / lx;
-            const long by = (d->nh + ly - 1) / ly, bx = (d->nw + lx - 1) / lx;
+            long by = (d->nh + ly - 1) / ly, bx = (d->nw + lx - 1) / lx;
+            // with overlap-add dx is assembled from the windows of the blocks of dL/dy; the windows of one
+            // parity class of tiles must not overlap
+            const bool oa = few_input_maps && ly >= d->kh - 1 && lx >= d->kw - 1;
+            if (oa) { by = ay; bx = ax; }
             const double cost = (double)(ay * ax + by * bx) * cand * cand;
             if (best < 0.0 || cost < best) {
-                best = cost; N = cand; Ly = ly; Lx = lx;
+                best = cost; N = cand; Ly = ly; Lx = lx; overlap_add = oa;
                 nty = (int)ay; ntx = (int)ax; nty2 = (int)by; ntx2 = (int)bx;
             }
         }
         if (N < 0) return FFTCONV_EUNSUPPORTED;   // a kernel side above 64
     }
-    // Overlap-add for bprop when a second transform of dL/dy (f' maps per tile) costs more than clearing dx
-    // and reading and writing its larger windows (f maps per tile).  Measured at S = 128: a gain of 21 % of
-    // the step for f = 3, f' = 96, losses of 2 to 12 % for f / f' = 96 / 256 and 64 / 64; windows of one
-    // parity class must not overlap
-    const bool overlap_add = Ly > 0 && (long)d->f * 4 <= d->fo && Ly >= d->kh - 1 && Lx >= d->kw - 1 &&
-                             !std::getenv("FFTCONV_NO_OVERLAP_ADD");
-    if (overlap_add) { nty2 = nty; ntx2 = ntx; }   // dx is assembled from the windows of the blocks of dL/dy
     const long T = (long)nty * ntx, T2 = (long)nty2 * ntx2;
     const int L = Ly;   // non-zero iff tiled
     const bool lean = (d->flags & FFTCONV_RECOMPUTE) != 0;

@@ -153,8 +153,12 @@ def test_tiled_layers_with_few_input_maps_use_overlap_add(fc, n, k, monkeypatch)
     assert p.contraction_flops == 6.0 * S * f * fo * B * nt * nt
     monkeypatch.setenv("FFTCONV_NO_OVERLAP_ADD", "1")       # read when the plan is made
     q = fc.Plan(S, f, fo, n, k)
-    assert q.tiling[2][0] == ceil_div(n, L) and q.slot_maps(fc.SPEC_G2) == S * q.tiling[2][0] ** 2 * fo
+    Lq = q.tiling[0][0]
+    assert q.tiling[2][0] == ceil_div(n, Lq) and q.slot_maps(fc.SPEC_G2) == S * q.tiling[2][0] ** 2 * fo
     assert q.workspace_bytes > p.workspace_bytes
+    # the tile size is the one with the fewest transformed points, counting the blocks of dL/dy twice
+    cost = lambda c: 2 * ceil_div(n - k + 1, c - k + 1) ** 2 * c * c
+    assert all(cost(N) <= cost(c) for c in (16, 20, 24, 28, 32, 40, 48, 56, 64) if c - k + 1 >= k - 1 and c - k + 1 >= 1)
     # windows of one parity class must not overlap: a kernel larger than the block keeps the other scheme
     monkeypatch.delenv("FFTCONV_NO_OVERLAP_ADD")
     r = fc.Plan(S, f, fo, 70, 40)
