@@ -75,7 +75,10 @@ static void replay_inverse(const InvArgs &a, bool acc)
             for (int tid = 0; tid < G::THREADS; ++tid) inv_y_gather<G, r>(tid, lds.data(), regs<G>(z, tid));
         });
         for (int tid = 0; tid < G::THREADS; ++tid) {
-            if constexpr (TILED) inv_y_finish_tiled<G>(tid, blk, a, regs<G>(z, tid));
+            if constexpr (TILED) {
+                if (a.add) inv_y_finish_tiled<G, true>(tid, blk, a, regs<G>(z, tid));
+                else inv_y_finish_tiled<G, false>(tid, blk, a, regs<G>(z, tid));
+            }
             else if (acc) inv_y_finish<G, true>(tid, blk, a, regs<G>(z, tid));
             else inv_y_finish<G, false>(tid, blk, a, regs<G>(z, tid));
         }
@@ -115,12 +118,19 @@ int replay_ifft2d_c2r_crop(int N, const float *spec, float *dst, int M, int crop
     return 1;
 }
 
+// Row and column of tile t under either numbering (for the tests' expected values).
+void replay_tile_row_col(int t, int tiles_x, int tiles, int by_class, int *ty, int *tx)
+{
+    const Tiling tl{0, 0, 1, tiles_x, tiles, 0, 0, 0, 0, by_class};
+    tile_row_col(t, tl, *ty, *tx);
+}
+
 // Tiled variants: src / dst are [S][C][H][W] images, M = S * tiles * C transforms of size N
 // (the full-extent geometry of N), tile t of an image at (ty * step + org, tx * step + org).
 int replay_fft2d_r2c_tiled(int N, const float *src, float *spec, int M, int ext_y, int ext_x, int H, int W, int C,
-                           int tiles_x, int tiles, int step_y, int step_x, int org_y, int org_x)
+                           int tiles_x, int tiles, int step_y, int step_x, int org_y, int org_x, int by_class)
 {
-    FwdArgs a{src, reinterpret_cast<cf *>(spec), M, ext_y, ext_x, {H, W, C, tiles_x, tiles, step_y, step_x, org_y, org_x}};
+    FwdArgs a{src, reinterpret_cast<cf *>(spec), M, ext_y, ext_x, {H, W, C, tiles_x, tiles, step_y, step_x, org_y, org_x, by_class}};
     const int T = maps_per_block(N);
 #define X(n_, t_, nx_) \
     if (N == n_ && T == t_ && n_ == nx_) { replay_forward<TileGeom<n_, t_, nx_, rounds_for(n_)>, true>(a); return 0; }
@@ -131,10 +141,11 @@ int replay_fft2d_r2c_tiled(int N, const float *src, float *spec, int M, int ext_
 
 // add / parity: overlap-add of the windows of one parity class of tiles (parity -1: every tile).
 int replay_ifft2d_c2r_tiled(int N, const float *spec, float *dst, int M, int crop_y, int crop_x, int c0_y, int c0_x,
-                            int H, int W, int C, int tiles_x, int tiles, int step_y, int step_x, int add, int parity)
+                            int H, int W, int C, int tiles_x, int tiles, int step_y, int step_x, int add, int parity,
+                            int by_class)
 {
     InvArgs a{reinterpret_cast<const cf *>(spec), dst, M, crop_y, crop_x, 1.0f / (float)(N * N), c0_y, c0_x,
-              {H, W, C, tiles_x, tiles, step_y, step_x, 0, 0}};
+              {H, W, C, tiles_x, tiles, step_y, step_x, 0, 0, by_class}};
     a.add = add;
     a.parity = parity;
     a.bin_stride = M;

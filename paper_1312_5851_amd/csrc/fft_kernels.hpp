@@ -56,7 +56,40 @@ struct Tiling {
     int tiles_x, tiles;   // tiles per image row, tiles per image
     int step_y, step_x;   // distance between neighbouring tile origins
     int org_y, org_x;     // offset of the first origin (0, or -(k-1) for the windows of bprop)
+    // 0: tile t is (t / tiles_x, t % tiles_x).  1: the tiles are numbered parity class by parity class
+    // (class 2 * (ty % 2) + tx % 2, classes in order 0..3, row-major inside a class), so that the
+    // transforms an overlap-add launch reads are neighbours in the spectrum.
+    int by_class;
 };
+
+// Row and column of tile t of a Tiling.
+FC_HD void tile_row_col(int t, const Tiling &tl, int &ty, int &tx)
+{
+    if (!tl.by_class) {
+        ty = t / tl.tiles_x;
+        tx = t % tl.tiles_x;
+        return;
+    }
+    const int tiles_y = tl.tiles / tl.tiles_x;
+    const int cy0 = (tiles_y + 1) / 2, cx0 = (tl.tiles_x + 1) / 2, cx1 = tl.tiles_x / 2;
+    const int n0 = cy0 * cx0, n1 = cy0 * cx1, n2 = (tiles_y / 2) * cx0;
+    int cls = 0, local = t;
+    if (local >= n0) { local -= n0; cls = 1; }
+    if (cls == 1 && local >= n1) { local -= n1; cls = 2; }
+    if (cls == 2 && local >= n2) { local -= n2; cls = 3; }
+    const int cx = (cls % 2) ? cx1 : cx0;
+    ty = 2 * (local / cx) + cls / 2;
+    tx = 2 * (local % cx) + cls % 2;
+}
+
+// First tile number of parity class cls under by_class numbering.
+FC_HD int tile_class_start(int cls, const Tiling &tl)
+{
+    const int tiles_y = tl.tiles / tl.tiles_x;
+    const int cy0 = (tiles_y + 1) / 2, cx0 = (tl.tiles_x + 1) / 2, cx1 = tl.tiles_x / 2;
+    const int n0 = cy0 * cx0, n1 = cy0 * cx1, n2 = (tiles_y / 2) * cx0;
+    return cls == 0 ? 0 : (cls == 1 ? n0 : (cls == 2 ? n0 + n1 : n0 + n1 + n2));
+}
 
 struct FwdArgs {
     const float *src;     // [M][ext_y][ext_x] real maps (tiled kernels: [S][C][H][W] images)
@@ -104,6 +137,7 @@ FC_HD int launch_to_spectrum_index(int ml, const InvArgs &a)
     if (a.parity < 0) return ml;
     const int C = a.t.C, sp = ml / C, c = ml % C;
     const int s = sp / a.cls_tiles, tc = sp % a.cls_tiles;
+    if (a.t.by_class) return (s * a.t.tiles + tile_class_start(a.parity, a.t) + tc) * C + c;
     const int ty = 2 * (tc / a.cls_cx) + a.parity / 2, tx = 2 * (tc % a.cls_cx) + a.parity % 2;
     return (s * a.t.tiles + ty * a.t.tiles_x + tx) * C + c;
 }
@@ -114,8 +148,10 @@ FC_HD TileOrigin tile_origin(int m, const Tiling &t)
     const int s = sp / t.tiles, tile = sp % t.tiles;
     TileOrigin o;
     o.image = s * t.C + c;
-    o.oy = (tile / t.tiles_x) * t.step_y + t.org_y;
-    o.ox = (tile % t.tiles_x) * t.step_x + t.org_x;
+    int ty, tx;
+    tile_row_col(tile, t, ty, tx);
+    o.oy = ty * t.step_y + t.org_y;
+    o.ox = tx * t.step_x + t.org_x;
     return o;
 }
 
@@ -475,10 +511,10 @@ FC_HD void inv_y_finish(int tid, int blk, const InvArgs &a, cf (&z)[G::N])
 }
 
 // Tiled variant of step 2: rows and columns [c0, c0 + crop) of the transform's output go to
-// the tile's place in a larger image, clipped at the image border.  With a.add they are added to
+// the tile's place in a larger image, clipped at the image border.  With ADD (and a.add) they are added to
 // what is there (overlap-add: the windows of neighbouring tiles overlap, so one launch handles
 // the tiles of one parity class, which do not).
-template <class G>
+template <class G, bool ADD = false>
 FC_HD void inv_y_finish_tiled(int tid, int blk, const InvArgs &a, cf (&z)[G::N])
 {
     constexpr int N = G::N, NX = G::NX;
@@ -496,14 +532,36 @@ FC_HD void inv_y_finish_tiled(int tid, int blk, const InvArgs &a, cf (&z)[G::N])
         if (o.ox + xs >= a.t.W) return;
         const int rows = a.crop_y < a.t.H - o.oy ? a.crop_y : a.t.H - o.oy;
         float *col = a.dst + ((size_t)o.image * a.t.H + o.oy) * a.t.W + o.ox + xs;
+        if constexpr (ADD) {
+            // overlap-add (c0 = 0): the old values of a group of rows are all loaded before the first of them
+            // is needed, so that their latencies overlap instead of adding up row by row
+            constexpr int GROUP = N < 16 ? N : 16;
+            static_for<0, N / GROUP>([&](auto gi) {
+                constexpr int y0 = decltype(gi)::value * GROUP;
+                float old[GROUP];
+                static_for<0, GROUP>([&](auto yi) {
+                    constexpr int y = y0 + decltype(yi)::value;
+                    old[y - y0] = y < rows ? col[(size_t)y * a.t.W] : 0.0f;
+                });
+                static_for<0, GROUP>([&](auto yi) {
+                    constexpr int y = y0 + decltype(yi)::value;
+                    const cf v = z[brev<N>(y)];
+                    if (y < rows) col[(size_t)y * a.t.W] = old[y - y0] + (which == 0 ? v.x : v.y) * a.scale;
+                });
+            });
+            static_for<(N / GROUP) * GROUP, N>([&](auto yi) {   // rows left over when N is not a multiple of the group
+                constexpr int y = decltype(yi)::value;
+                const cf v = z[brev<N>(y)];
+                if (y < rows) col[(size_t)y * a.t.W] += (which == 0 ? v.x : v.y) * a.scale;
+            });
+            return;
+        }
         static_for<0, N>([&](auto yi) {
             constexpr int y = decltype(yi)::value;
             const int ys = y - a.c0_y;
             if (ys >= 0 && ys < rows) {
                 const cf v = z[brev<N>(y)];
-                const float r = (which == 0 ? v.x : v.y) * a.scale;
-                float *out = col + (size_t)ys * a.t.W;
-                *out = a.add ? *out + r : r;
+                col[(size_t)ys * a.t.W] = (which == 0 ? v.x : v.y) * a.scale;
             }
         });
     });
@@ -604,7 +662,7 @@ __global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void ifft2d_c2r_crop
 }
 
 // Same schedule, output scattered to tiles of a larger image (never accumulating).
-template <class G, int FUSE = 0>
+template <class G, int FUSE = 0, bool ADD = false>   // ADD: overlap-add of the windows (a.add must be set)
 __global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void ifft2d_c2r_tiled_kernel(InvArgs a)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -621,7 +679,7 @@ __global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void ifft2d_c2r_tile
         __syncthreads();
         inv_y_gather<G, r>(tid, lds, z);
     });
-    inv_y_finish_tiled<G>(tid, blk, a, z);
+    inv_y_finish_tiled<G, ADD>(tid, blk, a, z);
 }
 #endif
 

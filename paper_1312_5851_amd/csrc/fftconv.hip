@@ -41,7 +41,7 @@ struct FftEntry {
     FwdKernel fwd;
     InvKernel inv, inv_acc;
     FwdKernel fwd_tiled;   // full-extent geometries (NX == N) of the sizes used for tiles only
-    InvKernel inv_tiled;
+    InvKernel inv_tiled, inv_tiled_add;   // ... writing each window once / adding overlapping windows
 };
 
 // Tiles use the full-extent geometry of N >= 16 (smaller transforms would be mostly overlap).
@@ -58,12 +58,19 @@ constexpr InvKernel tiled_inv_kernel()
     else return nullptr;
 }
 
+template <int N, int T, int NX>
+constexpr InvKernel tiled_add_inv_kernel()
+{
+    if constexpr (NX == N && N >= 16) return ifft2d_c2r_tiled_kernel<TileGeom<N, T, NX, rounds_for(N)>, 0, true>;
+    else return nullptr;
+}
+
 #define X(n_, t_, nx_)                                                                          \
     {n_, t_, nx_, TileGeom<n_, t_, nx_, rounds_for(n_)>::THREADS, TileGeom<n_, t_, nx_, rounds_for(n_)>::LDS_BYTES, \
      fft2d_r2c_kernel<TileGeom<n_, t_, nx_, rounds_for(n_)>>,                                    \
      ifft2d_c2r_crop_kernel<TileGeom<n_, t_, nx_, rounds_for(n_)>, false>,                       \
      ifft2d_c2r_crop_kernel<TileGeom<n_, t_, nx_, rounds_for(n_)>, true>,                        \
-     tiled_fwd_kernel<n_, t_, nx_>(), tiled_inv_kernel<n_, t_, nx_>()},
+     tiled_fwd_kernel<n_, t_, nx_>(), tiled_inv_kernel<n_, t_, nx_>(), tiled_add_inv_kernel<n_, t_, nx_>()},
 const FftEntry kFftTable[] = {FFTCONV_FOR_EACH_GEOM(X)};
 #undef X
 
@@ -271,19 +278,19 @@ int launch_forward(fftconv_plan_t p, int slot, const float *src, void *ws, hipSt
     switch (slot) {
         case FFTCONV_SPEC_X:   // dense N x N windows of x, one per output tile
             M = p->maps_x; ext_y = tiled(p) ? p->N : d.nh; ext_x = tiled(p) ? p->N : d.nw; stage = FFTCONV_STAGE_FFT_X;
-            t = Tiling{d.nh, d.nw, d.f, p->ntx, p->nty * p->ntx, p->Ly, p->Lx, 0, 0};
+            t = Tiling{d.nh, d.nw, d.f, p->ntx, p->nty * p->ntx, p->Ly, p->Lx, 0, 0, p->overlap_add ? 1 : 0};
             break;
         case FFTCONV_SPEC_W:   // kernels are never tiled
             M = p->maps_w; ext_y = d.kh; ext_x = d.kw; stage = FFTCONV_STAGE_FFT_W;
             break;
         case FFTCONV_SPEC_G:   // Ly x Lx blocks of dL/dy
             M = p->maps_g; ext_y = tiled(p) ? p->Ly : p->noh; ext_x = tiled(p) ? p->Lx : p->now; stage = FFTCONV_STAGE_FFT_G;
-            t = Tiling{p->noh, p->now, d.fo, p->ntx, p->nty * p->ntx, p->Ly, p->Lx, 0, 0};
+            t = Tiling{p->noh, p->now, d.fo, p->ntx, p->nty * p->ntx, p->Ly, p->Lx, 0, 0, p->overlap_add ? 1 : 0};
             break;
         case FFTCONV_SPEC_G2:  // N x N windows of dL/dy starting (kh-1, kw-1) before each tile of dx
             if (!tiled(p) || p->overlap_add) return FFTCONV_EINVAL;
             M = p->maps_g2; ext_y = ext_x = p->N; stage = FFTCONV_STAGE_FFT_G;
-            t = Tiling{p->noh, p->now, d.fo, p->ntx2, p->nty2 * p->ntx2, p->Ly, p->Lx, -(d.kh - 1), -(d.kw - 1)};
+            t = Tiling{p->noh, p->now, d.fo, p->ntx2, p->nty2 * p->ntx2, p->Ly, p->Lx, -(d.kh - 1), -(d.kw - 1), 0};
             break;
         default: return FFTCONV_EINVAL;
     }
@@ -450,12 +457,12 @@ int launch_inverse(fftconv_plan_t p, int pass, float *dst, void *ws, hipStream_t
     switch (pass) {
         case FFTCONV_FPROP:   // tiles of y: output rows [0, Ly) and columns [0, Lx) of each transform
             M = p->maps_g; a.crop_y = tiled(p) ? p->Ly : p->noh; a.crop_x = tiled(p) ? p->Lx : p->now;
-            a.t = Tiling{p->noh, p->now, d.fo, p->ntx, p->nty * p->ntx, p->Ly, p->Lx, 0, 0};
+            a.t = Tiling{p->noh, p->now, d.fo, p->ntx, p->nty * p->ntx, p->Ly, p->Lx, 0, 0, p->overlap_add ? 1 : 0};
             break;
         case FFTCONV_BPROP:   // tiles of dx: rows [kh-1, N), columns [kw-1, N), the part of the circular result free of wrap-around
             M = tiled(p) ? (long)d.S * p->nty2 * p->ntx2 * d.f : p->maps_x;
             a.crop_y = tiled(p) ? p->Ly : d.nh; a.crop_x = tiled(p) ? p->Lx : d.nw;
-            a.t = Tiling{d.nh, d.nw, d.f, p->ntx2, p->nty2 * p->ntx2, p->Ly, p->Lx, 0, 0};
+            a.t = Tiling{d.nh, d.nw, d.f, p->ntx2, p->nty2 * p->ntx2, p->Ly, p->Lx, 0, 0, p->overlap_add ? 1 : 0};
             a.c0_y = d.kh - 1; a.c0_x = d.kw - 1;
             if (p->overlap_add) {   // the whole N x N output of a block's transform, placed at the block's origin
                 a.crop_y = a.crop_x = p->N;
@@ -470,7 +477,7 @@ int launch_inverse(fftconv_plan_t p, int pass, float *dst, void *ws, hipStream_t
     const bool use_tiles = tiled(p) && pass != FFTCONV_ACCGRAD;
     const FftEntry *e = find_fft(p->N, use_tiles ? p->N : (a.crop_y > a.crop_x ? a.crop_y : a.crop_x));
     if (!e || (use_tiles && !e->inv_tiled)) return FFTCONV_EUNSUPPORTED;
-    InvKernel kernel = use_tiles ? e->inv_tiled : (accumulate ? e->inv_acc : e->inv);
+    InvKernel kernel = use_tiles ? (a.add ? e->inv_tiled_add : e->inv_tiled) : (accumulate ? e->inv_acc : e->inv);
     if (fused) {
         kernel = fused_inverse_kernel(e->N, e->T, e->NX, d.f, use_tiles);
         if (!kernel) return FFTCONV_EUNSUPPORTED;

@@ -145,7 +145,7 @@ def test_tiled_forward_windows(replay, N, H, k):
         M = S * tx * tx * C
         spec = np.full((B, M, 2), np.nan, np.float32)
         rc = replay.replay_fft2d_r2c_tiled(N, img.ctypes.data_as(FP), spec.ctypes.data_as(FP), M, ext, ext, size, size, C,
-                                           tx, tx * tx, L, L, org, org)
+                                           tx, tx * tx, L, L, org, org, 0)
         assert rc == 0
         got = spec[..., 0].astype(np.float64) + 1j * spec[..., 1]
         ref = reference_spectrum(tile_windows(img, N, tx, tx * tx, L, org, ext), N)
@@ -169,7 +169,7 @@ def test_tiled_inverse_scatters_each_tile_once(replay, N, H, k, c0):
     buf = np.concatenate([guard, dst.ravel(), guard])
     view = buf[64:64 + dst.size]
     rc = replay.replay_ifft2d_c2r_tiled(N, sp.ctypes.data_as(FP), view.ctypes.data_as(FP), M, L, L, c0, c0, H, H, C,
-                                        tx, tx * tx, L, L, 0, -1)
+                                        tx, tx * tx, L, L, 0, -1, 0)
     assert rc == 0
     assert np.all(np.isnan(buf[:64])) and np.all(np.isnan(buf[-64:]))
     got = view.reshape(S, C, H, H)
@@ -219,7 +219,7 @@ def test_tiled_rectangular_windows_and_scatter(replay):
         M = S * ty * tx * C
         spec = np.full((B, M, 2), np.nan, np.float32)
         rc = replay.replay_fft2d_r2c_tiled(N, img.ctypes.data_as(FP), spec.ctypes.data_as(FP), M, ext[0], ext[1], h, w, C,
-                                           tx, ty * tx, Ly, Lx, org[0], org[1])
+                                           tx, ty * tx, Ly, Lx, org[0], org[1], 0)
         assert rc == 0
         got = spec[..., 0].astype(np.float64) + 1j * spec[..., 1]
         ref = reference_spectrum(tile_windows(img, N, tx, ty * tx, (Ly, Lx), org, ext), N)
@@ -232,7 +232,7 @@ def test_tiled_rectangular_windows_and_scatter(replay):
     sp = np.ascontiguousarray(np.stack([spec.real, spec.imag], -1).astype(np.float32))
     dst = np.full((S, C, H, W), np.nan, np.float32)
     rc = replay.replay_ifft2d_c2r_tiled(N, sp.ctypes.data_as(FP), dst.ctypes.data_as(FP), M, Ly, Lx, kh - 1, kw - 1, H, W, C,
-                                        tx, ty * tx, Ly, Lx, 0, -1)
+                                        tx, ty * tx, Ly, Lx, 0, -1, 0)
     assert rc == 0 and not np.isnan(dst).any()
     for s in range(S):
         for t in range(ty * tx):
@@ -243,11 +243,30 @@ def test_tiled_rectangular_windows_and_scatter(replay):
                 assert np.abs(dst[s, c, oy:oy + h, ox:ox + w] - ref).max() < 3e-6
 
 
+def tiles_in_order(ty, tx, by_class):
+    """(row, column) of tile number t: row-major, or parity class by parity class (class 2 (row % 2) + column % 2,
+    row-major inside a class)."""
+    tiles = [(y, x) for y in range(ty) for x in range(tx)]
+    return sorted(tiles, key=lambda p: (2 * (p[0] % 2) + p[1] % 2, p)) if by_class else tiles
+
+
+@pytest.mark.parametrize("ty,tx", [(1, 1), (1, 4), (3, 1), (2, 2), (3, 5), (4, 3), (5, 5)])
+def test_tile_numbering_by_parity_class(replay, ty, tx):
+    for by_class in (0, 1):
+        want = tiles_in_order(ty, tx, by_class)
+        for t in range(ty * tx):
+            y, x = ctypes.c_int(-1), ctypes.c_int(-1)
+            replay.replay_tile_row_col(t, tx, ty * tx, by_class, ctypes.byref(y), ctypes.byref(x))
+            assert (y.value, x.value) == want[t], (t, by_class)
+
+
+@pytest.mark.parametrize("by_class", [0, 1])
 @pytest.mark.parametrize("N,Hy,Hx,kh,kw", [(16, 37, 30, 5, 3), (28, 70, 90, 6, 9), (48, 224, 100, 11, 11), (64, 65, 130, 3, 20)])
-def test_tiled_inverse_overlap_add(replay, N, Hy, Hx, kh, kw):
+def test_tiled_inverse_overlap_add(replay, N, Hy, Hx, kh, kw, by_class):
     """Overlap-add: the whole N x N output of every block's transform is added at the block's origin
     (blocks (N-kh+1) x (N-kw+1) apart, so neighbours overlap by kh-1 / kw-1), one parity class of
-    tiles per call; after the four calls every pixel holds the sum of the windows that cover it."""
+    tiles per call; after the four calls every pixel holds the sum of the windows that cover it.
+    With either numbering of the tiles."""
     rng = np.random.default_rng(11 * N + Hy)
     Ly, Lx = N - kh + 1, N - kw + 1
     S, C = 2, 3
@@ -259,12 +278,13 @@ def test_tiled_inverse_overlap_add(replay, N, Hy, Hx, kh, kw):
     dst = np.zeros((S, C, Hy, Hx), np.float32)
     for parity in range(4):
         rc = replay.replay_ifft2d_c2r_tiled(N, sp.ctypes.data_as(FP), dst.ctypes.data_as(FP), M, N, N, 0, 0, Hy, Hx, C,
-                                            tx, ty * tx, Ly, Lx, 1, parity)
+                                            tx, ty * tx, Ly, Lx, 1, parity, by_class)
         assert rc == 0
     ref = np.zeros((S, C, Hy, Hx))
+    order = tiles_in_order(ty, tx, by_class)
     for s in range(S):
         for t in range(ty * tx):
-            oy, ox = (t // tx) * Ly, (t % tx) * Lx
+            oy, ox = order[t][0] * Ly, order[t][1] * Lx
             h, w = min(N, Hy - oy), min(N, Hx - ox)
             for c in range(C):
                 ref[s, c, oy:oy + h, ox:ox + w] += patches[(s * ty * tx + t) * C + c, :h, :w]
@@ -320,3 +340,24 @@ def test_fused_product_inverse_is_the_valid_correlation(replay, N, k):
     assert replay.replay_ifft2d_c2r_crop_fused3(N, xs.ctypes.data_as(FP), ws.ctypes.data_as(FP), dst.ctypes.data_as(FP),
                                                M, fo, Sn * f, fo * f, no, no) == 0
     assert np.abs(dst.reshape(ref.shape) - ref).max() <= 2e-5 * np.abs(ref).max(), N
+
+
+def test_tiled_forward_with_tiles_numbered_by_class(replay):
+    """The forward transform of windows numbered class by class is the row-major one, reordered."""
+    rng = np.random.default_rng(77)
+    N, k, S, C, H, W = 16, 4, 2, 3, 50, 37
+    L = N - k + 1
+    ty, tx = -(-(H - k + 1) // L), -(-(W - k + 1) // L)
+    M = S * ty * tx * C
+    B = N * N // 2 + 2
+    img = rng.uniform(-1, 1, (S, C, H, W)).astype(np.float32)
+    out = []
+    for by_class in (0, 1):
+        spec = np.full((B, M, 2), np.nan, np.float32)
+        assert replay.replay_fft2d_r2c_tiled(N, img.ctypes.data_as(FP), spec.ctypes.data_as(FP), M, N, N, H, W, C,
+                                             tx, ty * tx, L, L, 0, 0, by_class) == 0
+        out.append(spec.reshape(B, S, ty * tx, C, 2))
+    row_major = tiles_in_order(ty, tx, 0)
+    perm = [row_major.index(p) for p in tiles_in_order(ty, tx, 1)]
+    # (to rounding: two maps share a complex transform, and the reordering changes the pairs when C is odd)
+    assert not np.isnan(out[1]).any() and np.abs(out[1] - out[0][:, :, perm]).max() <= 3e-6 * np.abs(out[0]).max()
