@@ -593,9 +593,12 @@ int fftconv_plan2d(fftconv_plan_t *out, const fftconv_desc2d *d)
     const int noh = d->nh - d->kh + 1, now = d->nw - d->kw + 1;
     int N = fft_size_for(d->nh > d->nw ? d->nh : d->nw), Ly = 0, Lx = 0, nty = 1, ntx = 1, nty2 = 1, ntx2 = 1;
     // Overlap-add for bprop of a tiled layer when a second transform of dL/dy (f' maps per tile) costs more
-    // than clearing dx and reading and writing its larger windows (f maps per tile).  Measured at S = 128: a
-    // gain of 21 % of the step for f = 3, f' = 96, losses of 2 to 12 % for f / f' = 96 / 256 and 64 / 64.
-    const bool few_input_maps = (long)d->f * 4 <= d->fo && !std::getenv("FFTCONV_NO_OVERLAP_ADD");
+    // than clearing dx and reading and writing its larger windows (f maps per tile).  Measured: gains of
+    // 21 % of the step for S = 128, f = 3, f' = 96, of 2 and 7 % for f = 96, f' = 256 (n = 96, 128), of 7 %
+    // for f = f' = 64.
+    const char *ratio_env = std::getenv("FFTCONV_OVERLAP_ADD_RATIO");   // for measurements: overlap-add if f * ratio <= f'
+    const long ratio = ratio_env ? std::atol(ratio_env) : 1;
+    const bool few_input_maps = (long)d->f * ratio <= d->fo && !std::getenv("FFTCONV_NO_OVERLAP_ADD");
     bool overlap_add = false;
     if (N < 0) {
         // Larger than the largest transform: cut into tiles of (N - kh + 1) x (N - kw + 1) outputs

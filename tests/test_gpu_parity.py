@@ -198,8 +198,9 @@ TILED_LAYERS = [
     wl.Layer("n80_k1", 2, 2, 2, 80, 1, 0.1, 97),          # k = 1: no overlap at all
     wl.Layer("n77_k6_ragged", 3, 5, 7, 77, 6, 0.1, 98),   # odd map counts: ragged transform groups
     wl.Layer("n72_k5", 2, 2, 3, 72, 5, 0.1, 101),         # tiles of a 5 * 2^m transform size
-    # (f * 4 <= f' and blocks at least k - 1 wide: bprop adds the overlapping windows of the blocks of dL/dy into
+    # (f <= f' and blocks at least k - 1 wide: bprop adds the overlapping windows of the blocks of dL/dy into
     #  dx, overlap-add; otherwise it transforms windows of dL/dy of its own, overlap-save)
+    wl.Layer("os_n100_k5", 2, 9, 4, 100, 5, 0.1, 123),          # more input than output maps: overlap-save
     wl.Layer("oa_n100_k5", 2, 2, 16, 100, 5, 0.1, 119),
     wl.Layer("oa_n224_k11_f3", 1, 3, 24, 224, 11, 0.05, 120),   # first-layer-like: 5 x 5 blocks, all four parity classes
     wl.Layer("oa_n70_k20", 1, 1, 8, 70, 20, 0.05, 121),         # windows overlap by more than half a block
@@ -209,7 +210,7 @@ TILED_LAYERS = [
 
 @pytest.mark.parametrize("layer", TILED_LAYERS, ids=lambda l: l.name)
 def test_full_parity_tiled_layers(fc, layer):
-    """n > 64: the maps are cut into overlapping tiles (overlap-save; for bprop with f * 4 <= f' overlap-add);
+    """n > 64: the maps are cut into overlapping tiles (overlap-save; for bprop with f <= f' overlap-add);
     all three passes against the oracle."""
     print(f"\ncase {layer}", flush=True)
     x, w, g = wl.make_inputs(layer)
@@ -230,7 +231,7 @@ def test_full_parity_tiled_layers(fc, layer):
     y = plan.fprop(xd, wd, outs[0][1])
     torch.cuda.synchronize()
     g2 = fc.SPEC_G2 if plan.slot_maps(fc.SPEC_G2) > 0 else 0     # no second transform of dL/dy with overlap-add
-    assert (g2 == 0) == (layer.f * 4 <= layer.fo and L >= layer.k - 1)
+    assert (g2 == 0) == (layer.f <= layer.fo and L >= layer.k - 1)
     assert plan.valid_slots() == fc.SPEC_X | fc.SPEC_W | fc.SPEC_G | g2
     for buf, _ in outs:
         assert torch.isnan(buf[:G]).all() and torch.isnan(buf[-G:]).all(), "stray write outside an output tensor"
