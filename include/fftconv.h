@@ -132,7 +132,7 @@ int fftconv_num_bins(fftconv_plan_t p);
  * sums over samples and tiles; bprop transforms, for each block of dx, the N x N window of
  * dL/dy that starts k - 1 rows and columns before it and keeps rows / columns [k-1, N) of
  * the inverse transform (the part of a circular result that no wrap-around touches).
- * When f <= fo (and L >= k - 1) bprop instead multiplies the blocks of dL/dy that accGrad
+ * When f <= fo (under FFTCONV_RECOMPUTE: f * 4 <= fo) and L >= k - 1, bprop instead multiplies the blocks of dL/dy that accGrad
  * transforms and adds the whole N x N inverse transform of each at the block's origin into dx
  * (overlap-add, in four launches over tiles whose windows do not overlap): dL/dy is transformed
  * once, there is no FFTCONV_SPEC_G2 slot, and tiles_dx equals tiles_y.  The

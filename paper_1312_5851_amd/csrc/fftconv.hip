@@ -597,7 +597,9 @@ int fftconv_plan2d(fftconv_plan_t *out, const fftconv_desc2d *d)
     // 21 % of the step for S = 128, f = 3, f' = 96, of 2 and 7 % for f = 96, f' = 256 (n = 96, 128), of 7 %
     // for f = f' = 64.
     const char *ratio_env = std::getenv("FFTCONV_OVERLAP_ADD_RATIO");   // for measurements: overlap-add if f * ratio <= f'
-    const long ratio = ratio_env ? std::atol(ratio_env) : 1;
+    // (without the spectral cache there is no second transform to save, only fewer blocks than windows to
+    //  transform: S = 128, f = 96, f' = 256, n = 96 then loses 8 % of the step, so the bar is higher)
+    const long ratio = ratio_env ? std::atol(ratio_env) : ((d->flags & FFTCONV_RECOMPUTE) ? 4 : 1);
     const bool few_input_maps = (long)d->f * ratio <= d->fo && !std::getenv("FFTCONV_NO_OVERLAP_ADD");
     bool overlap_add = false;
     if (N < 0) {

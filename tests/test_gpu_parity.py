@@ -247,7 +247,14 @@ def test_full_parity_tiled_layers(fc, layer):
     y2 = lean.fprop(xd, wd)
     dx3 = lean.bprop(gd, wd)
     torch.cuda.synchronize()
-    assert torch.equal(y2, y) and torch.equal(dx2, dx) and torch.equal(dw2, dw) and torch.equal(dx3, dx)
+    assert torch.equal(dx3, dx2)
+    same_scheme = lean.tiling == plan.tiling and fc.SPEC_G2 * (lean.slot_maps(fc.SPEC_G2) > 0) == g2
+    if same_scheme:     # same tiles, same kernels: the same bits
+        assert torch.equal(y2, y) and torch.equal(dx2, dx) and torch.equal(dw2, dw)
+    else:               # without the cache, overlap-add has a higher bar: other tiles or another scheme for bprop
+        check(y2.cpu().numpy(), direct.fprop(x, w), f"{layer.name} fprop (no cache)")
+        check(dx2.cpu().numpy(), direct.bprop(g, w, layer.n), f"{layer.name} bprop (no cache)")
+        check(dw2.cpu().numpy(), direct.accgrad(g, x, layer.k), f"{layer.name} accgrad (no cache)")
     assert lean.valid_slots() == 0
 
 
