@@ -114,34 +114,90 @@ def sampled_check(fc, layer, counts):
     check(dw.reshape(fo * f, k, k)[u], direct.accgrad(g, x, k, u), f"{layer.name} accgrad sample")
 
 
-@pytest.mark.parametrize("name", ["sweep_n16_k13", "sweep_n32_k11", "sweep_n64_k3", "sweep_n64_k13"])
-def test_sampled_parity_sweep_corners(fc, name):
-    """Corners of the n x k sweep (S=128, f=f'=256) at full size; the oracle evaluates a seeded
-    sample of whole output maps / kernels, sized so that each pass compares >= 1e4 elements."""
-    layer = wl.by_name(name)
+def stratified_units(rows, cols, count, seed, block=32):
+    """``count`` (at least) units r * cols + c of a rows x cols grid of output maps, chosen so that
+    every block x block cell of the grid holds one of them, plus the first and the last unit.
+
+    The grid's axes are the two free indices of the pass's per-bin matrix product (fprop: sample x
+    output map, bprop: sample x input map, accGrad: output map x input map).  With block = 32, the
+    side of one matrix-core tile, every workgroup tile and every wave tile of the contraction
+    contributes a compared map whatever tile shape the plan picked (64x64, 128x32, 64x96, 32x32);
+    the first and last units lie in the first and last workgroup of the inverse transform, and the
+    rows 0 and rows-1 / columns 0 and cols-1 they and the corner cells touch are fed by the first
+    and last workgroups of both forward transforms."""
+    rng = np.random.Generator(np.random.Philox(key=seed ^ 0x57A7))
+    picked = {0, rows * cols - 1}
+    for r0 in range(0, rows, block):
+        for c0 in range(0, cols, block):
+            r = r0 + int(rng.integers(0, min(block, rows - r0)))
+            c = c0 + int(rng.integers(0, min(block, cols - c0)))
+            picked.add(r * cols + c)
+    extra = min(count, rows * cols) - len(picked)
+    if extra > 0:
+        rest = np.setdiff1d(np.arange(rows * cols, dtype=np.int64), np.fromiter(picked, dtype=np.int64))
+        picked.update(int(v) for v in rng.choice(rest, size=extra, replace=False))
+    return np.sort(np.fromiter(picked, dtype=np.int64))
+
+
+def adjoint_check(x, w, g, y, dx, dw, what):
+    """<fprop(x,w), g> = <x, bprop(g,w)> = <w, accGrad(g,x)> on the whole device tensors (fp64 sums):
+    a property of Eqs. 1-3 that holds at any size and touches every output element."""
+    dot = lambda a, b: float((a.double().ravel() * b.double().ravel()).sum().item())
+    a, b, c = dot(y, g), dot(x, dx), dot(w, dw)
+    scale = float(torch.linalg.vector_norm(y.double()).item() * torch.linalg.vector_norm(g.double()).item())
+    print(f"{what} adjoint: {a:.9e} {b:.9e} {c:.9e} (|y||g| = {scale:.3e})", flush=True)
+    assert np.isfinite(a) and np.isfinite(b) and np.isfinite(c)
+    assert abs(a - b) <= 1e-5 * scale and abs(a - c) <= 1e-5 * scale and abs(b - c) <= 1e-5 * scale
+
+
+MIN_COMPARED = 100_000   # elements per output tensor that the oracle evaluates at a full-size sweep point
+
+
+def stratified_check(fc, layer):
+    """A layer at full size, in the launch configuration bench.py times.  Per pass the oracle evaluates
+    whole output maps / kernels holding at least 1e5 elements, stratified over the tiles of the
+    contraction and the ends of the transform launches (stratified_units); the adjoint identity then
+    checks the whole tensors."""
     print(f"\ncase {layer}", flush=True)
-    per_unit = (layer.no ** 2, layer.n ** 2, layer.k ** 2)
-    counts = tuple(max(8, min(96, -(-10000 // e))) for e in per_unit)
-    sampled_check(fc, layer, counts)
+    S, f, fo, n, k, no = layer.S, layer.f, layer.fo, layer.n, layer.k, layer.no
+    x, w, g = wl.make_inputs(layer)
+    plan = fc.Plan(S, f, fo, n, k)
+    xd, wd, gd = dev(x), dev(w), dev(g)
+    y, dx, dw = plan.fprop(xd, wd), plan.bprop(gd, wd), plan.accgrad(gd, xd)
+    torch.cuda.synchronize()
+    grids = ((S, fo, no * no), (S, f, n * n), (fo, f, k * k))
+    units = [stratified_units(r, c, -(-MIN_COMPARED // e), layer.seed + p) for p, (r, c, e) in enumerate(grids)]
+    for u, (r, c, e) in zip(units, grids):
+        assert len(u) * e >= min(MIN_COMPARED, r * c * e)
+        cells = {(int(v) // c // 32, int(v) % c // 32) for v in u}
+        assert len(cells) == -(-r // 32) * -(-c // 32), "a 32 x 32 cell of the product has no compared map"
+    pick = lambda t, u, e: t.reshape(-1, e)[torch.from_numpy(u).cuda()].cpu().numpy()
+    check(pick(y, units[0], no * no).reshape(-1, no, no), direct.fprop(x, w, units[0]),
+          f"{layer.name} fprop ({len(units[0])} maps, {len(units[0]) * no * no} elements)")
+    check(pick(dx, units[1], n * n).reshape(-1, n, n), direct.bprop(g, w, n, units[1]),
+          f"{layer.name} bprop ({len(units[1])} maps, {len(units[1]) * n * n} elements)")
+    check(pick(dw, units[2], k * k).reshape(-1, k, k), direct.accgrad(g, x, k, units[2]),
+          f"{layer.name} accgrad ({len(units[2])} kernels, {len(units[2]) * k * k} elements)")
+    adjoint_check(xd, wd, gd, y, dx, dw, layer.name)
 
 
-@pytest.mark.parametrize("idx", range(5))
-def test_sampled_parity_paper_table_columns(fc, idx):
+@pytest.mark.parametrize("layer", wl.sweep_layers(), ids=lambda l: l.name)
+def test_stratified_parity_every_sweep_point(fc, layer):
+    """Every point of the n x k sweep (S=128, f=f'=256; n in 16, 32, 64; k in 3..13)."""
+    stratified_check(fc, layer)
+
+
+@pytest.mark.parametrize("layer", wl.paper_table_layers(), ids=lambda l: l.name)
+def test_stratified_parity_paper_table_columns(fc, layer):
     """The five (k, n, f, f') columns of the paper's per-layer timing table at S=128."""
-    layer = wl.paper_table_layers()[idx]
-    print(f"\ncase {layer}", flush=True)
-    sampled_check(fc, layer, (64, 64, 96))
+    stratified_check(fc, layer)
 
 
 @pytest.mark.parametrize("name", ["fig3_n12", "fig3_n24", "fig3_n48", "fig3_k13", "fig3_S16", "fig3_S256"])
-def test_sampled_parity_figure_axes(fc, name):
+def test_stratified_parity_figure_axes(fc, name):
     """Points of the paper's speed figure axes (image size incl. sizes that are padded up,
-    kernel size, minibatch size; f=96, f'=256) at full size, oracle on a seeded sample."""
-    layer = wl.by_name(name)
-    print(f"\ncase {layer}", flush=True)
-    per_unit = (layer.no ** 2, layer.n ** 2, layer.k ** 2)
-    counts = tuple(max(8, min(96, -(-10000 // e))) for e in per_unit)
-    sampled_check(fc, layer, counts)
+    kernel size, minibatch size; f=96, f'=256)."""
+    stratified_check(fc, wl.by_name(name))
 
 
 @pytest.mark.parametrize("layer", [wl.TINY, SMALL_LAYERS[5], SMALL_LAYERS[7], wl.Layer("lean_wide", 9, 40, 70, 16, 3, 0.05, 81)],
