@@ -13,9 +13,9 @@
  * Sec. 4 pads to a power of two, the sizes 3 * 2^m, 5 * 2^m and 7 * 2^m cut its padding waste), the products are
  * accumulated per frequency bin over the summed index, and the result is
  * inverse-transformed and cropped.  The spectra of x, w and dL/dy are kept in a
- * caller-owned workspace and reused by later passes (the "keep the Fourier
- * representations in memory" option of Sec. 2.3) until the caller invalidates
- * them.
+ * caller-owned workspace and reused by later passes (the option Sec. 2.3 names
+ * for avoiding repeated transforms, at the price of memory) until the caller
+ * invalidates them.
  *
  * ALL DATA POINTERS ARE DEVICE POINTERS (fp32, contiguous, row-major):
  *   x [S][f ][n ][n ]     w [fo][f][k][k]
@@ -27,17 +27,19 @@
  * never synchronise with the host.  Return values report argument and launch
  * errors; on an argument error nothing is launched.
  *
- * A plan is not thread-safe; use one plan per host thread / stream.
+ * A plan is not thread-safe; use one plan per host thread / stream.  A plan belongs to the
+ * GPU that is current at its first launch; when a later call finds another GPU current, the
+ * plan starts over there with nothing cached.
  *
- * Environment switches, read at every call, for measurements and tests (results are the same
- * up to rounding order): FFTCONV_GEMM_TILE=0..7 forces a tile shape of the contraction kernel;
+ * Environment switches, all read once when a plan is made, for measurements and tests (results
+ * are the same up to rounding order): FFTCONV_GEMM_TILE=0..7 forces a tile shape of the contraction kernel;
  * FFTCONV_NO_XCD_REMAP, FFTCONV_NO_FULL_TILES select its plainer block numbering / its guarded
  * loads; FFTCONV_NO_SKINNY sends bprop and accGrad of layers with f <= 4 through the
  * matrix-core kernel instead of the streaming ones, FFTCONV_NO_SHARED_PASS keeps their two
  * products in separate launches instead of one pass over the spectrum of dL/dy; FFTCONV_NO_FUSED makes fprop of such
  * layers store and re-read the product spectrum instead of forming it inside the inverse
  * transform (which needs fo to be a multiple of the 16 to 64 maps a workgroup transforms),
- * FFTCONV_NO_FUSED_ORDER keeps that kernel's plain block order.  Read when a plan is made:
+ * FFTCONV_NO_FUSED_ORDER keeps that kernel's plain block order;
  * FFTCONV_NO_OVERLAP_ADD keeps the second transform of dL/dy for bprop of tiled layers,
  * FFTCONV_TILE_SIZE=N forces the transform size of the tiles, FFTCONV_OVERLAP_ADD_RATIO=r
  * moves the choice of overlap-add to f * r <= fo.
@@ -89,7 +91,8 @@ enum {
     FFTCONV_EUNSUPPORTED = 2, /* k > 64 with n > 64, more than 2^31 transforms in a slot, or unknown flag bits */
     FFTCONV_EWORKSPACE = 3,   /* workspace pointer null or not 256-byte aligned */
     FFTCONV_ELAUNCH = 4,      /* the HIP runtime refused a launch or an event call */
-    FFTCONV_ENOTREADY = 5     /* a stage-level call needs a spectrum that is not cached */
+    FFTCONV_ENOTREADY = 5,    /* a stage-level call needs a spectrum that is not cached */
+    FFTCONV_ENOMEM = 6        /* host memory for a plan could not be allocated */
 };
 
 /* Spectral cache slots (bit flags) and the scratch slot holding a pass's result spectrum.
@@ -157,8 +160,11 @@ size_t fftconv_workspace_bytes(fftconv_plan_t p);
  * m is the map index in the tensor's own order (s*f+i for x, j*f+i for w,
  * s*fo+j for g; tiled layers: (s*tiles+t)*f+i and (s*tiles+t)*fo+j for tile
  * t = ty*tiles_per_row+tx of sample s).  FFTCONV_SPEC_OUT holds the spectrum
- * of the last pass's result, laid out like that result.  Returns (size_t)-1 /
- * -1 for a bad slot (and for FFTCONV_SPEC_OUT under FFTCONV_RECOMPUTE). */
+ * of the last pass's result at the slot's start, laid out like that result; the
+ * one exception is the shared pass of layers with f <= 4 (see fftconv_bprop),
+ * which leaves dX's spectrum at the start and dW's behind it (256-byte aligned),
+ * whichever of the two passes ran.  Returns (size_t)-1 / -1 for a bad slot (and
+ * for FFTCONV_SPEC_OUT under FFTCONV_RECOMPUTE). */
 size_t fftconv_slot_offset(fftconv_plan_t p, int slot);
 long   fftconv_slot_maps(fftconv_plan_t p, int slot);
 
@@ -205,7 +211,9 @@ int fftconv_forward_transform(fftconv_plan_t p, int slot, const float *src, void
 int fftconv_contract(fftconv_plan_t p, int pass, void *ws, void *stream);
 
 /* Inverse transform + crop of the pass's result spectrum (where fftconv_contract
- * put it) into the pass's result tensor. */
+ * put it) into the pass's result tensor.  accumulate = 1 adds to dst instead of
+ * overwriting it; tiled layers (a map side above 64) support that for accGrad only
+ * and return EUNSUPPORTED for y and dx, launching nothing. */
 int fftconv_inverse_transform(fftconv_plan_t p, int pass, float *dst, void *ws, void *stream, int accumulate);
 
 /* ---- stage timing ------------------------------------------------------- */

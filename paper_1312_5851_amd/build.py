@@ -13,8 +13,21 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(_HERE), "include")
 
-# translation units of the library; they share no device code and compile side by side
-HIP_SOURCES = ["fftconv.hip", "fft_fused.hip"]
+# Translation units of the library as (source, extra defines, object name); they share no device
+# code and compile side by side.  The longest first, so that a pool of workers ends evenly.
+HIP_UNITS = [
+    ("fft_fused.hip", ["-DFFTCONV_FUSED_F=4"], "fft_fused_f4.o"),
+    ("fft_fused.hip", ["-DFFTCONV_FUSED_F=3"], "fft_fused_f3.o"),
+    ("fft_fused.hip", ["-DFFTCONV_FUSED_F=2"], "fft_fused_f2.o"),
+    ("fft_fused.hip", ["-DFFTCONV_FUSED_F=1"], "fft_fused_f1.o"),
+    ("fft_inv.hip", [], "fft_inv.o"),
+    ("fft_fwd.hip", [], "fft_fwd.o"),
+    ("contract.hip", [], "contract.o"),
+    ("fft_inv_tiled.hip", [], "fft_inv_tiled.o"),
+    ("skinny.hip", [], "skinny.o"),
+    ("fftconv.hip", [], "fftconv.o"),
+]
+MAX_JOBS = 8
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
@@ -43,22 +56,33 @@ def _sources_newer(target: str) -> bool:
     return False
 
 
-def build_library(force: bool = True, extra_flags=()) -> str:
-    """Compile the HIP sources under csrc/ for gfx950 and link them into libfftconv.so."""
+def build_library(force: bool = True, extra_flags=(), only_units=None) -> str:
+    """Compile the HIP sources under csrc/ for gfx950 and link them into libfftconv.so.
+
+    ``only_units``: names of sources to recompile; the other units reuse their objects if present."""
     out = lib_path()
     if force or _sources_newer(out):
         hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
         objdir = os.path.join(_HERE, "_build")
         os.makedirs(objdir, exist_ok=True)
-        jobs = []
-        for src in HIP_SOURCES:
-            obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
-            cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, "-I", INCLUDE, "-c", "-o", obj, os.path.join(CSRC, src)]
-            jobs.append((obj, cmd, subprocess.Popen(cmd)))
-        failed = [cmd for _, cmd, proc in jobs if proc.wait() != 0]
+        only = set(only_units) if only_units else None   # (after a change to one source: recompile just its units)
+        pending, running, objs, failed = list(HIP_UNITS), [], [], []
+        while pending or running:
+            while pending and len(running) < MAX_JOBS:
+                src, defines, objname = pending.pop(0)
+                obj = os.path.join(objdir, objname)
+                objs.append(obj)
+                if only is not None and src not in only and os.path.exists(obj):
+                    continue
+                cmd = [hipcc, *HIPCC_FLAGS, *defines, *extra_flags, "-I", INCLUDE, "-c", "-o", obj, os.path.join(CSRC, src)]
+                running.append((cmd, subprocess.Popen(cmd)))
+            if running:
+                cmd, proc = running.pop(0)
+                if proc.wait() != 0:
+                    failed.append(cmd)
         if failed:
             raise subprocess.CalledProcessError(1, failed[0])
-        link = [hipcc, "--offload-arch=gfx950", "-fPIC", "-shared", "-o", out, *[obj for obj, _, _ in jobs]]
+        link = [hipcc, "--offload-arch=gfx950", "-fPIC", "-shared", "-o", out, *objs]
         subprocess.run(link, check=True)
     return out
 
@@ -73,5 +97,10 @@ def build_host_replay(force: bool = False) -> str:
 
 
 if __name__ == "__main__":
-    print(build_library(force=True, extra_flags=sys.argv[1:]))
+    # python -m paper_1312_5851_amd.build [--only a.hip,b.hip] [extra hipcc flags]
+    argv = sys.argv[1:]
+    only = None
+    if argv and argv[0] == "--only":
+        only, argv = argv[1].split(","), argv[2:]
+    print(build_library(force=True, extra_flags=argv, only_units=only))
     print(build_host_replay(force=True))

@@ -39,22 +39,12 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include "contract_args.hpp"
 #include "fft_core.hpp"
 
 namespace fftconv {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
-
-struct GemmArgs {
-    const cf *A;     // left operand spectrum
-    const cf *B;     // right operand spectrum
-    cf *C;           // result spectrum, [bins][Md][Nd]
-    int Md, Nd, Kd;  // per-bin product sizes: C (Md x Nd) = op(A) (Md x Kd) * op(B) (Kd x Nd)
-    int bins;
-    int tiles_m, tiles_n;
-    int xcd_remap;   // 1: renumber workgroups so that each XCD gets contiguous work
-    int full_tiles_ok;   // 1: the operand and result matrices of a bin are below 2 GB, so 32-bit byte offsets suffice
-};
 
 constexpr int kXcds = 8;   // accelerator complex dies on MI355X; workgroups are dealt to them round-robin
 constexpr int kKT = 16;    // complex K elements per chunk (one 128-byte line of a K-contiguous row)

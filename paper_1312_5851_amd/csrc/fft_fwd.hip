@@ -1,0 +1,31 @@
+// Forward-transform kernels (fft_kernels.hpp), one instantiation per compiled geometry.
+#include <hip/hip_runtime.h>
+
+#include "kernel_tables.hpp"
+
+namespace fftconv {
+namespace {
+
+template <int N, int T, int NX>
+constexpr FwdKernel tiled_fwd_kernel()
+{
+    if constexpr (NX == N && N >= 16) return fft2d_r2c_kernel<TileGeom<N, T, NX, rounds_for(N)>, true>;
+    else return nullptr;
+}
+
+#define X(n_, t_, nx_)                                                                                              \
+    {n_, t_, nx_, TileGeom<n_, t_, nx_, rounds_for(n_)>::THREADS, TileGeom<n_, t_, nx_, rounds_for(n_)>::LDS_BYTES, \
+     fft2d_r2c_kernel<TileGeom<n_, t_, nx_, rounds_for(n_)>>, tiled_fwd_kernel<n_, t_, nx_>()},
+const FwdEntry kFwdTable[] = {FFTCONV_FOR_EACH_GEOM(X)};
+#undef X
+
+}  // namespace
+
+const FwdEntry *find_fwd_kernels(int N, int T, int NX)
+{
+    for (const FwdEntry &e : kFwdTable)
+        if (e.N == N && e.T == T && e.NX == NX) return &e;
+    return nullptr;
+}
+
+}  // namespace fftconv

@@ -1,7 +1,9 @@
 // C-ABI entry points of the fftconv library (declared in include/fftconv.h):
 // plan bookkeeping, the spectral cache, kernel selection and launches.
 // Host code only enqueues work on the caller's stream; all arithmetic of the
-// path runs in the kernels of fft_kernels.hpp and contract_kernels.hpp.
+// path runs in the kernels of fft_kernels.hpp, contract_kernels.hpp and
+// skinny_kernels.hpp, which are instantiated in translation units of their own
+// (kernel_tables.hpp).
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -11,10 +13,7 @@
 #include <vector>
 
 #include "../../include/fftconv.h"
-#include "contract_kernels.hpp"
-#include "fft_dispatch.hpp"
-#include "fft_fused.hpp"
-#include "skinny_kernels.hpp"
+#include "kernel_tables.hpp"
 
 using namespace fftconv;
 
@@ -31,106 +30,59 @@ struct ProfileRecord {
     hipEvent_t start, stop;
 };
 
-// ------------------------------------------------------------------ kernel tables
+// ------------------------------------------------------------------ kernel lookup
 
-typedef void (*FwdKernel)(FwdArgs);
-typedef void (*GemmKernel)(GemmArgs);
-
+// Everything a launch of one transform geometry needs: the forward, inverse and tiled kernels of
+// (N, T, NX) live in three tables (kernel_tables.hpp).
 struct FftEntry {
     int N, T, NX, threads, lds_bytes;
-    FwdKernel fwd;
-    InvKernel inv, inv_acc;
-    FwdKernel fwd_tiled;   // full-extent geometries (NX == N) of the sizes used for tiles only
-    InvKernel inv_tiled, inv_tiled_add;   // ... writing each window once / adding overlapping windows
+    FwdKernel fwd, fwd_tiled;
+    InvKernel inv, inv_acc, inv_tiled, inv_tiled_add;
 };
 
-// Tiles use the full-extent geometry of N >= 16 (smaller transforms would be mostly overlap).
-template <int N, int T, int NX>
-constexpr FwdKernel tiled_fwd_kernel()
-{
-    if constexpr (NX == N && N >= 16) return fft2d_r2c_kernel<TileGeom<N, T, NX, rounds_for(N)>, true>;
-    else return nullptr;
-}
-template <int N, int T, int NX>
-constexpr InvKernel tiled_inv_kernel()
-{
-    if constexpr (NX == N && N >= 16) return ifft2d_c2r_tiled_kernel<TileGeom<N, T, NX, rounds_for(N)>>;
-    else return nullptr;
-}
-
-template <int N, int T, int NX>
-constexpr InvKernel tiled_add_inv_kernel()
-{
-    if constexpr (NX == N && N >= 16) return ifft2d_c2r_tiled_kernel<TileGeom<N, T, NX, rounds_for(N)>, 0, true>;
-    else return nullptr;
-}
-
-#define X(n_, t_, nx_)                                                                          \
-    {n_, t_, nx_, TileGeom<n_, t_, nx_, rounds_for(n_)>::THREADS, TileGeom<n_, t_, nx_, rounds_for(n_)>::LDS_BYTES, \
-     fft2d_r2c_kernel<TileGeom<n_, t_, nx_, rounds_for(n_)>>,                                    \
-     ifft2d_c2r_crop_kernel<TileGeom<n_, t_, nx_, rounds_for(n_)>, false>,                       \
-     ifft2d_c2r_crop_kernel<TileGeom<n_, t_, nx_, rounds_for(n_)>, true>,                        \
-     tiled_fwd_kernel<n_, t_, nx_>(), tiled_inv_kernel<n_, t_, nx_>(), tiled_add_inv_kernel<n_, t_, nx_>()},
-const FftEntry kFftTable[] = {FFTCONV_FOR_EACH_GEOM(X)};
-#undef X
-
-const FftEntry *find_fft(int N, int ext)
+bool find_fft(int N, int ext, FftEntry &e)
 {
     const int T = maps_per_block(N), NX = extent_class(N, ext);
-    for (const FftEntry &e : kFftTable)
-        if (e.N == N && e.T == T && e.NX == NX) return &e;
-    return nullptr;
+    const FwdEntry *f = find_fwd_kernels(N, T, NX);
+    const InvEntry *i = find_inv_kernels(N, T, NX);
+    if (!f || !i) return false;
+    const InvTiledEntry *t = find_inv_tiled_kernels(N, T, NX);
+    e = FftEntry{N, T, NX, f->threads, f->lds_bytes, f->plain, f->tiled, i->plain, i->acc,
+                 t ? t->tiled : nullptr, t ? t->tiled_add : nullptr};
+    return true;
 }
 
-struct GemmEntry {
-    int MT, NT, wave_tiles, waves, occ, threads, lds_bytes;
-    GemmKernel pass[3];   // indexed by FFTCONV_FPROP / BPROP / ACCGRAD
+// Switches for measurements and tests, read from the environment once, when a plan is made.
+struct Switches {
+    int gemm_tile;   // forced tile shape of the contraction, or -1
+    bool no_xcd_remap, no_full_tiles, no_skinny, no_shared_pass, no_fused, no_fused_order;
 };
 
-// Layout / conjugation per pass (see contract_kernels.hpp):
-//   fprop   A = Xh [S][f]  K contiguous,  B = Wh [fo][f] K contiguous, conj B
-//   bprop   A = Gh [S][fo] K contiguous,  B = Wh [fo][f] K outer
-//   accGrad A = Gh [S][fo] K outer, conj A,  B = Xh [S][f] K outer
-#define GEMM_ENTRY(it, jt, wm, wn, occ) GEMM_ENTRY_SETS(it, jt, wm, wn, occ, 1)
-#define GEMM_ENTRY_SETS(it, jt, wm, wn, occ, sets)                                             \
-    {GemmTile<it, jt, wm, wn, sets>::MT, GemmTile<it, jt, wm, wn, sets>::NT, it * jt, wm * wn, occ, \
-     GemmTile<it, jt, wm, wn, sets>::THREADS, GemmTile<it, jt, wm, wn, sets>::LDS_BYTES,         \
-     {bin_cgemm_kernel<GemmTile<it, jt, wm, wn, sets>, true, true, false, true>,                 \
-      bin_cgemm_kernel<GemmTile<it, jt, wm, wn, sets>, true, false, false, false>,               \
-      bin_cgemm_kernel<GemmTile<it, jt, wm, wn, sets>, false, false, true, false>}}
-// (32x32 tiles per wave along M and N, waves along M and N, resident waves per SIMD)
-// One 32x32 tile per wave throughout.  Measured inside the full step on MI355X (operands
-// coming from HBM, not from a cache warmed by the previous launch), these shapes win over
-// larger wave tiles (64x32, 64x64 per wave), over 8-, 12- and 16-wave workgroups and over 1-
-// and 2-wave workgroups of the same wave tile at the K of these layers: four resident
-// workgroups per CU hide the per-tile prologue, epilogue and barrier waits best.
-const GemmEntry kGemmTable[] = {
-    GEMM_ENTRY(1, 1, 2, 2, 4),   // 0:  64 x 64
-    GEMM_ENTRY(1, 1, 4, 1, 4),   // 1: 128 x 32
-    GEMM_ENTRY(1, 1, 2, 3, 4),   // 2:  64 x 96
-    GEMM_ENTRY(1, 1, 1, 1, 4),   // 3:  32 x 32
-    // the same shapes with two register sets of operand chunks in flight, for HBM-bound products
-    GEMM_ENTRY_SETS(1, 1, 2, 2, 3, 2),   // 4:  64 x 64
-    GEMM_ENTRY_SETS(1, 1, 4, 1, 3, 2),   // 5: 128 x 32
-    GEMM_ENTRY_SETS(1, 1, 2, 3, 3, 2),   // 6:  64 x 96
-    GEMM_ENTRY_SETS(1, 1, 1, 1, 3, 2),   // 7:  32 x 32
-};
-#undef GEMM_ENTRY
-#undef GEMM_ENTRY_SETS
-constexpr int kNumShapes = 4;   // entries i and i + kNumShapes have the same shape
-constexpr int kNumGemm = sizeof(kGemmTable) / sizeof(kGemmTable[0]);
-
-// Picks the tile shape: least padded work first, then the order of the table.
-int choose_gemm_tile(int Md, int Nd, int /*Kd*/, int /*bins*/)
+Switches read_switches()
 {
+    Switches sw{};
+    sw.gemm_tile = -1;
     if (const char *env = std::getenv("FFTCONV_GEMM_TILE")) {
         const int v = std::atoi(env);
-        if (v >= 0 && v < kNumGemm) return v;
+        if (v >= 0 && v < gemm_kernel_count()) sw.gemm_tile = v;
     }
+    sw.no_xcd_remap = std::getenv("FFTCONV_NO_XCD_REMAP") != nullptr;
+    sw.no_full_tiles = std::getenv("FFTCONV_NO_FULL_TILES") != nullptr;
+    sw.no_skinny = std::getenv("FFTCONV_NO_SKINNY") != nullptr;
+    sw.no_shared_pass = std::getenv("FFTCONV_NO_SHARED_PASS") != nullptr;
+    sw.no_fused = std::getenv("FFTCONV_NO_FUSED") != nullptr;
+    sw.no_fused_order = std::getenv("FFTCONV_NO_FUSED_ORDER") != nullptr;
+    return sw;
+}
+
+// Picks the tile shape: least padded work first, then the order of the table.
+int choose_gemm_tile(int Md, int Nd, const Switches &sw)
+{
+    if (sw.gemm_tile >= 0) return sw.gemm_tile;
     int best = 0;
     long best_area = -1;
-    for (int i = 0; i < kNumShapes; ++i) {
-        const GemmEntry &e = kGemmTable[i];
+    for (int i = 0; i < gemm_shape_count(); ++i) {
+        const GemmEntry &e = gemm_kernel_table()[i];
         const long area = (long)((Md + e.MT - 1) / e.MT) * e.MT * ((Nd + e.NT - 1) / e.NT) * e.NT;
         if (best_area < 0 || area < best_area) { best_area = area; best = i; }
     }
@@ -163,6 +115,11 @@ struct fftconv_plan_s {
     unsigned ready;
     void *last_ws;
     int gemm_tile[3];
+    Switches sw;
+    // Set at the first launch: the device the plan runs on (cached spectra and raised LDS limits
+    // belong to it), and the kernels whose dynamic-LDS limit has been raised above 64 KB there.
+    int device;
+    std::vector<const void *> lds_raised;
     unsigned profiling;   // stage mask
     std::vector<ProfileRecord> records;
     std::vector<hipEvent_t> free_events;
@@ -185,11 +142,17 @@ struct StageTimer {
                 ev[i] = p->free_events.back();
                 p->free_events.pop_back();
             } else if (hipEventCreate(&ev[i]) != hipSuccess) {
+                if (i == 1) p->free_events.push_back(ev[0]);
                 status = FFTCONV_ELAUNCH;
                 return;
             }
         }
-        if (hipEventRecord(ev[0], stream) != hipSuccess) { status = FFTCONV_ELAUNCH; return; }
+        if (hipEventRecord(ev[0], stream) != hipSuccess) {
+            p->free_events.push_back(ev[0]);
+            p->free_events.push_back(ev[1]);
+            status = FFTCONV_ELAUNCH;
+            return;
+        }
         p->records.push_back({stage, ev[0], ev[1]});
         stop = ev[1];
         active = true;
@@ -208,19 +171,34 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(float *dst, size_t count
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x) dst[i] = 0.0f;
 }
 
+// A kernel needs its dynamic-LDS limit raised once before it may be launched with more than 64 KB;
+// the plan remembers for which kernels that has been done on its device (a kernel's LDS size is
+// fixed per plan).
 template <class K>
-int allow_lds(K kernel, int bytes)
+int allow_lds(fftconv_plan_t p, K kernel, int bytes)
 {
     if (bytes <= 64 * 1024) return FFTCONV_OK;
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                               bytes) == hipSuccess
-               ? FFTCONV_OK
-               : FFTCONV_ELAUNCH;
+    const void *fn = reinterpret_cast<const void *>(kernel);
+    for (const void *done : p->lds_raised)
+        if (done == fn) return FFTCONV_OK;
+    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) return FFTCONV_ELAUNCH;
+    p->lds_raised.push_back(fn);
+    return FFTCONV_OK;
 }
 
 int bind_workspace(fftconv_plan_t p, void *ws)
 {
     if (!ws || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0) return FFTCONV_EWORKSPACE;
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess) {   // no GPU: argument checks still answer, any launch will fail
+        (void)hipGetLastError();
+        device = -1;
+    }
+    if (device != p->device) {   // first launch, or the caller moved to another GPU: nothing carries over
+        p->device = device;
+        p->lds_raised.clear();
+        p->last_ws = nullptr;
+    }
     if (ws != p->last_ws) {
         p->valid = 0;
         p->ready = 0;
@@ -295,10 +273,11 @@ int launch_forward(fftconv_plan_t p, int slot, const float *src, void *ws, hipSt
         default: return FFTCONV_EINVAL;
     }
     const bool use_tiles = tiled(p) && slot != FFTCONV_SPEC_W;
-    const FftEntry *e = find_fft(p->N, use_tiles ? p->N : (ext_y > ext_x ? ext_y : ext_x));
-    if (!e || (use_tiles && !e->fwd_tiled)) return FFTCONV_EUNSUPPORTED;
+    FftEntry entry, *e = &entry;
+    if (!find_fft(p->N, use_tiles ? p->N : (ext_y > ext_x ? ext_y : ext_x), entry) || (use_tiles && !e->fwd_tiled))
+        return FFTCONV_EUNSUPPORTED;
     FwdKernel kernel = use_tiles ? e->fwd_tiled : e->fwd;
-    if (int rc = allow_lds(kernel, e->lds_bytes)) return rc;
+    if (int rc = allow_lds(p, kernel, e->lds_bytes)) return rc;
     FwdArgs a{src, slot_ptr(p, ws, slot), (int)M, ext_y, ext_x, t};
     // true convolution = correlation with the kernels rotated by 180 degrees: rotate them on the way in
     a.flip = (slot == FFTCONV_SPEC_W && (p->d.flags & FFTCONV_TRUE_CONV)) ? 1 : 0;
@@ -330,13 +309,6 @@ void pass_dims(fftconv_plan_t p, int pass, int &Md, int &Nd, int &Kd, int &slot_
     }
 }
 
-typedef void (*SkinnyKernel)(SkinnyArgs);
-const SkinnyKernel kSkinnyAccgrad[4] = {skinny_accgrad_kernel<1>, skinny_accgrad_kernel<2>, skinny_accgrad_kernel<3>,
-                                        skinny_accgrad_kernel<4>};
-
-const SkinnyKernel kSkinnyBprop[4] = {skinny_bprop_kernel<1>, skinny_bprop_kernel<2>, skinny_bprop_kernel<3>,
-                                      skinny_bprop_kernel<4>};
-
 // accGrad and bprop of a layer with at most four input maps: streaming kernels on the vector
 // ALU instead of matrix-core tiles that would be nine tenths padding.
 int launch_skinny(fftconv_plan_t p, int pass, void *ws, hipStream_t stream)
@@ -359,7 +331,7 @@ int launch_skinny(fftconv_plan_t p, int pass, void *ws, hipStream_t stream)
     }
     const long blocks = (long)a.bins * a.jblocks;
     if (blocks <= 0 || blocks > 0x7fffffffL) return FFTCONV_EUNSUPPORTED;
-    SkinnyKernel kernel = pass == FFTCONV_ACCGRAD ? kSkinnyAccgrad[p->d.f - 1] : kSkinnyBprop[p->d.f - 1];
+    SkinnyKernel kernel = pass == FFTCONV_ACCGRAD ? skinny_accgrad(p->d.f) : skinny_bprop(p->d.f);
     StageTimer timer(p, FFTCONV_STAGE_CGEMM_FPROP + pass, stream);
     hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kSkinnyThreads), 0, stream, a);
     if (int rc = check_launch()) return rc;
@@ -368,13 +340,9 @@ int launch_skinny(fftconv_plan_t p, int pass, void *ws, hipStream_t stream)
     return timer.finish();
 }
 
-typedef void (*SharedPassKernel)(SharedPassArgs);
-const SharedPassKernel kSharedPass[4] = {skinny_bprop_accgrad_kernel<1>, skinny_bprop_accgrad_kernel<2>,
-                                         skinny_bprop_accgrad_kernel<3>, skinny_bprop_accgrad_kernel<4>};
-
 bool shared_pass(fftconv_plan_t p)
 {
-    return p->shared_pass_ok && !std::getenv("FFTCONV_NO_SKINNY") && !std::getenv("FFTCONV_NO_SHARED_PASS");
+    return p->shared_pass_ok && !p->sw.no_skinny && !p->sw.no_shared_pass;
 }
 
 // Both result spectra of bprop and accGrad from one pass over the spectrum of dL/dy; timed as
@@ -400,13 +368,13 @@ int launch_shared_pass(fftconv_plan_t p, int pass, void *ws, hipStream_t stream)
     const int lds_bytes = (64 * 65 + 2 * 64 * F + kSkinnyWaves * ((rows + 63) / 64) * 64 * F) * 8;
     const long blocks = (long)a.bins * a.row_groups;
     if (blocks > 0x7fffffffL) return FFTCONV_EUNSUPPORTED;
-    SharedPassKernel kernel = kSharedPass[F - 1];
-    if (int rc = allow_lds(kernel, lds_bytes)) return rc;
+    SharedPassKernel kernel = skinny_bprop_accgrad(F);
+    if (int rc = allow_lds(p, kernel, lds_bytes)) return rc;
     StageTimer timer(p, FFTCONV_STAGE_CGEMM_FPROP + pass, stream);
     hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kSkinnyThreads), lds_bytes, stream, a);
     if (int rc = check_launch()) return rc;
     if (a.row_groups > 1) {
-        hipLaunchKernelGGL(sum_row_groups_kernel, dim3(512), dim3(256), 0, stream, a.DWpart, a.DW,
+        hipLaunchKernelGGL(sum_row_groups(), dim3(512), dim3(256), 0, stream, a.DWpart, a.DW,
                            (size_t)a.bins * a.N * F, a.row_groups);
         if (int rc = check_launch()) return rc;
     }
@@ -418,8 +386,8 @@ int launch_contract(fftconv_plan_t p, int pass, void *ws, hipStream_t stream)
     int Md, Nd, Kd, sa, sb;
     pass_dims(p, pass, Md, Nd, Kd, sa, sb);
     if ((p->valid & (unsigned)sa) == 0 || (p->valid & (unsigned)sb) == 0) return FFTCONV_ENOTREADY;
-    if (p->d.f <= 4 && pass != FFTCONV_FPROP && !std::getenv("FFTCONV_NO_SKINNY")) return launch_skinny(p, pass, ws, stream);
-    const GemmEntry &e = kGemmTable[p->gemm_tile[pass]];
+    if (p->d.f <= 4 && pass != FFTCONV_FPROP && !p->sw.no_skinny) return launch_skinny(p, pass, ws, stream);
+    const GemmEntry &e = gemm_kernel_table()[p->gemm_tile[pass]];
     GemmArgs g;
     g.A = slot_ptr(p, ws, sa);
     g.B = slot_ptr(p, ws, sb);
@@ -429,13 +397,13 @@ int launch_contract(fftconv_plan_t p, int pass, void *ws, hipStream_t stream)
     g.bins = p->B;
     g.tiles_m = (Md + e.MT - 1) / e.MT;
     g.tiles_n = (Nd + e.NT - 1) / e.NT;
-    g.xcd_remap = std::getenv("FFTCONV_NO_XCD_REMAP") ? 0 : 1;
+    g.xcd_remap = p->sw.no_xcd_remap ? 0 : 1;
     const long lim = 1L << 28;   // complex elements in 2 GB
     g.full_tiles_ok =
-        ((long)Md * Kd < lim && (long)Nd * Kd < lim && (long)Md * Nd < lim && !std::getenv("FFTCONV_NO_FULL_TILES")) ? 1 : 0;
+        ((long)Md * Kd < lim && (long)Nd * Kd < lim && (long)Md * Nd < lim && !p->sw.no_full_tiles) ? 1 : 0;
     const long blocks = (long)g.bins * g.tiles_m * g.tiles_n;
     if (blocks <= 0 || blocks > 0x7fffffffL) return FFTCONV_EUNSUPPORTED;
-    if (int rc = allow_lds(e.pass[pass], e.lds_bytes)) return rc;
+    if (int rc = allow_lds(p, e.pass[pass], e.lds_bytes)) return rc;
     StageTimer timer(p, FFTCONV_STAGE_CGEMM_FPROP + pass, stream);
     hipLaunchKernelGGL(e.pass[pass], dim3((unsigned)blocks), dim3(e.threads), e.lds_bytes, stream, g);
     if (int rc = check_launch()) return rc;
@@ -475,8 +443,12 @@ int launch_inverse(fftconv_plan_t p, int pass, float *dst, void *ws, hipStream_t
             break;
     }
     const bool use_tiles = tiled(p) && pass != FFTCONV_ACCGRAD;
-    const FftEntry *e = find_fft(p->N, use_tiles ? p->N : (a.crop_y > a.crop_x ? a.crop_y : a.crop_x));
-    if (!e || (use_tiles && !e->inv_tiled)) return FFTCONV_EUNSUPPORTED;
+    FftEntry entry, *e = &entry;
+    if (!find_fft(p->N, use_tiles ? p->N : (a.crop_y > a.crop_x ? a.crop_y : a.crop_x), entry) || (use_tiles && !e->inv_tiled))
+        return FFTCONV_EUNSUPPORTED;
+    // the tiled kernels either write every window once or add overlapping windows of a cleared dx:
+    // neither adds to what the caller's tensor held
+    if (use_tiles && accumulate) return FFTCONV_EUNSUPPORTED;
     InvKernel kernel = use_tiles ? (a.add ? e->inv_tiled_add : e->inv_tiled) : (accumulate ? e->inv_acc : e->inv);
     if (fused) {
         kernel = fused_inverse_kernel(e->N, e->T, e->NX, d.f, use_tiles);
@@ -484,9 +456,9 @@ int launch_inverse(fftconv_plan_t p, int pass, float *dst, void *ws, hipStream_t
         a.xs = slot_ptr(p, ws, FFTCONV_SPEC_X);
         a.wsp = slot_ptr(p, ws, FFTCONV_SPEC_W);
         a.fo = d.fo; a.Mx = (int)p->maps_x; a.Mw = (int)p->maps_w;
-        a.groups_per_sample = std::getenv("FFTCONV_NO_FUSED_ORDER") ? 0 : d.fo / e->T;
+        a.groups_per_sample = p->sw.no_fused_order ? 0 : d.fo / e->T;
     }
-    if (int rc = allow_lds(kernel, e->lds_bytes)) return rc;
+    if (int rc = allow_lds(p, kernel, e->lds_bytes)) return rc;
     a.spec = reinterpret_cast<const cf *>(reinterpret_cast<const unsigned char *>(slot_ptr(p, ws, result_slot(p, pass))) +
                                           spec_offset);
     a.dst = dst;
@@ -521,16 +493,38 @@ int launch_inverse(fftconv_plan_t p, int pass, float *dst, void *ws, hipStream_t
     return timer.finish();
 }
 
+}  // namespace
+
+namespace fftconv {
+InvKernel fused_inverse_kernel_f1(int N, int T, int NX, bool tiled);
+InvKernel fused_inverse_kernel_f2(int N, int T, int NX, bool tiled);
+InvKernel fused_inverse_kernel_f3(int N, int T, int NX, bool tiled);
+InvKernel fused_inverse_kernel_f4(int N, int T, int NX, bool tiled);
+
+InvKernel fused_inverse_kernel(int N, int T, int NX, int F, bool tiled)
+{
+    switch (F) {
+        case 1: return fused_inverse_kernel_f1(N, T, NX, tiled);
+        case 2: return fused_inverse_kernel_f2(N, T, NX, tiled);
+        case 3: return fused_inverse_kernel_f3(N, T, NX, tiled);
+        case 4: return fused_inverse_kernel_f4(N, T, NX, tiled);
+        default: return nullptr;
+    }
+}
+}  // namespace fftconv
+
+namespace {
+
 // fprop of a layer with at most four input maps: the products are formed inside the inverse
 // transform (nullptr: not applicable, or no such kernel for this geometry).
 InvKernel fused_fprop_kernel(fftconv_plan_t p, int pass, int accumulate)
 {
-    if (pass != FFTCONV_FPROP || accumulate || p->d.f > kMaxFusedMaps || std::getenv("FFTCONV_NO_FUSED")) return nullptr;
+    if (pass != FFTCONV_FPROP || accumulate || p->d.f > kMaxFusedMaps || p->sw.no_fused) return nullptr;
     const bool use_tiles = tiled(p);
     const int crop_y = use_tiles ? p->Ly : p->noh, crop_x = use_tiles ? p->Lx : p->now;
-    const FftEntry *e = find_fft(p->N, use_tiles ? p->N : (crop_y > crop_x ? crop_y : crop_x));
+    FftEntry entry, *e = &entry;
     // the maps of a workgroup must share a sample, whose part of the x spectrum must fit the LDS buffer
-    if (!e || p->d.fo % e->T != 0 || (long)p->B * p->d.f * 8 > e->lds_bytes) return nullptr;
+    if (!find_fft(p->N, use_tiles ? p->N : (crop_y > crop_x ? crop_y : crop_x), entry) || p->d.fo % e->T != 0 || (long)p->B * p->d.f * 8 > e->lds_bytes) return nullptr;
     return fused_inverse_kernel(e->N, e->T, e->NX, p->d.f, use_tiles);
 }
 
@@ -640,7 +634,7 @@ int fftconv_plan2d(fftconv_plan_t *out, const fftconv_desc2d *d)
     if (maps_x > lim || maps_w > lim || maps_g > lim || maps_g2 > lim || out_y > lim || out_dx > lim)
         return FFTCONV_EUNSUPPORTED;
     fftconv_plan_s *p = new (std::nothrow) fftconv_plan_s();
-    if (!p) return FFTCONV_EINVAL;
+    if (!p) return FFTCONV_ENOMEM;
     p->d = *d;
     p->noh = noh;
     p->now = now;
@@ -687,10 +681,13 @@ int fftconv_plan2d(fftconv_plan_t *out, const fftconv_desc2d *d)
     }
     p->last_ws = nullptr;
     p->profiling = 0;
+    p->device = -1;
+    p->lds_raised.reserve(32);   // more than the kernels one plan launches: no host allocation at launch time
+    p->sw = read_switches();
     for (int pass = 0; pass < 3; ++pass) {
         int Md, Nd, Kd, sa, sb;
         pass_dims(p, pass, Md, Nd, Kd, sa, sb);
-        p->gemm_tile[pass] = choose_gemm_tile(Md, Nd, Kd, p->B);
+        p->gemm_tile[pass] = choose_gemm_tile(Md, Nd, p->sw);
     }
     *out = p;
     return FFTCONV_OK;
@@ -822,6 +819,7 @@ const char *fftconv_strerror(int status)
         case FFTCONV_EWORKSPACE: return "workspace pointer null or not 256-byte aligned";
         case FFTCONV_ELAUNCH: return "HIP launch or event call failed";
         case FFTCONV_ENOTREADY: return "operand spectrum not cached for this workspace";
+        case FFTCONV_ENOMEM: return "out of host memory";
         default: return "unknown status";
     }
 }

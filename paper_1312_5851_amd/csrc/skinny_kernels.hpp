@@ -15,21 +15,10 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include "contract_args.hpp"
 #include "fft_core.hpp"
 
 namespace fftconv {
-
-struct SkinnyArgs {
-    const cf *X;   // accGrad: Xh [bins][M][F];  bprop: Wh [bins][N][F]
-    const cf *G;   // Gh  [bins][M][N]
-    cf *C;         // accGrad: dWh [bins][N][F];  bprop: dXh [bins][M][F]
-    int M, N;      // rows m (samples x tiles), output maps j
-    int bins;
-    int jblocks;   // accGrad: ceil(N / 64);  bprop: row blocks ceil(M / 64)
-};
-
-constexpr int kSkinnyThreads = 256;
-constexpr int kSkinnyWaves = kSkinnyThreads / 64;   // K slices a workgroup works on at a time
 
 // acc + a * b and acc + conj(a) * b as four fused multiply-adds each (a product formed first and
 // added afterwards would take six instructions, and these kernels have little else to issue)
@@ -190,19 +179,6 @@ __global__ __launch_bounds__(kSkinnyThreads) void skinny_bprop_kernel(SkinnyArgs
 // waves each sum a quarter of the tile's columns; for dWh, lane = column and the four waves each
 // sum a quarter of the tile's rows.  dWh of a column block is complete when its last tile is done;
 // the partial sums of dXh live in LDS, one slot per (quarter, row), until the end.
-struct SharedPassArgs {
-    const cf *G;   // Gh  [bins][M][N]
-    const cf *X;   // Xh  [bins][M][F]
-    const cf *W;   // Wh  [bins][N][F]
-    cf *DX;        // dXh [bins][M][F]
-    cf *DW;        // dWh [bins][N][F]
-    cf *DWpart;    // row_groups > 1: partial sums of dWh, [row_groups][bins][N][F]
-    int M, N, bins;
-    int row_groups;   // ceil(M / kSharedPassMaxRows) workgroups per bin, each on its own rows
-};
-
-constexpr int kSharedPassMaxRows = 256;   // rows per workgroup: more, and the partial sums of dXh would crowd the LDS
-
 template <int F>
 constexpr int shared_pass_lds_elems(int M)
 {
@@ -333,7 +309,7 @@ __global__ __launch_bounds__(kSkinnyThreads) void skinny_bprop_accgrad_kernel(Sh
 }
 
 // dWh = sum over row groups of the partial sums the kernel above leaves, in a fixed order.
-__global__ __launch_bounds__(256) void sum_row_groups_kernel(const cf *part, cf *out, size_t count, int groups)
+static __global__ __launch_bounds__(256) void sum_row_groups_kernel(const cf *part, cf *out, size_t count, int groups)
 {
     for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < count; e += (size_t)gridDim.x * blockDim.x) {
         cf sum = part[e];

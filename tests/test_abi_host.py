@@ -215,9 +215,18 @@ def test_invalidate_bookkeeping_and_null_pointer_errors(fc):
     assert lib.fftconv_contract(p._h, 7, one, None) == 1
     assert lib.fftconv_contract(p._h, 0, one, None) == 5                      # nothing cached: launches nothing
     assert lib.fftconv_inverse_transform(p._h, 0, None, one, None, 0) == 1
-    for s in range(6):
+    for s in range(7):
         assert fc.strerror(s) and fc.strerror(s) != "unknown status"
     assert fc.strerror(99) == "unknown status"
+
+
+def test_tiled_inverse_refuses_to_accumulate_into_y_and_dx(fc):
+    """accumulate on the tiled inverse of y / dx is refused (nothing launched), not silently ignored."""
+    p = fc.Plan(1, 2, 3, 100, 5)
+    assert p.tiling[0] != (0, 0)
+    one = ctypes.c_void_p(256)
+    for pass_id in (fc.FPROP, fc.BPROP):
+        assert fc._lib.fftconv_inverse_transform(p._h, pass_id, one, one, None, 1) == 2
 
 
 def test_paper_ram_closed_form_and_table(fc):
