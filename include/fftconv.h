@@ -92,7 +92,8 @@ enum {
     FFTCONV_EWORKSPACE = 3,   /* workspace pointer null or not 256-byte aligned */
     FFTCONV_ELAUNCH = 4,      /* the HIP runtime refused a launch or an event call */
     FFTCONV_ENOTREADY = 5,    /* a stage-level call needs a spectrum that is not cached */
-    FFTCONV_ENOMEM = 6        /* host memory for a plan could not be allocated */
+    FFTCONV_ENOMEM = 6,       /* host memory for a plan could not be allocated */
+    FFTCONV_ESCRATCH = 7      /* fftconv_pass_static: the layer needs more workspace than the static scratch holds */
 };
 
 /* Spectral cache slots (bit flags) and the scratch slot holding a pass's result spectrum.
@@ -198,6 +199,31 @@ int fftconv_bprop(fftconv_plan_t p, const float *g, const float *w, float *dx, v
  * overwrites dw, accumulate = 1 adds the gradient to it. */
 int fftconv_accgrad(fftconv_plan_t p, const float *g, const float *x, float *dw, void *ws, void *stream,
                     int accumulate);
+
+/* ---- one pass without any allocation ------------------------------------ */
+
+/* For callers that cannot allocate device memory or obtain a workspace: code running
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * same pass as fftconv_fprop (pass = FFTCONV_FPROP: a = x, b = w, out = y),
+ * fftconv_bprop (FFTCONV_BPROP: a = g, b = w, out = dx) or fftconv_accgrad
+ * (FFTCONV_ACCGRAD: a = g, b = x, out = dw; `accumulate` as there, 0 for the other two),
+ * run by the same kernels, with the spectral workspace taken from an array of
+ * FFTCONV_STATIC_SCRATCH_BYTES that is part of the library's device code: every GPU the
+ * library runs on holds one copy of it from the first call there until the process ends.
+ * The call allocates nothing, on the device or on the host, and records no events (stage
+ * timing is off for its launches).
+ *
+ * Returns FFTCONV_ESCRATCH, launching nothing, if fftconv_workspace_bytes(p) exceeds
+ * FFTCONV_STATIC_SCRATCH_BYTES (plan with FFTCONV_RECOMPUTE to need only three slots).
+ * All calls on one GPU, from any plan, share that GPU's array: nothing is cached across
+ * calls (both operands are transformed every time, fftconv_valid_slots is 0 afterwards,
+ * and the plan's cache bits for a caller-owned workspace are dropped too), the array is
+ * left holding the last call's spectra (every call writes all it reads, so nothing needs
+ * clearing), and calls that overlap in time on one GPU (two streams, two threads) race on
+ * it: serialise them. */
+#define FFTCONV_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+int fftconv_pass_static(fftconv_plan_t p, int pass, const float *a, const float *b, float *out, void *stream,
+                        int accumulate);
 
 /* ---- single stages (same kernels; for stage tests and per-stage timing) - */
 

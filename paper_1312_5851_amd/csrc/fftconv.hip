@@ -9,6 +9,7 @@
 #include <cstdint>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -16,6 +17,11 @@
 #include "kernel_tables.hpp"
 
 using namespace fftconv;
+
+// Workspace of fftconv_pass_static: part of the code object, one copy per GPU.  Host code never
+// uses this name as an address; it asks the runtime for the copy's address on the current device
+// (static_scratch_ptr below) and passes that to the kernels like any caller-owned workspace.
+static __device__ __align__(256) unsigned char scratch[FFTCONV_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -761,6 +767,44 @@ int fftconv_accgrad(fftconv_plan_t p, const float *g, const float *x, float *dw,
     return run_pass(p, FFTCONV_ACCGRAD, g, x, dw, ws, stream, accumulate);
 }
 
+// Address of the current device's copy of `scratch`, looked up once per device.
+static int static_scratch_ptr(void **out)
+{
+    constexpr int kMaxDevices = 64;
+    static void *ptrs[kMaxDevices];
+    static std::mutex lock;
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) return FFTCONV_ELAUNCH;
+    std::lock_guard<std::mutex> guard(lock);
+    if (!ptrs[device]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return FFTCONV_ELAUNCH;
+        ptrs[device] = ptr;
+    }
+    *out = ptrs[device];
+    return FFTCONV_OK;
+}
+
+int fftconv_pass_static(fftconv_plan_t p, int pass, const float *a, const float *b, float *out, void *stream,
+                        int accumulate)
+{
+    if (!p || pass < FFTCONV_FPROP || pass > FFTCONV_ACCGRAD || !a || !b || !out) return FFTCONV_EINVAL;
+    if (accumulate && pass != FFTCONV_ACCGRAD) return FFTCONV_EINVAL;
+    if (p->ws_bytes > FFTCONV_STATIC_SCRATCH_BYTES) return FFTCONV_ESCRATCH;
+    void *ws = nullptr;
+    if (int rc = static_scratch_ptr(&ws)) return rc;
+    // The array belongs to every plan and call on this GPU: nothing in it is this plan's cache.
+    p->last_ws = nullptr;
+    const unsigned profiling = p->profiling;
+    p->profiling = 0;   // event brackets would create events
+    const int rc = run_pass(p, pass, a, b, out, ws, stream, accumulate);
+    p->profiling = profiling;
+    p->valid = 0;
+    p->ready = 0;
+    p->last_ws = nullptr;
+    return rc;
+}
+
 int fftconv_forward_transform(fftconv_plan_t p, int slot, const float *src, void *ws, void *stream)
 {
     if (!p || !src) return FFTCONV_EINVAL;
@@ -820,6 +864,7 @@ const char *fftconv_strerror(int status)
         case FFTCONV_ELAUNCH: return "HIP launch or event call failed";
         case FFTCONV_ENOTREADY: return "operand spectrum not cached for this workspace";
         case FFTCONV_ENOMEM: return "out of host memory";
+        case FFTCONV_ESCRATCH: return "the layer's workspace exceeds the library's static scratch (FFTCONV_STATIC_SCRATCH_BYTES)";
         default: return "unknown status";
     }
 }

@@ -18,6 +18,7 @@ from . import build as _build
 FFTCONV_OK = 0
 SPEC_X, SPEC_W, SPEC_G, SPEC_OUT, SPEC_G2 = 1, 2, 4, 8, 16
 FPROP, BPROP, ACCGRAD = 0, 1, 2
+STATIC_SCRATCH_BYTES = 32 << 20   # workspace limit of fftconv_pass_static
 RECOMPUTE = 1   # plan flag: memory-efficient mode (no spectral cache, three-slot workspace)
 TRUE_CONV = 2   # plan flag: true convolution (kernel index reversed) instead of cross-correlation
 NUM_STAGES = 9
@@ -28,7 +29,7 @@ STAGE_NAMES = ("fft_x", "fft_w", "fft_g", "cgemm_fprop", "cgemm_bprop", "cgemm_a
 EXPORTS = (
     "fftconv_plan", "fftconv_plan2d", "fftconv_plan_destroy", "fftconv_fft_size", "fftconv_num_bins",
     "fftconv_workspace_bytes", "fftconv_slot_offset", "fftconv_slot_maps", "fftconv_invalidate",
-    "fftconv_valid_slots", "fftconv_fprop", "fftconv_bprop", "fftconv_accgrad",
+    "fftconv_valid_slots", "fftconv_fprop", "fftconv_bprop", "fftconv_accgrad", "fftconv_pass_static",
     "fftconv_forward_transform", "fftconv_contract", "fftconv_inverse_transform",
     "fftconv_profile_enable", "fftconv_profile_read", "fftconv_strerror",
     "fftconv_paper_ram_bytes", "fftconv_contraction_flops", "fftconv_tiling",
@@ -72,6 +73,7 @@ def _load() -> ctypes.CDLL:
         "fftconv_fprop": (ip, [vp, vp, vp, vp, vp, vp]),
         "fftconv_bprop": (ip, [vp, vp, vp, vp, vp, vp]),
         "fftconv_accgrad": (ip, [vp, vp, vp, vp, vp, vp, ip]),
+        "fftconv_pass_static": (ip, [vp, ip, vp, vp, vp, vp, ip]),
         "fftconv_forward_transform": (ip, [vp, ip, vp, vp, vp]),
         "fftconv_contract": (ip, [vp, ip, vp, vp]),
         "fftconv_inverse_transform": (ip, [vp, ip, vp, vp, vp, ip]),
@@ -226,6 +228,13 @@ class Plan:
         _check(_lib.fftconv_accgrad(self._h, _ptr(g, "g"), _ptr(x, "x"), _ptr(dw, "dw"), self._ws_ptr(), _stream(),
                                     1 if accumulate else 0), "fftconv_accgrad")
         return dw
+
+    def pass_static(self, pass_id: int, a, b, out, accumulate: bool = False):
+        """fftconv_pass_static: the pass on the library's own static scratch; allocates nothing
+        (``out`` must exist)."""
+        _check(_lib.fftconv_pass_static(self._h, pass_id, _ptr(a, "a"), _ptr(b, "b"), _ptr(out, "out"), _stream(),
+                                        1 if accumulate else 0), "fftconv_pass_static")
+        return out
 
     # -- single stages -----------------------------------------------------
     def forward_transform(self, slot: int, src):

@@ -215,9 +215,25 @@ def test_invalidate_bookkeeping_and_null_pointer_errors(fc):
     assert lib.fftconv_contract(p._h, 7, one, None) == 1
     assert lib.fftconv_contract(p._h, 0, one, None) == 5                      # nothing cached: launches nothing
     assert lib.fftconv_inverse_transform(p._h, 0, None, one, None, 0) == 1
-    for s in range(7):
+    for s in range(8):
         assert fc.strerror(s) and fc.strerror(s) != "unknown status"
     assert fc.strerror(99) == "unknown status"
+
+
+def test_static_scratch_pass_checks_its_arguments_before_anything_else(fc):
+    """fftconv_pass_static answers argument and size errors without touching a GPU."""
+    lib, one = fc._lib, ctypes.c_void_p(256)
+    small, big = fc.Plan(2, 2, 2, 16, 3), fc.Plan(128, 96, 256, 32, 5)
+    assert small.workspace_bytes <= fc.STATIC_SCRATCH_BYTES < big.workspace_bytes
+    assert lib.fftconv_pass_static(None, 0, one, one, one, None, 0) == 1
+    assert lib.fftconv_pass_static(small._h, 3, one, one, one, None, 0) == 1
+    assert lib.fftconv_pass_static(small._h, 0, None, one, one, None, 0) == 1
+    assert lib.fftconv_pass_static(small._h, 0, one, one, one, None, 1) == 1     # only accGrad accumulates
+    assert lib.fftconv_pass_static(big._h, 0, one, one, one, None, 0) == 7
+    assert "static scratch" in fc.strerror(7)
+    # the limit in the header is the one the binding quotes
+    text = open(os.path.join(ROOT, "include", "fftconv.h")).read()
+    assert "#define FFTCONV_STATIC_SCRATCH_BYTES ((size_t)32 << 20)" in text and fc.STATIC_SCRATCH_BYTES == 32 << 20
 
 
 def test_tiled_inverse_refuses_to_accumulate_into_y_and_dx(fc):
