@@ -109,9 +109,10 @@ struct InvArgs {
     float scale;          // 1 / N^2
     int c0_y, c0_x;       // tiled kernels: first stored row / column of the transform's output
     Tiling t;             // read by the tiled kernels only
-    int add;              // tiled kernels: 1 = add the window to what dst holds (overlap-add), 0 = overwrite
+    int add;              // tiled kernels: 1 = overlap-add of the windows (see inv_y_finish_tiled), 0 = overwrite
     // Overlap-add launches handle one parity class of tiles, 2 * (ty % 2) + tx % 2 == parity, whose windows
-    // do not overlap each other: the launch's transform ml = (s * cls_tiles + t') * C + c stands for tile
+    // do not overlap each other; they must run in the order parity = 0, 1, 2, 3, each complete before the
+    // next (later classes add to what earlier ones stored; what dst held before the first is never read): the launch's transform ml = (s * cls_tiles + t') * C + c stands for tile
     // (2 * (t' / cls_cx) + parity / 2, 2 * (t' % cls_cx) + parity % 2) of sample s.  parity = -1: every
     // tile, in the order of the spectrum.
     int parity, cls_cx, cls_tiles;
@@ -511,9 +512,9 @@ FC_HD void inv_y_finish(int tid, int blk, const InvArgs &a, cf (&z)[G::N])
 }
 
 // Tiled variant of step 2: rows and columns [c0, c0 + crop) of the transform's output go to
-// the tile's place in a larger image, clipped at the image border.  With ADD (and a.add) they are added to
-// what is there (overlap-add: the windows of neighbouring tiles overlap, so one launch handles
-// the tiles of one parity class, which do not).
+// the tile's place in a larger image, clipped at the image border.  With ADD (and a.add) the windows of
+// neighbouring tiles overlap and are summed (overlap-add): one launch handles the tiles of one parity
+// class, which do not overlap each other.
 template <class G, bool ADD = false>
 FC_HD void inv_y_finish_tiled(int tid, int blk, const InvArgs &a, cf (&z)[G::N])
 {
@@ -533,26 +534,33 @@ FC_HD void inv_y_finish_tiled(int tid, int blk, const InvArgs &a, cf (&z)[G::N])
         const int rows = a.crop_y < a.t.H - o.oy ? a.crop_y : a.t.H - o.oy;
         float *col = a.dst + ((size_t)o.image * a.t.H + o.oy) * a.t.W + o.ox + xs;
         if constexpr (ADD) {
-            // overlap-add (c0 = 0): the old values of a group of rows are all loaded before the first of them
-            // is needed, so that their latencies overlap instead of adding up row by row
+            // Overlap-add (c0 = 0, windows placed at multiples of the step).  A pixel lies in the windows of up
+            // to four tiles, one per parity class; the launches run in class order 0..3, and the tile of the
+            // lowest class among those covering a pixel stores its value plainly while the later ones add to
+            // what they find.  So dx needs no clearing, only the overlap strips are ever read, and every sum
+            // has a fixed order.  With a = ty % 2, b = tx % 2 and classes 2a + b, a tile is not the first
+            // writer of a pixel exactly if a horizontal neighbour covers it and b = 1, or a vertical one and a = 1.
+            const int ty = o.oy / a.t.step_y, tx = o.ox / a.t.step_x, tiles_y = a.t.tiles / a.t.tiles_x;
+            const int ovy = N - a.t.step_y, ovx = N - a.t.step_x;   // kh - 1, kw - 1: rows / columns shared with a neighbour
+            const bool add_x = (tx & 1) && ((xs < ovx) || (xs >= a.t.step_x && tx + 1 < a.t.tiles_x));
+            const bool odd_ty = (ty & 1) != 0, below = ty + 1 < tiles_y;
+            // the old values of a group of rows are all loaded before the first of them is needed, so that
+            // their latencies overlap instead of adding up row by row
             constexpr int GROUP = N < 16 ? N : 16;
-            static_for<0, N / GROUP>([&](auto gi) {
+            static_for<0, (N + GROUP - 1) / GROUP>([&](auto gi) {
                 constexpr int y0 = decltype(gi)::value * GROUP;
-                float old[GROUP];
-                static_for<0, GROUP>([&](auto yi) {
+                constexpr int CNT = N - y0 < GROUP ? N - y0 : GROUP;
+                float old[CNT];
+                static_for<0, CNT>([&](auto yi) {
                     constexpr int y = y0 + decltype(yi)::value;
-                    old[y - y0] = y < rows ? col[(size_t)y * a.t.W] : 0.0f;
+                    const bool adds = add_x || (odd_ty && (y < ovy || (y >= a.t.step_y && below)));
+                    old[y - y0] = (y < rows && adds) ? col[(size_t)y * a.t.W] : 0.0f;
                 });
-                static_for<0, GROUP>([&](auto yi) {
+                static_for<0, CNT>([&](auto yi) {
                     constexpr int y = y0 + decltype(yi)::value;
                     const cf v = z[brev<N>(y)];
                     if (y < rows) col[(size_t)y * a.t.W] = old[y - y0] + (which == 0 ? v.x : v.y) * a.scale;
                 });
-            });
-            static_for<(N / GROUP) * GROUP, N>([&](auto yi) {   // rows left over when N is not a multiple of the group
-                constexpr int y = decltype(yi)::value;
-                const cf v = z[brev<N>(y)];
-                if (y < rows) col[(size_t)y * a.t.W] += (which == 0 ? v.x : v.y) * a.scale;
             });
             return;
         }

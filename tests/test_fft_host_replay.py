@@ -261,12 +261,16 @@ def test_tile_numbering_by_parity_class(replay, ty, tx):
 
 
 @pytest.mark.parametrize("by_class", [0, 1])
-@pytest.mark.parametrize("N,Hy,Hx,kh,kw", [(16, 37, 30, 5, 3), (28, 70, 90, 6, 9), (48, 224, 100, 11, 11), (64, 65, 130, 3, 20)])
+@pytest.mark.parametrize("N,Hy,Hx,kh,kw", [(16, 37, 30, 5, 3), (28, 70, 90, 6, 9), (48, 224, 100, 11, 11), (64, 65, 130, 3, 20),
+                                          (16, 14, 60, 3, 3),      # one row of tiles
+                                          (16, 40, 44, 9, 9),      # blocks exactly k - 1 wide: windows two apart touch
+                                          (20, 100, 21, 1, 2)])    # kh = 1: no vertical overlap at all
 def test_tiled_inverse_overlap_add(replay, N, Hy, Hx, kh, kw, by_class):
     """Overlap-add: the whole N x N output of every block's transform is added at the block's origin
     (blocks (N-kh+1) x (N-kw+1) apart, so neighbours overlap by kh-1 / kw-1), one parity class of
-    tiles per call; after the four calls every pixel holds the sum of the windows that cover it.
-    With either numbering of the tiles."""
+    tiles per call, in class order; after the four calls every pixel holds the sum of the windows that
+    cover it, whatever the destination held before (the first class covering a pixel stores, the later
+    ones add: nothing is cleared beforehand).  With either numbering of the tiles."""
     rng = np.random.default_rng(11 * N + Hy)
     Ly, Lx = N - kh + 1, N - kw + 1
     S, C = 2, 3
@@ -275,7 +279,7 @@ def test_tiled_inverse_overlap_add(replay, N, Hy, Hx, kh, kw, by_class):
     patches = rng.uniform(-1, 1, (M, N, N))
     spec = reference_spectrum(patches, N)
     sp = np.ascontiguousarray(np.stack([spec.real, spec.imag], -1).astype(np.float32))
-    dst = np.zeros((S, C, Hy, Hx), np.float32)
+    dst = np.full((S, C, Hy, Hx), np.nan, np.float32)
     for parity in range(4):
         rc = replay.replay_ifft2d_c2r_tiled(N, sp.ctypes.data_as(FP), dst.ctypes.data_as(FP), M, N, N, 0, 0, Hy, Hx, C,
                                             tx, ty * tx, Ly, Lx, 1, parity, by_class)
