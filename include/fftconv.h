@@ -148,7 +148,8 @@ int fftconv_tiling(fftconv_plan_t p, int tile[2], int tiles_y[2], int tiles_dx[2
 
 /* Bytes of device workspace the passes need: the x, w and g spectra (8*B bytes
  * per map for S*f + fo*f + S*fo maps, the count of Sec. 2.3) plus one result
- * spectrum of 8*B*max(S*fo, S*f, fo*f) bytes; each slot 256-byte aligned.
+ * slot of 8*B*max(S*fo, S*f, fo*f) bytes (8*B*(S*f + fo*f + 1) if that is more and
+ * the layer takes the joint bprop + accGrad launch); each slot 256-byte aligned.
  * With FFTCONV_RECOMPUTE: the three slots only.  Tiled layers hold one transform per
  * tile (fftconv_slot_maps) and, unless bprop uses overlap-add, one more slot, FFTCONV_SPEC_G2. */
 size_t fftconv_workspace_bytes(fftconv_plan_t p);
@@ -162,7 +163,7 @@ size_t fftconv_workspace_bytes(fftconv_plan_t p);
  * s*fo+j for g; tiled layers: (s*tiles+t)*f+i and (s*tiles+t)*fo+j for tile
  * t = ty*tiles_per_row+tx of sample s).  FFTCONV_SPEC_OUT holds the spectrum
  * of the last pass's result at the slot's start, laid out like that result; the
- * one exception is the shared pass of layers with f <= 4 (see fftconv_bprop),
+ * one exception is the joint launch for bprop and accGrad (see fftconv_bprop),
  * which leaves dX's spectrum at the start and dW's behind it (256-byte aligned),
  * whichever of the two passes ran.  Returns (size_t)-1 / -1 for a bad slot (and
  * for FFTCONV_SPEC_OUT under FFTCONV_RECOMPUTE). */
@@ -185,13 +186,17 @@ int fftconv_fprop(fftconv_plan_t p, const float *x, const float *w, float *y, vo
 /* Eq. (2), summed over j: dx[s,i] = sum_j g[s,j] * w[j,i]^T (adjoint of fprop in x).
  * Uses the g and w slots; stores the full n x n window.  dx is overwritten.
  *
- * Layers with f <= 4 (spectra cached; tiled layers only if bprop uses overlap-add): if the slots of x, w and g are
- * all valid, the first of fftconv_bprop / fftconv_accgrad to be called forms the result
- * spectra of both in one pass over the spectrum of dL/dy and leaves the other's in
- * FFTCONV_SPEC_OUT; the other pass, called next with the same tensors, only
- * inverse-transforms it.  The waiting spectrum is used once, and is dropped when one of
- * its operand slots is invalidated or transformed again or another call writes
- * FFTCONV_SPEC_OUT; results are those of separate calls up to rounding order. */
+ * One launch for the products of bprop and accGrad.  Both read the spectrum of dL/dy.  If the spectra are
+ * cached, both passes use the same transforms of dL/dy (untiled layers, or tiled ones whose bprop uses
+ * overlap-add) and the slots of x, w and g are all valid, the first of fftconv_bprop / fftconv_accgrad to be
+ * called forms the result spectra of both and leaves the other's in FFTCONV_SPEC_OUT; the other pass, called
+ * next with the same tensors, only inverse-transforms it.  Layers with f <= 4 do this in one streaming pass
+ * over the spectrum of dL/dy; layers with more input maps run both matrix-core contractions in one launch,
+ * provided both result spectra together stay below 192 MiB (so that each still sits in the memory-side cache
+ * when its inverse transform reads it).  The waiting spectrum is used once, and is dropped when one of its
+ * operand slots is invalidated or transformed again or another call writes FFTCONV_SPEC_OUT; results are
+ * those of separate calls up to rounding order.
+ * FFTCONV_NO_SHARED_PASS in the environment keeps the two products in separate launches. */
 int fftconv_bprop(fftconv_plan_t p, const float *g, const float *w, float *dx, void *ws, void *stream);
 
 /* Eq. (3), summed over the minibatch: dw[j,i] = sum_s g[s,j] * x[s,i] (adjoint of

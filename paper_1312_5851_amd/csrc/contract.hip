@@ -18,7 +18,8 @@ namespace {
      GemmTile<it, jt, wm, wn, sets>::THREADS, GemmTile<it, jt, wm, wn, sets>::LDS_BYTES,         \
      {bin_cgemm_kernel<GemmTile<it, jt, wm, wn, sets>, true, true, false, true>,                 \
       bin_cgemm_kernel<GemmTile<it, jt, wm, wn, sets>, true, false, false, false>,               \
-      bin_cgemm_kernel<GemmTile<it, jt, wm, wn, sets>, false, false, true, false>}}
+      bin_cgemm_kernel<GemmTile<it, jt, wm, wn, sets>, false, false, true, false>},              \
+     bin_cgemm_bprop_accgrad_kernel<GemmTile<it, jt, wm, wn, sets>>}
 // (32x32 tiles per wave along M and N, waves along M and N, resident waves per SIMD)
 // One 32x32 tile per wave throughout.  Measured inside the full step on MI355X (operands
 // coming from HBM, not from a cache warmed by the previous launch), these shapes win over

@@ -16,6 +16,11 @@ struct GemmArgs {
     int full_tiles_ok;   // 1: the operand and result matrices of a bin are below 2 GB, so 32-bit byte offsets suffice
 };
 
+// bprop's and accGrad's products in one launch (bin_cgemm_bprop_accgrad_kernel): both with the same tile shape.
+struct GemmPairArgs {
+    GemmArgs bprop, accgrad;
+};
+
 struct SkinnyArgs {
     const cf *X;   // accGrad: Xh [bins][M][F];  bprop: Wh [bins][N][F]
     const cf *G;   // Gh  [bins][M][N]

@@ -282,29 +282,24 @@ __device__ __forceinline__ void contract_tile(cf *lds, int tid, int lane, int wm
         });
 }
 
-// Launch: grid = bins * tiles_m * tiles_n blocks of G::THREADS threads, G::LDS_BYTES dynamic LDS.
-template <class G, bool A_KIN, bool B_KIN, bool CONJ_A, bool CONJ_B>
-__global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void bin_cgemm_kernel(GemmArgs g)
+// Workgroups are dealt round-robin to the XCDs (each with its own L2).  Renumbering them makes
+// every XCD walk a contiguous range of (bin, tile) work: all tiles of a bin then share one L2.
+__device__ __forceinline__ int xcd_contiguous_work(int remap)
 {
-    constexpr int IT = G::IT, JT = G::JT;
-    extern __shared__ __align__(16) unsigned char lds_raw[];
-    cf *lds = reinterpret_cast<cf *>(lds_raw);
-
-    const int tid = (int)threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave % G::WM, wn = wave / G::WM;
-
-    // Workgroups are dealt round-robin to the XCDs (each with its own L2).  Renumber
-    // them so that every XCD walks a contiguous range of (bin, tile) work: all tiles of
-    // a bin then share one L2.
     const int total = (int)gridDim.x;
     const int xcd = (int)blockIdx.x % kXcds, slot = (int)blockIdx.x / kXcds;
     const int per = total / kXcds, rem = total % kXcds;
-    const int work = g.xcd_remap ? xcd * per + (xcd < rem ? xcd : rem) + slot : (int)blockIdx.x;
+    return remap ? xcd * per + (xcd < rem ? xcd : rem) + slot : (int)blockIdx.x;
+}
 
-    const int tiles = g.tiles_m * g.tiles_n;
-    const int bin = work / tiles;
-    const int t = work % tiles;
+// One workgroup's tile t of bin `bin`: C[bin] tile = op(A[bin]) * op(B[bin]).
+template <class G, bool A_KIN, bool B_KIN, bool CONJ_A, bool CONJ_B>
+__device__ __forceinline__ void cgemm_tile(const GemmArgs &g, int bin, int t, cf *lds)
+{
+    constexpr int IT = G::IT, JT = G::JT;
+    const int tid = (int)threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave % G::WM, wn = wave / G::WM;
     const int i0 = (t % g.tiles_m) * G::MT, j0 = (t / g.tiles_m) * G::NT;
 
     // leading dimensions follow from the layouts: K-contiguous operands are [rows][Kd],
@@ -380,6 +375,33 @@ __global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void bin_cgemm_kerne
                 }
             }
         }
+}
+
+// Launch: grid = bins * tiles_m * tiles_n blocks of G::THREADS threads, G::LDS_BYTES dynamic LDS.
+template <class G, bool A_KIN, bool B_KIN, bool CONJ_A, bool CONJ_B>
+__global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void bin_cgemm_kernel(GemmArgs g)
+{
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    const int work = xcd_contiguous_work(g.xcd_remap);
+    const int tiles = g.tiles_m * g.tiles_n;
+    cgemm_tile<G, A_KIN, B_KIN, CONJ_A, CONJ_B>(g, work / tiles, work % tiles, reinterpret_cast<cf *>(lds_raw));
+}
+
+// The contractions of bprop and accGrad in one launch (both read the spectrum of dL/dy, Eqs. 2 and 3):
+// the work of a bin is its bprop tiles followed by its accGrad tiles, so the workgroups that read
+// Gh[bin] for either product run next to each other on one XCD and the second read comes from its
+// L2; one launch also has one ramp and one tail instead of two, and the tiles of one product fill the
+// last, partly empty round of the other.  Launch: grid = bins * (tiles of bprop + tiles of accGrad).
+template <class G>
+__global__ __launch_bounds__(G::THREADS, G::WAVES_PER_SIMD) void bin_cgemm_bprop_accgrad_kernel(GemmPairArgs p)
+{
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    cf *lds = reinterpret_cast<cf *>(lds_raw);
+    const int work = xcd_contiguous_work(p.bprop.xcd_remap);
+    const int tiles_b = p.bprop.tiles_m * p.bprop.tiles_n, tiles_a = p.accgrad.tiles_m * p.accgrad.tiles_n;
+    const int bin = work / (tiles_b + tiles_a), t = work % (tiles_b + tiles_a);
+    if (t < tiles_b) cgemm_tile<G, true, false, false, false>(p.bprop, bin, t, lds);
+    else cgemm_tile<G, false, false, true, false>(p.accgrad, bin, t - tiles_b, lds);
 }
 
 }  // namespace fftconv

@@ -121,6 +121,7 @@ struct fftconv_plan_s {
     unsigned ready;
     void *last_ws;
     int gemm_tile[3];
+    int pair_tile;   // tile shape of the joint bprop + accGrad launch
     Switches sw;
     // Set at the first launch: the device the plan runs on (cached spectra and raised LDS limits
     // belong to it), and the kernels whose dynamic-LDS limit has been raised above 64 KB there.
@@ -343,15 +344,50 @@ int launch_skinny(fftconv_plan_t p, int pass, void *ws, hipStream_t stream)
 
 bool shared_pass(fftconv_plan_t p)
 {
-    return p->shared_pass_ok && !p->sw.no_skinny && !p->sw.no_shared_pass;
+    return p->shared_pass_ok && !p->sw.no_shared_pass && (p->d.f > 4 || !p->sw.no_skinny);
 }
 
 // Both result spectra of bprop and accGrad from one pass over the spectrum of dL/dy; timed as
 // the contraction of the pass that asked for it.
+void fill_gemm_args(fftconv_plan_t p, int pass, const GemmEntry &e, void *ws, cf *C, GemmArgs &g)
+{
+    int Md, Nd, Kd, sa, sb;
+    pass_dims(p, pass, Md, Nd, Kd, sa, sb);
+    g.A = slot_ptr(p, ws, sa);
+    g.B = slot_ptr(p, ws, sb);
+    g.C = C;
+    g.Md = Md; g.Nd = Nd; g.Kd = Kd;
+    g.bins = p->B;
+    g.tiles_m = (Md + e.MT - 1) / e.MT;
+    g.tiles_n = (Nd + e.NT - 1) / e.NT;
+    g.xcd_remap = p->sw.no_xcd_remap ? 0 : 1;
+    const long lim = 1L << 28;   // complex elements in 2 GB
+    g.full_tiles_ok = ((long)Md * Kd < lim && (long)Nd * Kd < lim && (long)Md * Nd < lim && !p->sw.no_full_tiles) ? 1 : 0;
+}
+
+// The same for layers with more than four input maps: the matrix-core contractions of both passes in
+// one launch (bin_cgemm_bprop_accgrad_kernel).
+int launch_pair_contract(fftconv_plan_t p, int pass, void *ws, hipStream_t stream)
+{
+    const GemmEntry &e = gemm_kernel_table()[p->pair_tile];
+    unsigned char *out = reinterpret_cast<unsigned char *>(slot_ptr(p, ws, FFTCONV_SPEC_OUT));
+    GemmPairArgs a;
+    fill_gemm_args(p, FFTCONV_BPROP, e, ws, reinterpret_cast<cf *>(out), a.bprop);
+    fill_gemm_args(p, FFTCONV_ACCGRAD, e, ws, reinterpret_cast<cf *>(out + p->off_shared_dw), a.accgrad);
+    const long blocks = (long)p->B * ((long)a.bprop.tiles_m * a.bprop.tiles_n + (long)a.accgrad.tiles_m * a.accgrad.tiles_n);
+    if (blocks <= 0 || blocks > 0x7fffffffL) return FFTCONV_EUNSUPPORTED;
+    if (int rc = allow_lds(p, e.bprop_accgrad, e.lds_bytes)) return rc;
+    StageTimer timer(p, FFTCONV_STAGE_CGEMM_FPROP + pass, stream);
+    hipLaunchKernelGGL(e.bprop_accgrad, dim3((unsigned)blocks), dim3(e.threads), e.lds_bytes, stream, a);
+    if (int rc = check_launch()) return rc;
+    return timer.finish();
+}
+
 int launch_shared_pass(fftconv_plan_t p, int pass, void *ws, hipStream_t stream)
 {
     const unsigned need = FFTCONV_SPEC_X | FFTCONV_SPEC_W | FFTCONV_SPEC_G;
     if ((p->valid & need) != need) return FFTCONV_ENOTREADY;
+    if (p->d.f > 4) return launch_pair_contract(p, pass, ws, stream);
     SharedPassArgs a{};
     unsigned char *out = reinterpret_cast<unsigned char *>(slot_ptr(p, ws, FFTCONV_SPEC_OUT));
     a.G = slot_ptr(p, ws, FFTCONV_SPEC_G);
@@ -390,18 +426,8 @@ int launch_contract(fftconv_plan_t p, int pass, void *ws, hipStream_t stream)
     if (p->d.f <= 4 && pass != FFTCONV_FPROP && !p->sw.no_skinny) return launch_skinny(p, pass, ws, stream);
     const GemmEntry &e = gemm_kernel_table()[p->gemm_tile[pass]];
     GemmArgs g;
-    g.A = slot_ptr(p, ws, sa);
-    g.B = slot_ptr(p, ws, sb);
     const int sc = result_slot(p, pass);
-    g.C = slot_ptr(p, ws, sc);
-    g.Md = Md; g.Nd = Nd; g.Kd = Kd;
-    g.bins = p->B;
-    g.tiles_m = (Md + e.MT - 1) / e.MT;
-    g.tiles_n = (Nd + e.NT - 1) / e.NT;
-    g.xcd_remap = p->sw.no_xcd_remap ? 0 : 1;
-    const long lim = 1L << 28;   // complex elements in 2 GB
-    g.full_tiles_ok =
-        ((long)Md * Kd < lim && (long)Nd * Kd < lim && (long)Md * Nd < lim && !p->sw.no_full_tiles) ? 1 : 0;
+    fill_gemm_args(p, pass, e, ws, slot_ptr(p, ws, sc), g);
     const long blocks = (long)g.bins * g.tiles_m * g.tiles_n;
     if (blocks <= 0 || blocks > 0x7fffffffL) return FFTCONV_EUNSUPPORTED;
     if (int rc = allow_lds(p, e.pass[pass], e.lds_bytes)) return rc;
@@ -653,6 +679,18 @@ int fftconv_plan2d(fftconv_plan_t *out, const fftconv_desc2d *d)
     p->maps_g = (long)d->S * d->fo * T;
     p->maps_g2 = (long)d->S * d->fo * T2;
     p->maps_out = out_y > out_dx ? (out_y > maps_w ? out_y : maps_w) : (out_dx > maps_w ? out_dx : maps_w);
+    // bprop and accGrad of a layer whose two passes read the same transforms of dL/dy (untiled, or tiled with
+    // overlap-add) form both of their result spectra in one launch, side by side in the OUT slot: dXh at
+    // its start, dWh behind it (256-byte aligned, hence the spare map)
+    const bool one_g = !lean && (L == 0 || overlap_add);
+    // The joint launch of the matrix-core contractions pays when both result spectra then wait in the 256 MB
+    // memory-side cache for their inverse transforms; beyond that the second transform reads a spectrum that
+    // has been pushed out meanwhile and loses what the launch gained.  Measured, step with / without it:
+    // S = 128, f = f' = 256, n = 16 (102 MB of dXh + dWh) 0.290 / 0.296 ms; f = 256, f' = 384, n = 16 (136 MB)
+    // 0.397 / 0.402; f = 96, f' = 256, n = 32 (151 MB) 0.493 / 0.497; f = f' = 256, n = 32 (540 MB) 0.993 / 0.984.
+    const bool pair_fits_cache = (double)(out_dx + maps_w) * 8.0 * (N * N / 2 + 2) <= 192.0 * 1024 * 1024;
+    const bool pair_ok = one_g && d->f > 4 && pair_fits_cache;
+    if (pair_ok && out_dx + maps_w + 1 <= lim && p->maps_out < out_dx + maps_w + 1) p->maps_out = out_dx + maps_w + 1;
     const size_t per_map = (size_t)8 * p->B;
     p->off_x = 0;
     p->off_w = p->off_x + align_up(per_map * maps_x);
@@ -677,8 +715,8 @@ int fftconv_plan2d(fftconv_plan_t *out, const fftconv_desc2d *d)
         p->off_shared_dw = align_up(rows * d->f * p->B * sizeof(cf));
         p->off_shared_part = p->off_shared_dw + dw_bytes;
         const size_t need = p->off_shared_part + (p->shared_row_groups > 1 ? (size_t)p->shared_row_groups * dw_bytes : 0);
-        p->shared_pass_ok = !lean && (L == 0 || overlap_add) && d->f <= 4 && p->maps_out > 0 &&
-                            need <= (size_t)p->maps_out * p->B * sizeof(cf);
+        const size_t room = p->maps_out > 0 ? (size_t)p->maps_out * p->B * sizeof(cf) : 0;
+        p->shared_pass_ok = d->f <= 4 ? (one_g && need <= room) : (pair_ok && p->off_shared_part <= room);
     }
     p->last_ws = nullptr;
     p->profiling = 0;
@@ -689,6 +727,20 @@ int fftconv_plan2d(fftconv_plan_t *out, const fftconv_desc2d *d)
         int Md, Nd, Kd, sa, sb;
         pass_dims(p, pass, Md, Nd, Kd, sa, sb);
         p->gemm_tile[pass] = choose_gemm_tile(Md, Nd, p->sw);
+    }
+    {   // one tile shape for both products of the joint bprop + accGrad launch: least padded work over the two
+        int Mb, Nb, Kb, Ma, Na, Ka, sa, sb;
+        pass_dims(p, FFTCONV_BPROP, Mb, Nb, Kb, sa, sb);
+        pass_dims(p, FFTCONV_ACCGRAD, Ma, Na, Ka, sa, sb);
+        p->pair_tile = 0;
+        double best_work = -1.0;
+        for (int i = 0; i < gemm_shape_count(); ++i) {
+            const GemmEntry &e = gemm_kernel_table()[i];
+            const auto padded = [&](int M, int Nn) { return (double)((M + e.MT - 1) / e.MT) * e.MT * ((Nn + e.NT - 1) / e.NT) * e.NT; };
+            const double work = padded(Mb, Nb) * Kb + padded(Ma, Na) * Ka;
+            if (best_work < 0.0 || work < best_work) { best_work = work; p->pair_tile = i; }
+        }
+        if (p->sw.gemm_tile >= 0) p->pair_tile = p->sw.gemm_tile;
     }
     *out = p;
     return FFTCONV_OK;

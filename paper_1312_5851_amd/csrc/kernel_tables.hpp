@@ -11,6 +11,7 @@ namespace fftconv {
 typedef void (*FwdKernel)(FwdArgs);
 typedef void (*InvKernel)(InvArgs);
 typedef void (*GemmKernel)(GemmArgs);
+typedef void (*GemmPairKernel)(GemmPairArgs);
 typedef void (*SkinnyKernel)(SkinnyArgs);
 typedef void (*SharedPassKernel)(SharedPassArgs);
 typedef void (*SumGroupsKernel)(const cf *, cf *, size_t, int);
@@ -45,6 +46,7 @@ InvKernel fused_inverse_kernel(int N, int T, int NX, int F, bool tiled);
 struct GemmEntry {
     int MT, NT, waves, occ, threads, lds_bytes;
     GemmKernel pass[3];   // indexed by FFTCONV_FPROP / BPROP / ACCGRAD
+    GemmPairKernel bprop_accgrad;   // both of their products in one launch
 };
 // Entries i and i + gemm_shape_count() have the same shape (the second half keeps two register
 // sets of operand chunks in flight).

@@ -433,11 +433,17 @@ def test_few_input_maps_both_contraction_paths(fc, layer, monkeypatch):
 @pytest.mark.parametrize("layer", [wl.Layer("shared_f3", 70, 3, 70, 20, 5, 0.1, 110), wl.Layer("shared_f4_rows", 200, 4, 33, 12, 3, 0.1, 111),
                                    wl.Layer("shared_f1", 5, 1, 130, 30, 7, 0.1, 112),
                                    wl.Layer("shared_f3_rows300", 300, 3, 33, 12, 3, 0.1, 124),     # two row groups per bin
-                                   wl.Layer("shared_tiled_rows", 70, 2, 9, 70, 5, 0.1, 125)],      # tiled, overlap-add
+                                   wl.Layer("shared_tiled_rows", 70, 2, 9, 70, 5, 0.1, 125),       # tiled, overlap-add
+                                   # more than four input maps: both matrix-core contractions in one launch
+                                   wl.Layer("pair_f8", 20, 8, 70, 20, 5, 0.1, 126),
+                                   wl.Layer("pair_tails", 130, 65, 97, 16, 3, 0.05, 127),          # every dimension one past a tile multiple
+                                   wl.Layer("pair_f5_fo3", 9, 5, 3, 12, 5, 0.1, 128),              # dX's spectrum larger than dW's
+                                   wl.Layer("pair_tiled", 3, 6, 17, 100, 5, 0.1, 129)],            # tiled, overlap-add
                          ids=lambda l: l.name)
 def test_bprop_and_accgrad_share_one_pass_over_the_gradient_spectrum(fc, layer):
-    """With f <= 4 and all three spectra cached, whichever of bprop / accGrad runs first forms both
-    result spectra and leaves the other's for it.  Every order of calls, and every change of an
+    """With all three spectra cached, whichever of bprop / accGrad runs first forms both result spectra
+    (f <= 4: one streaming kernel; more input maps: both matrix-core contractions in one launch) and
+    leaves the other's for it.  Every order of calls, and every change of an
     operand in between, must give the oracle's results."""
     print(f"\ncase {layer}", flush=True)
     x, w, g = wl.make_inputs(layer)
