@@ -40,8 +40,14 @@ constexpr int maps_per_block(int N) { return N <= 8 ? 64 : (N <= 20 ? 32 : 16); 
 // LDS hand-overs between the two phases: two from N = 40 up, where one would not fit the
 // 160 KB of LDS or would leave room for a single workgroup per CU.  (At N = 32 two rounds
 // let four workgroups share a CU instead of two; inside the full step that measured the same
-// as one round, so N = 32 keeps the simpler single round.)
+// as one round, so N = 32 keeps the simpler single round.  The narrow extent classes of
+// N >= 40, whose hand-over would fit one round, measured no better with one: forward of 5 x 5
+// kernels at N = 64 234 against 238 us, the inverse to 5 x 5 at N = 48 and 56 a quarter and a tenth
+// slower, so every class of a size keeps the same two-team schedule.)
 constexpr int rounds_for(int N) { return N >= 40 ? 2 : 1; }
+
+template <int N, int T, int NX>
+using Geom = TileGeom<N, T, NX, rounds_for(N)>;
 
 // Smallest compiled extent class that covers `ext` columns of an N-point transform.
 inline int extent_class(int N, int ext)

@@ -26,12 +26,12 @@ struct FusedEntry {
 template <int N, int T, int NX>
 constexpr InvKernel tiled_kernel()
 {
-    if constexpr (NX == N && N >= 16) return ifft2d_c2r_tiled_kernel<TileGeom<N, T, NX, rounds_for(N)>, F>;
+    if constexpr (NX == N && N >= 16) return ifft2d_c2r_tiled_kernel<Geom<N, T, NX>, F>;
     else return nullptr;
 }
 
 #define X(n_, t_, nx_) \
-    {n_, t_, nx_, ifft2d_c2r_crop_kernel<TileGeom<n_, t_, nx_, rounds_for(n_)>, false, F>, tiled_kernel<n_, t_, nx_>()},
+    {n_, t_, nx_, ifft2d_c2r_crop_kernel<Geom<n_, t_, nx_>, false, F>, tiled_kernel<n_, t_, nx_>()},
 const FusedEntry kFusedTable[] = {FFTCONV_FOR_EACH_GEOM(X)};
 #undef X
 

@@ -9,13 +9,13 @@ namespace {
 template <int N, int T, int NX>
 constexpr FwdKernel tiled_fwd_kernel()
 {
-    if constexpr (NX == N && N >= 16) return fft2d_r2c_kernel<TileGeom<N, T, NX, rounds_for(N)>, true>;
+    if constexpr (NX == N && N >= 16) return fft2d_r2c_kernel<Geom<N, T, NX>, true>;
     else return nullptr;
 }
 
 #define X(n_, t_, nx_)                                                                                              \
-    {n_, t_, nx_, TileGeom<n_, t_, nx_, rounds_for(n_)>::THREADS, TileGeom<n_, t_, nx_, rounds_for(n_)>::LDS_BYTES, \
-     fft2d_r2c_kernel<TileGeom<n_, t_, nx_, rounds_for(n_)>>, tiled_fwd_kernel<n_, t_, nx_>()},
+    {n_, t_, nx_, Geom<n_, t_, nx_>::THREADS, Geom<n_, t_, nx_>::LDS_BYTES, \
+     fft2d_r2c_kernel<Geom<n_, t_, nx_>>, tiled_fwd_kernel<n_, t_, nx_>()},
 const FwdEntry kFwdTable[] = {FFTCONV_FOR_EACH_GEOM(X)};
 #undef X
 

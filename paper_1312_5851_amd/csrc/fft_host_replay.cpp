@@ -98,7 +98,7 @@ int replay_fft2d_r2c(int N, const float *src, float *spec, int M, int ext_y, int
     a.flip = flip;
     const int T = maps_per_block(N), NX = extent_class(N, ext_y > ext_x ? ext_y : ext_x);
 #define X(n_, t_, nx_) \
-    if (N == n_ && T == t_ && NX == nx_) { replay_forward<TileGeom<n_, t_, nx_, rounds_for(n_)>>(a); return 0; }
+    if (N == n_ && T == t_ && NX == nx_) { replay_forward<Geom<n_, t_, nx_>>(a); return 0; }
     FFTCONV_FOR_EACH_GEOM(X)
 #undef X
     return 1;
@@ -112,7 +112,7 @@ int replay_ifft2d_c2r_crop(int N, const float *spec, float *dst, int M, int crop
     a.bin_stride = M;
     const int T = maps_per_block(N), NX = extent_class(N, crop_y > crop_x ? crop_y : crop_x);
 #define X(n_, t_, nx_) \
-    if (N == n_ && T == t_ && NX == nx_) { replay_inverse<TileGeom<n_, t_, nx_, rounds_for(n_)>>(a, accumulate != 0); return 0; }
+    if (N == n_ && T == t_ && NX == nx_) { replay_inverse<Geom<n_, t_, nx_>>(a, accumulate != 0); return 0; }
     FFTCONV_FOR_EACH_GEOM(X)
 #undef X
     return 1;
@@ -133,7 +133,7 @@ int replay_fft2d_r2c_tiled(int N, const float *src, float *spec, int M, int ext_
     FwdArgs a{src, reinterpret_cast<cf *>(spec), M, ext_y, ext_x, {H, W, C, tiles_x, tiles, step_y, step_x, org_y, org_x, by_class}};
     const int T = maps_per_block(N);
 #define X(n_, t_, nx_) \
-    if (N == n_ && T == t_ && n_ == nx_) { replay_forward<TileGeom<n_, t_, nx_, rounds_for(n_)>, true>(a); return 0; }
+    if (N == n_ && T == t_ && n_ == nx_) { replay_forward<Geom<n_, t_, nx_>, true>(a); return 0; }
     FFTCONV_FOR_EACH_GEOM(X)
 #undef X
     return 1;
@@ -159,7 +159,7 @@ int replay_ifft2d_c2r_tiled(int N, const float *spec, float *dst, int M, int cro
     }
     const int T = maps_per_block(N);
 #define X(n_, t_, nx_) \
-    if constexpr (n_ == nx_) { if (N == n_ && T == t_) { replay_inverse<TileGeom<n_, t_, nx_, rounds_for(n_)>, true>(a, false); return 0; } }
+    if constexpr (n_ == nx_) { if (N == n_ && T == t_) { replay_inverse<Geom<n_, t_, nx_>, true>(a, false); return 0; } }
     FFTCONV_FOR_EACH_GEOM(X)
 #undef X
     return 1;
@@ -180,7 +180,7 @@ int replay_ifft2d_c2r_crop_fused3(int N, const float *xs, const float *wsp, floa
     a.fo = fo; a.Mx = Mx; a.Mw = Mw;
     const int T = maps_per_block(N);
 #define X(n_, t_, nx_) \
-    if constexpr (n_ == nx_) { if (N == n_ && T == t_) { replay_inverse<TileGeom<n_, t_, nx_, rounds_for(n_)>, false, 3>(a, false); return 0; } }
+    if constexpr (n_ == nx_) { if (N == n_ && T == t_) { replay_inverse<Geom<n_, t_, nx_>, false, 3>(a, false); return 0; } }
     FFTCONV_FOR_EACH_GEOM(X)
 #undef X
     return 1;

@@ -8,9 +8,9 @@ namespace fftconv {
 namespace {
 
 #define X(n_, t_, nx_)                                                                                              \
-    {n_, t_, nx_, TileGeom<n_, t_, nx_, rounds_for(n_)>::THREADS, TileGeom<n_, t_, nx_, rounds_for(n_)>::LDS_BYTES, \
-     ifft2d_c2r_crop_kernel<TileGeom<n_, t_, nx_, rounds_for(n_)>, false>,                                          \
-     ifft2d_c2r_crop_kernel<TileGeom<n_, t_, nx_, rounds_for(n_)>, true>},
+    {n_, t_, nx_, Geom<n_, t_, nx_>::THREADS, Geom<n_, t_, nx_>::LDS_BYTES, \
+     ifft2d_c2r_crop_kernel<Geom<n_, t_, nx_>, false>,                                          \
+     ifft2d_c2r_crop_kernel<Geom<n_, t_, nx_>, true>},
 const InvEntry kInvTable[] = {FFTCONV_FOR_EACH_GEOM(X)};
 #undef X
 

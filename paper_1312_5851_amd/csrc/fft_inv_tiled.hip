@@ -10,7 +10,7 @@ namespace {
 template <int N, int T, int NX, bool ADD>
 constexpr InvKernel tiled_inv_kernel()
 {
-    if constexpr (NX == N && N >= 16) return ifft2d_c2r_tiled_kernel<TileGeom<N, T, NX, rounds_for(N)>, 0, ADD>;
+    if constexpr (NX == N && N >= 16) return ifft2d_c2r_tiled_kernel<Geom<N, T, NX>, 0, ADD>;
     else return nullptr;
 }
 
