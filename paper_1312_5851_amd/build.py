@@ -24,6 +24,7 @@ HIP_UNITS = [
     ("fft_fwd.hip", [], "fft_fwd.o"),
     ("contract.hip", [], "contract.o"),
     ("fft_inv_tiled.hip", [], "fft_inv_tiled.o"),
+    ("fft_inv_quad.hip", [], "fft_inv_quad.o"),
     ("skinny.hip", [], "skinny.o"),
     ("fftconv.hip", [], "fftconv.o"),
 ]

@@ -8,6 +8,7 @@
 #include <vector>
 
 #include "fft_dispatch.hpp"
+#include "fft_quad_kernels.hpp"
 
 using namespace fftconv;
 
@@ -85,7 +86,69 @@ static void replay_inverse(const InvArgs &a, bool acc)
     }
 }
 
+// The quad-split inverse: the cross-lane sums of a quad, two DPP adds on the device, are formed here from the
+// four lanes' stored partial results in the same order, (a + b) + (c + d).
+template <class G>
+static void quad_sums(const std::vector<std::array<cf, G::M>> &part, int tid, cf (&out)[G::M])
+{
+    const int q0 = tid & ~3, q = tid & 3;
+    for (int i = 0; i < G::M; ++i) {
+        // lane q: (own + neighbour) + (the other pair's sum), each pair's sum formed the same way
+        const cf own = part[q0 + q][i], nb = part[q0 + (q ^ 1)][i];
+        const cf oa = part[q0 + (q ^ 2)][i], ob = part[q0 + (q ^ 3)][i];
+        out[i] = (own + nb) + (oa + ob);
+    }
+}
+
+template <class G>
+static void replay_inverse_quad(const InvArgs &a, bool acc)
+{
+    std::vector<cf> lds(G::LDS_ELEMS);
+    std::vector<std::array<cf, G::M>> part(G::THREADS);
+    const int blocks = (a.M + G::T - 1) / G::T;
+    for (int blk = 0; blk < blocks; ++blk) {
+        std::memset(lds.data(), 0xFF, sizeof(cf) * lds.size());
+        for (int round = 0; round < G::ROUNDS; ++round) {
+            for (int tid = 0; tid < G::THREADS; ++tid) {
+                cf v[G::M];
+                quad_inv_x_load<G>(tid, blk, round, a, v);
+                quad_inv_x_partial<G>(tid, v, reinterpret_cast<cf(&)[G::M]>(*part[tid].data()));
+            }
+            for (int tid = 0; tid < G::THREADS; ++tid) {
+                cf u[G::M];
+                quad_sums<G>(part, tid, u);
+                quad_inv_x_write<G>(tid, round, lds.data(), u);
+            }
+        }
+        for (int tid = 0; tid < G::YITEMS; ++tid)
+            quad_inv_y_partial<G>(tid, lds.data(), reinterpret_cast<cf(&)[G::M]>(*part[tid].data()));
+        for (int tid = 0; tid < G::YITEMS; ++tid) {
+            cf z[G::M];
+            quad_sums<G>(part, tid, z);
+            if (acc) quad_inv_y_store<G, true>(tid, blk, a, z);
+            else quad_inv_y_store<G, false>(tid, blk, a, z);
+        }
+    }
+}
+
 extern "C" {
+
+// Inverse + crop of the extent class N / 4 (crop <= N / 4) with each transform split over four lanes; N in 40, 48, 56, 64.
+int replay_ifft2d_c2r_crop_quad(int N, const float *spec, float *dst, int M, int crop_y, int crop_x, int accumulate, int flip)
+{
+    InvArgs a{reinterpret_cast<const cf *>(spec), dst, M, crop_y, crop_x, 1.0f / (float)(N * N)};
+    a.flip = flip;
+    a.parity = -1;
+    a.bin_stride = M;
+    if (crop_y > N / 4 || crop_x > N / 4) return 2;
+    switch (N) {
+        case 40: replay_inverse_quad<QuadGeom<40, maps_per_block(40)>>(a, accumulate != 0); return 0;
+        case 48: replay_inverse_quad<QuadGeom<48, maps_per_block(48)>>(a, accumulate != 0); return 0;
+        case 56: replay_inverse_quad<QuadGeom<56, maps_per_block(56)>>(a, accumulate != 0); return 0;
+        case 64: replay_inverse_quad<QuadGeom<64, maps_per_block(64)>>(a, accumulate != 0); return 0;
+        default: return 1;
+    }
+}
 
 int replay_fft_size(int n) { return fft_size_for(n); }
 int replay_extent_class(int N, int ext) { return extent_class(N, ext); }

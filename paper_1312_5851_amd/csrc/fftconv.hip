@@ -61,7 +61,7 @@ bool find_fft(int N, int ext, FftEntry &e)
 // Switches for measurements and tests, read from the environment once, when a plan is made.
 struct Switches {
     int gemm_tile;   // forced tile shape of the contraction, or -1
-    bool no_xcd_remap, no_full_tiles, no_skinny, no_shared_pass, no_fused, no_fused_order;
+    bool no_xcd_remap, no_full_tiles, no_skinny, no_shared_pass, no_fused, no_fused_order, quad;
 };
 
 Switches read_switches()
@@ -78,6 +78,7 @@ Switches read_switches()
     sw.no_shared_pass = std::getenv("FFTCONV_NO_SHARED_PASS") != nullptr;
     sw.no_fused = std::getenv("FFTCONV_NO_FUSED") != nullptr;
     sw.no_fused_order = std::getenv("FFTCONV_NO_FUSED_ORDER") != nullptr;
+    sw.quad = std::getenv("FFTCONV_QUAD") != nullptr;
     return sw;
 }
 
@@ -484,6 +485,15 @@ int launch_inverse(fftconv_plan_t p, int pass, float *dst, void *ws, hipStream_t
         a.wsp = slot_ptr(p, ws, FFTCONV_SPEC_W);
         a.fo = d.fo; a.Mx = (int)p->maps_x; a.Mw = (int)p->maps_w;
         a.groups_per_sample = p->sw.no_fused_order ? 0 : d.fo / e->T;
+    }
+    // on request (it measured slower, see fft_quad_kernels.hpp): small windows (the extent class N / 4) of the
+    // sizes from 40 up with every 1-D transform split over four lanes
+    if (!use_tiles && !fused && p->sw.quad && e->NX * 4 == e->N) {
+        if (const InvQuadEntry *qe = find_inv_quad_kernels(e->N)) {
+            kernel = accumulate ? qe->acc : qe->plain;
+            e->threads = qe->threads;
+            e->lds_bytes = qe->lds_bytes;
+        }
     }
     if (int rc = allow_lds(p, kernel, e->lds_bytes)) return rc;
     a.spec = reinterpret_cast<const cf *>(reinterpret_cast<const unsigned char *>(slot_ptr(p, ws, result_slot(p, pass))) +

@@ -1,5 +1,5 @@
 // The compiled kernels, grouped in tables that the host code searches.  Each table lives in a
-// translation unit of its own (fft_fwd.hip, fft_inv.hip, fft_inv_tiled.hip, fft_fused.hip once
+// translation unit of its own (fft_fwd.hip, fft_inv.hip, fft_inv_quad.hip, fft_inv_tiled.hip, fft_fused.hip once
 // per number of input maps, contract.hip, skinny.hip) so that the library's parts compile side
 // by side; the host code in fftconv.hip instantiates no kernel itself.
 #pragma once
@@ -32,7 +32,15 @@ struct InvTiledEntry {
     InvKernel tiled, tiled_add;   // each window written once / overlapping windows added
 };
 
+// Inverse transforms of the extent class N / 4 with every 1-D transform split over four lanes
+// (fft_quad_kernels.hpp); N >= 40 only.
+struct InvQuadEntry {
+    int N, T, threads, lds_bytes;
+    InvKernel plain, acc;
+};
+
 const FwdEntry *find_fwd_kernels(int N, int T, int NX);
+const InvQuadEntry *find_inv_quad_kernels(int N);   // nullptr if N has none
 const InvEntry *find_inv_kernels(int N, int T, int NX);
 const InvTiledEntry *find_inv_tiled_kernels(int N, int T, int NX);
 

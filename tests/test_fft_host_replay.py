@@ -96,6 +96,35 @@ def test_inverse_crops_scales_and_accumulates(replay, N):
             assert np.abs(acc - (base + full[:, :crop, :crop])).max() < 3e-6
 
 
+@pytest.mark.parametrize("N", [40, 48, 56, 64])
+def test_quad_split_inverse_for_small_windows(replay, N):
+    """The inverse for windows of at most N/4 x N/4 with every 1-D transform split over four lanes
+    (partial transforms of N/4 points, twiddled, summed across the quad): same results as the
+    one-lane-per-transform kernel, for square and rectangular crops, ragged map counts, accumulating
+    and flipped stores."""
+    rng = np.random.default_rng(700 + N)
+    T = replay.replay_maps_per_block(N)
+    for crop in (1, 3, 5, (2, N // 4), (N // 4, 1), N // 4):
+        cy, cx = crop if isinstance(crop, tuple) else (crop, crop)
+        for M in (1, 2, T + 3):
+            full = rng.uniform(-1, 1, (M, N, N))
+            spec = reference_spectrum(full, N)
+            s = np.ascontiguousarray(np.stack([spec.real, spec.imag], -1).astype(np.float32))
+            for flip in (0, 1):
+                want = full[:, :cy, :cx][:, ::-1, ::-1] if flip else full[:, :cy, :cx]
+                dst = np.full((M, cy, cx), np.nan, np.float32)
+                assert replay.replay_ifft2d_c2r_crop_quad(N, s.ctypes.data_as(FP), dst.ctypes.data_as(FP), M, cy, cx, 0, flip) == 0
+                assert np.abs(dst - want).max() < 3e-6, (N, crop, M, flip)
+                base = rng.uniform(-1, 1, (M, cy, cx)).astype(np.float32)
+                acc = base.copy()
+                assert replay.replay_ifft2d_c2r_crop_quad(N, s.ctypes.data_as(FP), acc.ctypes.data_as(FP), M, cy, cx, 1, flip) == 0
+                assert np.abs(acc - (base + want)).max() < 3e-6
+                ref = inverse(replay, spec, N, (cy, cx), flip=flip)
+                assert np.abs(dst - ref).max() < 2e-6
+    big = np.zeros((1, N // 4 + 1, 1), np.float32)
+    assert replay.replay_ifft2d_c2r_crop_quad(N, s.ctypes.data_as(FP), big.ctypes.data_as(FP), 1, N // 4 + 1, 1, 0, 0) == 2
+
+
 @pytest.mark.parametrize("N", [16, 20, 24, 28])
 def test_impulse_constant_and_round_trip(replay, N):
     imp = np.zeros((3, N, N), np.float32); imp[:, 0, 0] = 1

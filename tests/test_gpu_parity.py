@@ -503,6 +503,35 @@ def test_true_convolution_flag(fc, dims):
         check(dw2.cpu().numpy(), 2 * ref, f"true conv accgrad accumulate flags={flags}")
 
 
+@pytest.mark.parametrize("dims", [(3, 5, 7, 64, 64, 11, 11), (2, 19, 3, 50, 60, 7, 16), (4, 3, 35, 41, 44, 1, 12),
+                                  (2, 6, 5, 40, 33, 10, 3), (5, 4, 4, 56, 56, 14, 14)], ids=lambda d: "x".join(map(str, d)))
+def test_kernel_gradient_inverse_split_over_lane_quads(fc, dims, monkeypatch):
+    """Kernels of at most N/4 x N/4 on transforms of 40 points and up: with FFTCONV_QUAD set, the inverse
+    transform of dL/dw splits every 1-D transform over four lanes (partial transforms summed across the quad
+    by DPP adds; off by default because it measured slower).  Against the oracle and against the
+    one-lane-per-transform kernel; overwriting, accumulating and with the rotated store of the
+    true-convolution reading."""
+    S, f, fo, nh, nw, kh, kw = dims
+    print(f"\ncase quad {dims}", flush=True)
+    x, w, g = rect_inputs(800 + nh + kw, *dims)
+    xd, wd, gd = dev(x), dev(w), dev(g)
+    for flags in (0, fc.TRUE_CONV):
+        ref = direct.accgrad(g, x, (kh, kw), true_conv=bool(flags))
+        one_lane = fc.Plan(S, f, fo, (nh, nw), (kh, kw), flags=flags).accgrad(gd, xd)
+        monkeypatch.setenv("FFTCONV_QUAD", "1")
+        plan = fc.Plan(S, f, fo, (nh, nw), (kh, kw), flags=flags)
+        monkeypatch.delenv("FFTCONV_QUAD")
+        assert plan.fft_size >= 40 and 4 * max(kh, kw) <= plan.fft_size
+        dw = plan.accgrad(gd, xd)
+        dw2 = plan.accgrad(gd, xd, dw.clone(), accumulate=True)
+        torch.cuda.synchronize()
+        assert not torch.equal(dw, one_lane), "the two kernels round differently: identical bits mean the switch did nothing"
+        check(dw.cpu().numpy(), ref, f"quad accgrad flags={flags}")
+        check(dw2.cpu().numpy(), 2 * ref, f"quad accgrad accumulating flags={flags}")
+        check(one_lane.cpu().numpy(), ref, f"one lane per transform, flags={flags}")
+        assert not torch.equal(dw, torch.zeros_like(dw))
+
+
 def test_transposed_layer_gives_transposed_results(fc):
     """Swapping height and width of every tensor swaps them in every result (bitwise is not
     expected: the two axes are transformed in different phases)."""
