@@ -348,9 +348,31 @@ def write_report(args):
         r.pop("roofline", None)
         recs.append(r)
     json.dump(recs, open(args.report + ".json", "w"), indent=1)
+    open(args.report + ".md", "w").write(render_report(layers, recs))
+
+
+def render_report(layers, recs):
+    """The per-layer table of write_report as markdown."""
+    head = ("# All layers: BASELINE configs, n x k sweep, paper-table columns, speed-figure axes, tiled layers (one MI355X)\n\n"
+            "Command: `python bench.py --report gpurun_out/report` (per layer: per-pass times, memory-efficient mode, stage table, "
+            "then 3 warm-up and 20 timed steps, i.e. the order of the default bench line).  \"no-cache step\" is the same step in the "
+            "memory-efficient mode (plan flag RECOMPUTE: every pass transforms its operands again, three-slot workspace).  "
+            "bprop and accGrad are timed in alternation: with all spectra cached the first of the two also forms the other's result "
+            "spectrum, so their warm times belong together (accGrad's is then the inverse transform alone).  Stage percentages use HIP "
+            "events recorded around every launch, on algorithmic bytes / flops against 8 TB/s and 157.3 TFLOP/s; the events read 2-3 us "
+            "above rocprofv3's kernel durations, which matters for the 10-20 us transform launches of N <= 16 (rocprofv3 durations: "
+            "hot_path_*.md).  Contraction: the first column is matrix-core utilisation in the sense of flops issued (6 per complex "
+            "multiply-add: three real products), the second prices the same launches at the 8 flops of the textbook complex "
+            "multiply-add and can pass 100; with more than four input maps and both result spectra under 192 MiB, bprop's launch forms "
+            "accGrad's product too (one figure for both, `-` for accGrad); for layers with f = 3 the contractions of bprop and accGrad "
+            "are one streaming kernel bound by HBM (its matrix-core percentage says nothing) and fprop has no contraction launch "
+            "(`-`): its products are formed inside the inverse transform, whose percentage then counts the output bytes and the small "
+            "operand spectra only.  `large_*` layers (n > 64) run on overlapping tiles; their transform percentages count image bytes "
+            "once plus one spectrum per tile.\n\n")
     lines = ["| layer | S,f,f',n,k | step ms | no-cache step ms | direct-equiv TFLOP/s (step) | fprop warm/cold ms | bprop warm/cold ms | "
-             "accGrad warm/cold ms | FFT stages % of 8 TB/s (x,w,g / y,dx,dw) | contraction % of 157.3 TFLOP/s (algorithmic) |",
-             "|---|---|---|---|---|---|---|---|---|---|"]
+             "accGrad warm/cold ms | FFT stages % of 8 TB/s (x,w,g / y,dx,dw) | contraction, % of 157.3 TFLOP/s on issued flops "
+             "(fprop,bprop,accGrad) | the same on algorithmic flops |",
+             "|---|---|---|---|---|---|---|---|---|---|---|"]
     for layer, r in zip(layers, recs):
         st, ps = r["stages"], r["passes"]
         pct = lambda n: f"{100 * st[n].get('frac_hbm_peak', st[n].get('frac_mfma_peak', 0)):.0f}" if n in st else "-"
@@ -361,9 +383,7 @@ def write_report(args):
                      f" | {pct('fft_x')},{pct('fft_w')},{pct('fft_g')} / {pct('ifft_y')},{pct('ifft_dx')},{pct('ifft_dw')} | "
                      f"{iss('cgemm_fprop')},{iss('cgemm_bprop')},{iss('cgemm_accgrad')} | "
                      f"{pct('cgemm_fprop')},{pct('cgemm_bprop')},{pct('cgemm_accgrad')} |")
-    head = ("Stage figures here use HIP events recorded around every launch (they read 2-3 us above rocprofv3's kernel "
-            "durations on the 10-20 us transform launches; the rocprofv3 durations are in the hot_path_*.md files).\n\n")
-    open(args.report + ".md", "w").write(head + "\n".join(lines) + "\n")
+    return head + "\n".join(lines) + "\n"
 
 
 def main():
