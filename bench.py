@@ -246,9 +246,10 @@ def measure(layer, args, inputs=None):
         tpath = os.path.join(ROOT, "profiles", f"traffic_{layer.name}.json")
         if os.path.exists(tpath):
             traffic = json.load(open(tpath)).get("cgemm_hbm_bytes_per_launch")
-        rocprof_us = None
+        rocprof_us, rocprof_products = None, 1.0
         if os.path.exists(tpath):
             rocprof_us = json.load(open(tpath)).get("cgemm_rocprof_avg_us")
+            rocprof_products = json.load(open(tpath)).get("cgemm_products_per_launch", 1.0)
         roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                     "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": traffic,
                     # the same launches priced three ways: algorithmic flops (8 per complex multiply-add, the
@@ -260,7 +261,7 @@ def measure(layer, args, inputs=None):
                     "clock": "HIP events recorded on the launch stream around each contraction launch (includes "
                              "dispatch latency; reads a few us above rocprofv3's kernel duration)",
                     "rocprof_avg_launch_us": rocprof_us,
-                    "frac_issued_rocprof": (per_launch * plan.contraction_flops / (rocprof_us * 1e-6) / 1e12 / PEAK_FP32_MFMA_TFLOPS
+                    "frac_issued_rocprof": (rocprof_products * plan.contraction_flops / (rocprof_us * 1e-6) / 1e12 / PEAK_FP32_MFMA_TFLOPS
                                             if rocprof_us else None),
                     "launches": {n: {"avg_ms": gemm_live[n], "products": products[n]} for n in timed},
                     "kernel": ("bin_cgemm_kernel (fprop) and bin_cgemm_bprop_accgrad_kernel (both other products in one launch)"
