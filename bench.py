@@ -355,7 +355,7 @@ def write_report(args):
 def render_report(layers, recs):
     """The per-layer table of write_report as markdown."""
     head = ("# All layers: BASELINE configs, n x k sweep, paper-table columns, speed-figure axes, tiled layers (one MI355X)\n\n"
-            "Command: `python bench.py --report gpurun_out/report` (per layer: per-pass times, memory-efficient mode, stage table, "
+            "Command: `python bench.py --report PATH` (per layer: per-pass times, memory-efficient mode, stage table, "
             "then 3 warm-up and 20 timed steps, i.e. the order of the default bench line).  \"no-cache step\" is the same step in the "
             "memory-efficient mode (plan flag RECOMPUTE: every pass transforms its operands again, three-slot workspace).  "
             "bprop and accGrad are timed in alternation: with all spectra cached the first of the two also forms the other's result "
