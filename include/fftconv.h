@@ -41,7 +41,9 @@
  * transform (which needs fo to be a multiple of the 16 to 64 maps a workgroup transforms),
  * FFTCONV_NO_FUSED_ORDER keeps that kernel's plain block order; FFTCONV_QUAD makes the inverse transform of
  * dL/dw for kernels of at most N/4 x N/4 on transforms of 40 points and up split every 1-D transform over four
- * lanes with cross-lane (DPP) sums, a variant that measured slower than the default;
+ * lanes with cross-lane (DPP) sums, a variant that measured slower than the default; FFTCONV_NO_SMALL_BATCH keeps
+ * the usual 16 to 64 maps per workgroup of the transform kernels for launches of few maps too (such launches
+ * otherwise run with 2 to 16 maps per workgroup, which spreads them over more CUs);
  * FFTCONV_NO_OVERLAP_ADD keeps the second transform of dL/dy for bprop of tiled layers,
  * FFTCONV_TILE_SIZE=N forces the transform size of the tiles, FFTCONV_OVERLAP_ADD_RATIO=r
  * moves the choice of overlap-add to f * r <= fo.

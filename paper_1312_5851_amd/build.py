@@ -21,6 +21,8 @@ HIP_UNITS = [
     ("fft_fused.hip", ["-DFFTCONV_FUSED_F=2"], "fft_fused_f2.o"),
     ("fft_fused.hip", ["-DFFTCONV_FUSED_F=1"], "fft_fused_f1.o"),
     ("fft_inv.hip", [], "fft_inv.o"),
+    ("fft_inv_small.hip", [], "fft_inv_small.o"),
+    ("fft_fwd_small.hip", [], "fft_fwd_small.o"),
     ("fft_fwd.hip", [], "fft_fwd.o"),
     ("contract.hip", [], "contract.o"),
     ("fft_inv_tiled.hip", [], "fft_inv_tiled.o"),

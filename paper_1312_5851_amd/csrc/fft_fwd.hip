@@ -9,7 +9,7 @@ namespace {
 template <int N, int T, int NX>
 constexpr FwdKernel tiled_fwd_kernel()
 {
-    if constexpr (NX == N && N >= 16) return fft2d_r2c_kernel<Geom<N, T, NX>, true>;
+    if constexpr (NX == N && N >= 16 && T == maps_per_block(N)) return fft2d_r2c_kernel<Geom<N, T, NX>, true>;
     else return nullptr;
 }
 
@@ -25,7 +25,7 @@ const FwdEntry *find_fwd_kernels(int N, int T, int NX)
 {
     for (const FwdEntry &e : kFwdTable)
         if (e.N == N && e.T == T && e.NX == NX) return &e;
-    return nullptr;
+    return find_fwd_kernels_small(N, T, NX);
 }
 
 }  // namespace fftconv

@@ -181,6 +181,35 @@ int replay_ifft2d_c2r_crop(int N, const float *spec, float *dst, int M, int crop
     return 1;
 }
 
+// The same two with the few-maps-per-workgroup geometries that launches of few maps take.
+int replay_small_maps_per_block(int N) { return small_maps_per_block(N); }
+
+int replay_fft2d_r2c_small(int N, const float *src, float *spec, int M, int ext_y, int ext_x, int flip)
+{
+    FwdArgs a{src, reinterpret_cast<cf *>(spec), M, ext_y, ext_x};
+    a.flip = flip;
+    const int T = small_maps_per_block(N), NX = extent_class(N, ext_y > ext_x ? ext_y : ext_x);
+#define X(n_, t_, nx_) \
+    if (N == n_ && T == t_ && NX == nx_) { replay_forward<Geom<n_, t_, nx_>>(a); return 0; }
+    FFTCONV_FOR_EACH_SMALL_GEOM(X)
+#undef X
+    return 1;
+}
+
+int replay_ifft2d_c2r_crop_small(int N, const float *spec, float *dst, int M, int crop_y, int crop_x, int accumulate, int flip)
+{
+    InvArgs a{reinterpret_cast<const cf *>(spec), dst, M, crop_y, crop_x, 1.0f / (float)(N * N)};
+    a.flip = flip;
+    a.parity = -1;
+    a.bin_stride = M;
+    const int T = small_maps_per_block(N), NX = extent_class(N, crop_y > crop_x ? crop_y : crop_x);
+#define X(n_, t_, nx_) \
+    if (N == n_ && T == t_ && NX == nx_) { replay_inverse<Geom<n_, t_, nx_>>(a, accumulate != 0); return 0; }
+    FFTCONV_FOR_EACH_SMALL_GEOM(X)
+#undef X
+    return 1;
+}
+
 // Row and column of tile t under either numbering (for the tests' expected values).
 void replay_tile_row_col(int t, int tiles_x, int tiles, int by_class, int *ty, int *tx)
 {

@@ -20,7 +20,7 @@ const InvEntry *find_inv_kernels(int N, int T, int NX)
 {
     for (const InvEntry &e : kInvTable)
         if (e.N == N && e.T == T && e.NX == NX) return &e;
-    return nullptr;
+    return find_inv_kernels_small(N, T, NX);
 }
 
 }  // namespace fftconv

@@ -46,9 +46,11 @@ struct FftEntry {
     InvKernel inv, inv_acc, inv_tiled, inv_tiled_add;
 };
 
-bool find_fft(int N, int ext, FftEntry &e)
+// `maps`: transforms in the launch, or 0 for a launch that must use the usual maps per workgroup (tiled and
+// fused kernels exist for those only).
+bool find_fft(int N, int ext, long maps, FftEntry &e)
 {
-    const int T = maps_per_block(N), NX = extent_class(N, ext);
+    const int T = maps > 0 ? maps_per_block_for(N, maps, true) : maps_per_block(N), NX = extent_class(N, ext);
     const FwdEntry *f = find_fwd_kernels(N, T, NX);
     const InvEntry *i = find_inv_kernels(N, T, NX);
     if (!f || !i) return false;
@@ -61,7 +63,7 @@ bool find_fft(int N, int ext, FftEntry &e)
 // Switches for measurements and tests, read from the environment once, when a plan is made.
 struct Switches {
     int gemm_tile;   // forced tile shape of the contraction, or -1
-    bool no_xcd_remap, no_full_tiles, no_skinny, no_shared_pass, no_fused, no_fused_order, quad;
+    bool no_xcd_remap, no_full_tiles, no_skinny, no_shared_pass, no_fused, no_fused_order, quad, no_small_batch;
 };
 
 Switches read_switches()
@@ -79,6 +81,7 @@ Switches read_switches()
     sw.no_fused = std::getenv("FFTCONV_NO_FUSED") != nullptr;
     sw.no_fused_order = std::getenv("FFTCONV_NO_FUSED_ORDER") != nullptr;
     sw.quad = std::getenv("FFTCONV_QUAD") != nullptr;
+    sw.no_small_batch = std::getenv("FFTCONV_NO_SMALL_BATCH") != nullptr;
     return sw;
 }
 
@@ -277,7 +280,8 @@ int launch_forward(fftconv_plan_t p, int slot, const float *src, void *ws, hipSt
     }
     const bool use_tiles = tiled(p) && slot != FFTCONV_SPEC_W;
     FftEntry entry, *e = &entry;
-    if (!find_fft(p->N, use_tiles ? p->N : (ext_y > ext_x ? ext_y : ext_x), entry) || (use_tiles && !e->fwd_tiled))
+    if (!find_fft(p->N, use_tiles ? p->N : (ext_y > ext_x ? ext_y : ext_x), use_tiles || p->sw.no_small_batch ? 0 : M, entry) ||
+        (use_tiles && !e->fwd_tiled))
         return FFTCONV_EUNSUPPORTED;
     FwdKernel kernel = use_tiles ? e->fwd_tiled : e->fwd;
     if (int rc = allow_lds(p, kernel, e->lds_bytes)) return rc;
@@ -472,7 +476,9 @@ int launch_inverse(fftconv_plan_t p, int pass, float *dst, void *ws, hipStream_t
     }
     const bool use_tiles = tiled(p) && pass != FFTCONV_ACCGRAD;
     FftEntry entry, *e = &entry;
-    if (!find_fft(p->N, use_tiles ? p->N : (a.crop_y > a.crop_x ? a.crop_y : a.crop_x), entry) || (use_tiles && !e->inv_tiled))
+    if (!find_fft(p->N, use_tiles ? p->N : (a.crop_y > a.crop_x ? a.crop_y : a.crop_x),
+                  use_tiles || fused || p->sw.no_small_batch ? 0 : M, entry) ||
+        (use_tiles && !e->inv_tiled))
         return FFTCONV_EUNSUPPORTED;
     // the tiled kernels either write every window once or add overlapping windows of a cleared dx:
     // neither adds to what the caller's tensor held
@@ -491,6 +497,7 @@ int launch_inverse(fftconv_plan_t p, int pass, float *dst, void *ws, hipStream_t
     if (!use_tiles && !fused && p->sw.quad && e->NX * 4 == e->N) {
         if (const InvQuadEntry *qe = find_inv_quad_kernels(e->N)) {
             kernel = accumulate ? qe->acc : qe->plain;
+            e->T = qe->T;
             e->threads = qe->threads;
             e->lds_bytes = qe->lds_bytes;
         }
@@ -559,7 +566,7 @@ InvKernel fused_fprop_kernel(fftconv_plan_t p, int pass, int accumulate)
     const int crop_y = use_tiles ? p->Ly : p->noh, crop_x = use_tiles ? p->Lx : p->now;
     FftEntry entry, *e = &entry;
     // the maps of a workgroup must share a sample, whose part of the x spectrum must fit the LDS buffer
-    if (!find_fft(p->N, use_tiles ? p->N : (crop_y > crop_x ? crop_y : crop_x), entry) || p->d.fo % e->T != 0 || (long)p->B * p->d.f * 8 > e->lds_bytes) return nullptr;
+    if (!find_fft(p->N, use_tiles ? p->N : (crop_y > crop_x ? crop_y : crop_x), 0, entry) || p->d.fo % e->T != 0 || (long)p->B * p->d.f * 8 > e->lds_bytes) return nullptr;
     return fused_inverse_kernel(e->N, e->T, e->NX, p->d.f, use_tiles);
 }
 

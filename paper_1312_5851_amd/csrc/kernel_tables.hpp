@@ -39,7 +39,9 @@ struct InvQuadEntry {
     InvKernel plain, acc;
 };
 
-const FwdEntry *find_fwd_kernels(int N, int T, int NX);
+const FwdEntry *find_fwd_kernels(int N, int T, int NX);        // either list of geometries
+const FwdEntry *find_fwd_kernels_small(int N, int T, int NX);  // few maps per workgroup (fft_fwd_small.hip)
+const InvEntry *find_inv_kernels_small(int N, int T, int NX);  // (fft_inv_small.hip)
 const InvQuadEntry *find_inv_quad_kernels(int N);   // nullptr if N has none
 const InvEntry *find_inv_kernels(int N, int T, int NX);
 const InvTiledEntry *find_inv_tiled_kernels(int N, int T, int NX);

@@ -96,6 +96,34 @@ def test_inverse_crops_scales_and_accumulates(replay, N):
             assert np.abs(acc - (base + full[:, :crop, :crop])).max() < 3e-6
 
 
+@pytest.mark.parametrize("N", SIZES)
+def test_small_batch_geometries(replay, N):
+    """The geometries with few maps per workgroup (one or two waves; launches of few maps take them): forward
+    and inverse, every extent class, ragged map counts, flipped loads and accumulating stores."""
+    rng = np.random.default_rng(900 + N)
+    T = replay.replay_small_maps_per_block(N)
+    assert T * N // 2 >= 48 and T < replay.replay_maps_per_block(N)
+    B = N * N // 2 + 2
+    for ext in sorted({1, N // 4, N // 4 + 1, N // 2 + 1, N}):
+        for M in (1, T + 1, 3 * T):
+            src = rng.uniform(-1, 1, (M, ext, ext)).astype(np.float32)
+            for flip in (0, 1):
+                spec = np.full((B, M, 2), np.nan, np.float32)
+                assert replay.replay_fft2d_r2c_small(N, src.ctypes.data_as(FP), spec.ctypes.data_as(FP), M, ext, ext, flip) == 0
+                got = spec[..., 0].astype(np.float64) + 1j * spec[..., 1]
+                ref = reference_spectrum(src[:, ::-1, ::-1] if flip else src, N)
+                assert np.abs(got - ref).max() <= 3e-6 * max(np.abs(ref).max(), 1), (N, ext, M, flip)
+            full = rng.uniform(-1, 1, (M, N, N))
+            sp = reference_spectrum(full, N)
+            s = np.ascontiguousarray(np.stack([sp.real, sp.imag], -1).astype(np.float32))
+            base = rng.uniform(-1, 1, (M, ext, ext)).astype(np.float32)
+            for acc in (0, 1):
+                dst = base.copy() if acc else np.full((M, ext, ext), np.nan, np.float32)
+                assert replay.replay_ifft2d_c2r_crop_small(N, s.ctypes.data_as(FP), dst.ctypes.data_as(FP), M, ext, ext, acc, 0) == 0
+                want = full[:, :ext, :ext] + (base if acc else 0)
+                assert np.abs(dst - want).max() < 3e-6, (N, ext, M, acc)
+
+
 @pytest.mark.parametrize("N", [40, 48, 56, 64])
 def test_quad_split_inverse_for_small_windows(replay, N):
     """The inverse for windows of at most N/4 x N/4 with every 1-D transform split over four lanes
