@@ -480,7 +480,7 @@ int launch_inverse(fftconv_plan_t p, int pass, float *dst, void *ws, hipStream_t
                   use_tiles || fused || p->sw.no_small_batch ? 0 : M, entry) ||
         (use_tiles && !e->inv_tiled))
         return FFTCONV_EUNSUPPORTED;
-    // the tiled kernels either write every window once or add overlapping windows of a cleared dx:
+    // the tiled kernels either write every window once or assemble dx from overlapping windows:
     // neither adds to what the caller's tensor held
     if (use_tiles && accumulate) return FFTCONV_EUNSUPPORTED;
     InvKernel kernel = use_tiles ? (a.add ? e->inv_tiled_add : e->inv_tiled) : (accumulate ? e->inv_acc : e->inv);
