@@ -168,9 +168,13 @@ struct GemmTile {
     static constexpr int STAGE = kKT * (SA + SB);       // complex elements of one chunk (A then B)
     static constexpr int LDS_BYTES = 2 * STAGE * 8;     // two chunks
     static constexpr int ACC_REGS = 3 * IT * JT * 16;
-    // waves per SIMD the register allocation must allow (the accumulators alone take ACC_REGS of 512)
-    static constexpr int WAVES_PER_SIMD =
+    // waves per SIMD the register allocation must allow (the accumulators alone take ACC_REGS of 512), and no
+    // more than LDS lets a CU hold anyway: a 128 x 32 tile takes 41.5 KB, so three workgroups of four waves
+    // share a CU and a wave may use 168 registers instead of spilling at 128
+    static constexpr int BY_LDS = (160 * 1024 / LDS_BYTES) * (WM * WN) / 4;
+    static constexpr int BY_REGS =
         SETS > 1 ? 3 : (ACC_REGS <= 48 ? (WM * WN >= 4 ? 4 : 3) : (ACC_REGS <= 96 ? 2 : 1));
+    static constexpr int WAVES_PER_SIMD = BY_LDS >= 1 && BY_LDS < BY_REGS ? BY_LDS : BY_REGS;
 };
 
 // The K loop of one tile.  la / lb are the two operands' loaders (general or full-tile), one per
