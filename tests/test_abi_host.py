@@ -287,3 +287,11 @@ def test_workloads_are_seeded_and_shaped():
     assert all(1 <= l.k <= l.n <= 64 for l in every)
     u = wl.sample_units(100, 10, 3)
     assert len(set(u.tolist())) == 10 and np.array_equal(u, wl.sample_units(100, 10, 3))
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """Every box has one GPU: bench.py --gpus N with N > 1 exits with a message before touching a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
