@@ -295,3 +295,12 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/fftconv.h is a C interface: it compiles as C99 with warnings as errors."""
+    import subprocess
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "fftconv.h"\nint main(void) { fftconv_desc d = {1, 1, 1, 8, 3, 0}; return d.S - 1 + (int)(FFTCONV_STATIC_SCRATCH_BYTES == 0); }\n')
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only",
+                    "-I", os.path.join(ROOT, "include"), str(src)], check=True)
