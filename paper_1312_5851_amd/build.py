@@ -8,6 +8,7 @@ from __future__ import annotations
 import os
 import subprocess
 import sys
+import time
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
@@ -79,9 +80,13 @@ def build_library(force: bool = True, extra_flags=(), only_units=None) -> str:
                     continue
                 cmd = [hipcc, *HIPCC_FLAGS, *defines, *extra_flags, "-I", INCLUDE, "-c", "-o", obj, os.path.join(CSRC, src)]
                 running.append((cmd, subprocess.Popen(cmd)))
-            if running:
-                cmd, proc = running.pop(0)
-                if proc.wait() != 0:
+            if running:   # free the slot of whichever compile ends first
+                done = [i for i, (_, proc) in enumerate(running) if proc.poll() is not None]
+                if not done:
+                    time.sleep(0.2)
+                    continue
+                cmd, proc = running.pop(done[0])
+                if proc.returncode != 0:
                     failed.append(cmd)
         if failed:
             raise subprocess.CalledProcessError(1, failed[0])
